@@ -1,0 +1,62 @@
+"""Independent reference routines used to pin the oracle.
+
+Nothing here looks at pages: attention is computed on contiguous arrays, by a
+different formulation (vectorised numpy, and torch's fp64 SDPA) from the
+oracle's scalar C loops.  The paged images the oracle reads are built by
+`build_paged_pool`, which places every bf16 element individually from the
+statement of the layout (token-major, kv-head-major, K then V), one Python
+integer computation per element.
+"""
+import numpy as np
+
+
+def bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    return (np.asarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def f32_to_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bits, round to nearest even (test-local copy; used only to make exact inputs)."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def contiguous_attention(q_bits, k_bits, v_bits, scale):
+    """q [Q,d], k/v [n,H,d] as bf16 bits -> fp64 [Q,d]; query head a uses kv head a // (Q//H)."""
+    q, k, v = bits_to_f64(q_bits), bits_to_f64(k_bits), bits_to_f64(v_bits)
+    Q, d = q.shape
+    n, H, _ = k.shape
+    G = Q // H
+    out = np.zeros((Q, d))
+    for a in range(Q):
+        h = a // G
+        s = (k[:, h, :] @ q[a]) * scale           # [n]
+        w = np.exp(s - s.max())
+        w /= w.sum()
+        out[a] = w @ v[:, h, :]
+    return out
+
+
+def torch_sdpa_attention(q_bits, k_bits, v_bits, scale):
+    import torch
+    q = torch.from_numpy(bits_to_f64(q_bits))                       # [Q,d]
+    k = torch.from_numpy(bits_to_f64(k_bits)).permute(1, 0, 2)      # [H,n,d]
+    v = torch.from_numpy(bits_to_f64(v_bits)).permute(1, 0, 2)
+    G = q.shape[0] // k.shape[0]
+    k = k.repeat_interleave(G, dim=0)
+    v = v.repeat_interleave(G, dim=0)
+    o = torch.nn.functional.scaled_dot_product_attention(q[None, :, None, :], k[None], v[None], scale=scale)
+    return o[0, :, 0, :].numpy()
+
+
+def build_paged_pool(pool_u16, page_bytes, table, k_bits, v_bits, first_token=0):
+    """Place K/V [n,H,d] into the pool image element by element."""
+    n, H, d = k_bits.shape
+    for t in range(n):
+        for h in range(H):
+            for which, src in ((0, k_bits), (1, v_bits)):
+                for j in range(d):
+                    stream_byte = ((first_token + t) * H + h) * (4 * d) + which * 2 * d + 2 * j
+                    page = int(table[stream_byte // page_bytes])
+                    assert page >= 0
+                    byte = page * page_bytes + stream_byte % page_bytes
+                    pool_u16[byte // 2] = src[t, h, j]
