@@ -1,0 +1,183 @@
+/*
+ * ukv.h -- C ABI of the unified key-value cache decode path for MI355X (gfx950).
+ *
+ * The operations are the data-parallel steps behind the unified KV cache of SeaLLM
+ * (arXiv 2504.15720, section 4.4 "Unified KV Cache" and the unified block manager of
+ * section 5): several co-located LLM services share ONE pool of equal-sized blocks
+ * ("pages", the paper's merged cache blocks); each request owns a block table that maps
+ * its logical blocks to physical pages, and a second index locates data inside a page.
+ *
+ * Layout (all services, one attention layer per table).  A request's cache is a byte
+ * stream: token-major, then kv-head-major, then K[head_dim] followed by V[head_dim] in
+ * bf16.  One such K|V pair is a head-row of R = 4*head_dim bytes; a token occupies
+ * T = n_kv_heads*R bytes (= n_kv_heads*head_dim*2*sizeof(bf16)).  Stream byte s lives in
+ * physical page  page_table[table_off + s / page_bytes]  at in-page offset
+ * s % page_bytes (the second index; it is derived, not stored).  page_bytes must be a
+ * multiple of every service's R, so a head-row never straddles pages; token rows may.
+ * A request of n tokens owns ceil(n*T/page_bytes) pages.
+ *
+ * Conventions.
+ *   - Every function returns UKV_OK (0) or a negative error code and never throws.
+ *     ukv_last_error() gives a human-readable detail for the calling thread's last failure.
+ *   - "HOST" pointers are read on the CPU during the call and may be reused on return.
+ *     "DEVICE" pointers are HIP device memory owned by the caller and must stay valid
+ *     until the work enqueued on `stream` has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work and return without synchronising.  One pool must be driven from one stream at
+ *     a time: calls on the same pool share staging and scratch buffers.
+ *   - The library never allocates or frees the pool memory itself.  It owns its host
+ *     object, the free list, pinned staging buffers and a small device scratch.
+ *   - There is no CPU fallback: without a usable HIP device the compute calls fail with
+ *     UKV_EHIP.
+ */
+#ifndef UKV_H
+#define UKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define UKV_OK 0
+#define UKV_EINVAL (-1) /* bad argument, unsupported shape, bad page id, double free */
+#define UKV_ENOMEM (-2) /* free list exhausted (state unchanged) or host allocation failed */
+#define UKV_ENOSPC (-3) /* caller-provided workspace or output array too small */
+#define UKV_EHIP (-4)   /* a HIP runtime call failed */
+
+#define UKV_MAX_SERVICES 16
+
+typedef struct ukv_pool ukv_pool_t; /* opaque host object */
+
+/* One co-located service, reduced to the shape of one attention layer.
+ * Supported: head_dim in {64, 128}; n_q_heads = G * n_kv_heads with G in {1, 2, 4, 8}.
+ * scale == 0 selects 1/sqrt(head_dim). */
+typedef struct {
+    uint32_t n_q_heads;
+    uint32_t n_kv_heads;
+    uint32_t head_dim;
+    float scale;
+} ukv_service_t;
+
+/* base: DEVICE, page_bytes-aligned start of the pool; bytes: its size (a whole number of
+ * pages is used).  page_bytes: power of two, >= 1024, multiple of every service's R. */
+typedef struct {
+    void *base;
+    uint64_t bytes;
+    uint32_t page_bytes;
+    uint32_t n_services;
+    const ukv_service_t *services; /* HOST [n_services] */
+} ukv_pool_desc_t;
+
+typedef struct {
+    uint32_t n_q_heads, n_kv_heads, head_dim, group;
+    uint32_t head_row_bytes; /* R */
+    uint32_t token_bytes;    /* T */
+    float scale;
+    uint32_t heads_per_slice; /* kv heads one workgroup covers */
+    uint32_t n_slices;        /* n_kv_heads / heads_per_slice */
+    uint32_t token_lanes;     /* tokens a workgroup reads per iteration */
+    uint64_t n_pages;
+    uint64_t free_pages;
+} ukv_service_info_t;
+
+/* Unified block manager (section 5: "calculate proper block shape, and manage the cache
+ * blocks"): validates the services against the page size and builds a LIFO free list that
+ * first hands out pages 0, 1, 2, ...  No device work. */
+int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out);
+int ukv_pool_destroy(ukv_pool_t *pool);
+int ukv_pool_info(const ukv_pool_t *pool, uint32_t service, ukv_service_info_t *out);
+
+/* ceil(n_tokens * T / page_bytes) for the service; 0 on a bad argument. */
+uint64_t ukv_pages_for_tokens(const ukv_pool_t *pool, uint32_t service, uint64_t n_tokens);
+
+/* Pop n page ids (LIFO) into out_ids HOST [n].  UKV_ENOMEM leaves the free list unchanged. */
+int ukv_pages_alloc(ukv_pool_t *pool, uint32_t n, int32_t *out_ids);
+/* Push n page ids back, in order.  Out-of-range or already-free ids: UKV_EINVAL, list unchanged. */
+int ukv_pages_free(ukv_pool_t *pool, uint32_t n, const int32_t *ids);
+
+/* Mixed-service batch descriptor (structure of arrays).  Requests of different services may
+ * be mixed freely; the paper's same-service batch (section 4.2) is the case of one service. */
+typedef struct {
+    uint32_t n_requests;
+    const uint32_t *service_id; /* HOST [n] */
+    const uint32_t *ctx_len;    /* HOST [n] tokens valid for attention (new token included) */
+    const uint64_t *table_off;  /* HOST [n] entry offset of each request's table in page_table */
+    int32_t *page_table;        /* DEVICE concatenated int32 page ids */
+    const void *q;              /* DEVICE bf16, [n_q_heads][head_dim] per request */
+    const uint64_t *q_off;      /* HOST [n] element offsets into q (multiples of 8) */
+    void *out;                  /* DEVICE fp32, [n_q_heads][head_dim] per request */
+    const uint64_t *out_off;    /* HOST [n] element offsets into out (multiples of 4) */
+    const void *new_k;          /* DEVICE bf16 [n_kv_heads][head_dim] per request (append only) */
+    const void *new_v;          /* DEVICE bf16, same layout (append only) */
+    const uint64_t *new_off;    /* HOST [n] element offsets into new_k/new_v (multiples of 8) */
+    uint32_t n_patches;         /* page-table entries to write before appending (may be 0) */
+    const uint64_t *patch_entry; /* HOST [n_patches] entry index into page_table */
+    const int32_t *patch_page;   /* HOST [n_patches] page id to store there */
+} ukv_batch_t;
+
+/* Store side of the cache (section 4.4: storing a step's KV pairs into merged blocks).
+ * First writes the n_patches table entries, then copies request i's new K/V to token index
+ * ctx_len[i]-1 of its stream, bit for bit.  Requests with ctx_len == 0 are skipped.  Uses
+ * service_id, ctx_len, table_off, page_table, new_k, new_v, new_off and the patch arrays. */
+int ukv_append(ukv_pool_t *pool, const ukv_batch_t *batch, void *stream);
+
+/* Upper bound of the workspace ukv_decode_attention needs for ANY batch of at most
+ * n_requests requests of this pool's services, under the current tunables. */
+size_t ukv_decode_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests);
+
+/* Decode phase (section 2.1: one new token per request attends to all cached KV pairs),
+ * reading K/V through the block tables of the unified cache (section 4.4):
+ *   out[i][a][:] = sum_t softmax_t(scale * q[i][a] . K[t][a/G]) * V[t][a/G],  t < ctx_len[i],
+ * fp32 accumulation over bf16 inputs, fp32 output; ctx_len == 0 gives zeros.  Bytes of the
+ * pool past ctx_len never influence the result.  The batch is cut into token ranges that
+ * run as one split-KV launch over all services plus a merge launch.
+ * workspace: DEVICE, 256-byte aligned, ws_bytes >= ukv_decode_workspace_bytes(); else UKV_ENOSPC.
+ * Uses service_id, ctx_len, table_off, page_table, q, q_off, out, out_off. */
+int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes,
+                         void *stream);
+
+/* Test hook: copy tokens [0, ctx_len[i]) of every request out of the pool into contiguous
+ * k_out / v_out DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i] (HOST). */
+int ukv_gather(ukv_pool_t *pool, const ukv_batch_t *batch, void *k_out, void *v_out, const uint64_t *kv_off,
+               void *stream);
+
+/* Host-only view of the split-KV plan for a batch (no device work): how the launch would be cut. */
+typedef struct {
+    uint32_t n_seqs;        /* (request, head-slice) sequences */
+    uint32_t n_items;       /* (sequence, token range) work items */
+    uint32_t n_spans;       /* workgroups of the decode launch */
+    uint32_t n_reduce;      /* sequences merged by the second launch */
+    uint64_t partial_floats; /* fp32 values of split partials */
+    uint64_t plan_bytes;     /* bytes copied to the device per call */
+    uint64_t kv_bytes;       /* sum ctx_len * T: algorithmic KV bytes of the step */
+} ukv_plan_info_t;
+/* items_out (HOST, may be NULL): n_items_cap rows of {request, first kv head, n kv heads, t0, t1, span}. */
+int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_info_t *info,
+                    uint32_t *items_out, uint32_t n_items_cap);
+
+/* Tunables (integers).  Setting one never changes results beyond fp32 summation order. */
+#define UKV_PARAM_MAX_SPANS 1        /* upper limit of decode workgroups per launch */
+#define UKV_PARAM_MIN_SPAN_BYTES 2   /* do not cut spans smaller than this many KV bytes */
+#define UKV_PARAM_BLOCK_THREADS 3    /* 256 or 512 */
+#define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
+#define UKV_PARAM_PROFILE 5          /* 1 = time kernels with HIP events (see ukv_profile_read) */
+int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
+int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
+
+/* Kernel times collected while UKV_PARAM_PROFILE is 1 (HIP events on the caller's stream).
+ * Reading waits for the recorded events and resets the accumulators. */
+typedef struct {
+    uint32_t n_decode, n_reduce, n_append;
+    double decode_ms, reduce_ms, append_ms; /* sums over the launches */
+} ukv_profile_t;
+int ukv_profile_read(ukv_pool_t *pool, ukv_profile_t *out);
+
+const char *ukv_strerror(int code);
+const char *ukv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UKV_H */

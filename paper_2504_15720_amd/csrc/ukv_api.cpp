@@ -1,0 +1,404 @@
+// C-ABI entry points that enqueue device work: append, decode attention, gather.
+// Host side only marshals: it plans, stages the plan in pinned memory, copies it with one
+// asynchronous transfer and launches the kernels on the caller's stream.
+#include <algorithm>
+#include <cstring>
+
+#include "ukv_internal.h"
+
+using namespace ukv;
+
+namespace {
+
+int hip_fail(hipError_t e, const char *what) {
+    set_error(std::string(what) + ": " + hipGetErrorString(e));
+    return UKV_EHIP;
+}
+#define HIP_TRY(expr, what)                                                                                        \
+    do {                                                                                                           \
+        hipError_t e_ = (expr);                                                                                    \
+        if (e_ != hipSuccess)                                                                                      \
+            return hip_fail(e_, what);                                                                             \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Pinned staging ring: a slot is reused only after the copy that read it has completed.
+int stage_acquire(ukv_pool *p, size_t bytes, ukv_pool::Stage **out) {
+    ukv_pool::Stage &st = p->stage[p->next_stage];
+    p->next_stage = (p->next_stage + 1) % ukv_pool::kStages;
+    if (!st.ev)
+        HIP_TRY(hipEventCreateWithFlags(&st.ev, hipEventDisableTiming), "hipEventCreate");
+    if (st.pending) {
+        HIP_TRY(hipEventSynchronize(st.ev), "hipEventSynchronize(staging)");
+        st.pending = false;
+    }
+    if (st.cap < bytes) {
+        if (st.host)
+            HIP_TRY(hipHostFree(st.host), "hipHostFree");
+        st.host = nullptr;
+        st.cap = 0;
+        const size_t cap = std::max<size_t>(align_up(bytes * 2, 4096), 64 * 1024);
+        HIP_TRY(hipHostMalloc(&st.host, cap, hipHostMallocDefault), "hipHostMalloc");
+        st.cap = cap;
+    }
+    *out = &st;
+    return UKV_OK;
+}
+
+int stage_submit(ukv_pool::Stage *st, void *dst, size_t bytes, hipStream_t s) {
+    HIP_TRY(hipMemcpyAsync(dst, st->host, bytes, hipMemcpyHostToDevice, s), "hipMemcpyAsync(plan)");
+    HIP_TRY(hipEventRecord(st->ev, s), "hipEventRecord(staging)");
+    st->pending = true;
+    return UKV_OK;
+}
+
+int scratch_reserve(ukv_pool *p, size_t bytes, hipStream_t s) {
+    if (p->dev_scratch_cap >= bytes)
+        return UKV_OK;
+    if (p->dev_scratch) {
+        HIP_TRY(hipStreamSynchronize(s), "hipStreamSynchronize");
+        HIP_TRY(hipFree(p->dev_scratch), "hipFree");
+        p->dev_scratch = nullptr;
+        p->dev_scratch_cap = 0;
+    }
+    const size_t cap = std::max<size_t>(align_up(bytes * 2, 4096), 256 * 1024);
+    HIP_TRY(hipMalloc(&p->dev_scratch, cap), "hipMalloc(scratch)");
+    p->dev_scratch_cap = cap;
+    return UKV_OK;
+}
+
+// Profiling: a pair of events around one kernel launch.
+struct ProfScope {
+    ukv_pool *p;
+    hipStream_t s;
+    int which;
+    ukv_pool::EvPair ev{};
+    bool on = false;
+    int begin() {
+        if (!p->tun.profile)
+            return UKV_OK;
+        if (!p->ev_free.empty()) {
+            ev = p->ev_free.back();
+            p->ev_free.pop_back();
+        } else {
+            HIP_TRY(hipEventCreate(&ev.a), "hipEventCreate");
+            HIP_TRY(hipEventCreate(&ev.b), "hipEventCreate");
+        }
+        ev.which = which;
+        HIP_TRY(hipEventRecord(ev.a, s), "hipEventRecord");
+        on = true;
+        return UKV_OK;
+    }
+    int end() {
+        if (!on)
+            return UKV_OK;
+        HIP_TRY(hipEventRecord(ev.b, s), "hipEventRecord");
+        p->ev_used.push_back(ev);
+        return UKV_OK;
+    }
+};
+
+struct BlobLayout {
+    size_t classes, seqs, items, spans, reduce, total;
+};
+
+BlobLayout blob_layout(size_t n_seqs, size_t n_items, size_t n_spans, size_t n_reduce) {
+    BlobLayout b{};
+    size_t o = 0;
+    b.classes = o;
+    o = align_up(o + sizeof(ClassTable));
+    b.seqs = o;
+    o = align_up(o + n_seqs * sizeof(SeqRec));
+    b.items = o;
+    o = align_up(o + n_items * sizeof(Item));
+    b.spans = o;
+    o = align_up(o + (n_spans + 1) * sizeof(uint32_t));
+    b.reduce = o;
+    o = align_up(o + n_reduce * sizeof(ReduceRec));
+    b.total = o;
+    return b;
+}
+
+size_t max_slices(const ukv_pool *p) {
+    size_t m = 1;
+    for (uint32_t s = 0; s < p->n_services; ++s)
+        m = std::max<size_t>(m, p->classes.c[s].n_kv / p->classes.c[s].hs);
+    return m;
+}
+
+size_t blob_capacity(const ukv_pool *p, uint32_t n_requests) {
+    const size_t n_seqs = (size_t)n_requests * max_slices(p);
+    const size_t n_spans = (size_t)(2 * p->tun.max_spans + 2);
+    return blob_layout(n_seqs, n_seqs + n_spans, n_spans, n_seqs).total;
+}
+
+} // namespace
+
+extern "C" {
+
+size_t ukv_decode_workspace_bytes(const ukv_pool_t *p, uint32_t n_requests) {
+    if (!p)
+        return 0;
+    return blob_capacity(p, n_requests) + align_up(max_partial_floats(p, n_requests) * sizeof(float));
+}
+
+int ukv_plan_decode(const ukv_pool_t *p, const ukv_batch_t *b, ukv_plan_info_t *info, uint32_t *items_out,
+                    uint32_t n_items_cap) {
+    if (!p || !b || !info) {
+        set_error("null argument");
+        return UKV_EINVAL;
+    }
+    Plan plan;
+    int rc = build_plan(p, b, plan);
+    if (rc != UKV_OK)
+        return rc;
+    info->n_seqs = (uint32_t)plan.seqs.size();
+    info->n_items = (uint32_t)plan.items.size();
+    info->n_spans = (uint32_t)plan.span_first.size() - 1;
+    info->n_reduce = (uint32_t)plan.reduce.size();
+    info->partial_floats = plan.partial_floats;
+    info->plan_bytes = blob_layout(plan.seqs.size(), plan.items.size(), info->n_spans, plan.reduce.size()).total;
+    info->kv_bytes = plan.kv_bytes;
+    if (items_out) {
+        // request index of each sequence: sequences are emitted request by request
+        std::vector<uint32_t> seq_req(plan.seqs.size());
+        uint32_t k = 0;
+        for (uint32_t i = 0; i < b->n_requests; ++i) {
+            const ClassRec &c = p->classes.c[b->service_id[i]];
+            for (uint32_t h0 = 0; h0 < c.n_kv; h0 += c.hs)
+                seq_req[k++] = i;
+        }
+        const uint32_t n = std::min<uint32_t>(n_items_cap, info->n_items);
+        for (uint32_t it = 0; it < n; ++it) {
+            const Item &x = plan.items[it];
+            const SeqRec &s = plan.seqs[x.seq];
+            uint32_t *row = items_out + (size_t)it * 6;
+            row[0] = seq_req[x.seq];
+            row[1] = s.head0;
+            row[2] = p->classes.c[s.cls].hs;
+            row[3] = x.t0;
+            row[4] = x.t1;
+            row[5] = plan.item_span[it];
+        }
+    }
+    return UKV_OK;
+}
+
+int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream) {
+    if (!p || !b) {
+        set_error("null pool or batch");
+        return UKV_EINVAL;
+    }
+    if (b->n_requests == 0)
+        return UKV_OK;
+    if (!b->page_table || !b->q || !b->out) {
+        set_error("page_table, q and out must be non-null device pointers");
+        return UKV_EINVAL;
+    }
+    if (!workspace || ((uintptr_t)workspace & 255)) {
+        set_error("workspace must be non-null and 256-byte aligned");
+        return UKV_EINVAL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    Plan plan;
+    int rc = build_plan(p, b, plan);
+    if (rc != UKV_OK)
+        return rc;
+    const uint32_t n_spans = (uint32_t)plan.span_first.size() - 1;
+    const BlobLayout L = blob_layout(plan.seqs.size(), plan.items.size(), n_spans, plan.reduce.size());
+    const size_t part_off = align_up(L.total);
+    if (part_off + plan.partial_floats * sizeof(float) > ws_bytes) {
+        set_error("workspace too small for this batch");
+        return UKV_ENOSPC;
+    }
+    ukv_pool::Stage *st = nullptr;
+    rc = stage_acquire(p, L.total, &st);
+    if (rc != UKV_OK)
+        return rc;
+    unsigned char *h = (unsigned char *)st->host;
+    std::memcpy(h + L.classes, &p->classes, sizeof(ClassTable));
+    std::memcpy(h + L.seqs, plan.seqs.data(), plan.seqs.size() * sizeof(SeqRec));
+    std::memcpy(h + L.items, plan.items.data(), plan.items.size() * sizeof(Item));
+    std::memcpy(h + L.spans, plan.span_first.data(), plan.span_first.size() * sizeof(uint32_t));
+    if (!plan.reduce.empty())
+        std::memcpy(h + L.reduce, plan.reduce.data(), plan.reduce.size() * sizeof(ReduceRec));
+    rc = stage_submit(st, workspace, L.total, s);
+    if (rc != UKV_OK)
+        return rc;
+
+    unsigned char *w = (unsigned char *)workspace;
+    DecodeArgs a{};
+    a.pool_base = p->base;
+    a.log2_page = p->log2_page;
+    a.page_table = b->page_table;
+    a.q = b->q;
+    a.out = (float *)b->out;
+    a.classes = (const ClassRec *)(w + L.classes);
+    a.seqs = (const SeqRec *)(w + L.seqs);
+    a.items = (const Item *)(w + L.items);
+    a.span_first = (const uint32_t *)(w + L.spans);
+    a.partials = (float *)(w + part_off);
+
+    {
+        ProfScope ps{p, s, 0};
+        if ((rc = ps.begin()) != UKV_OK)
+            return rc;
+        HIP_TRY(launch_decode(a, n_spans, (uint32_t)p->tun.block_threads, s), "launch decode kernel");
+        if ((rc = ps.end()) != UKV_OK)
+            return rc;
+    }
+    if (!plan.reduce.empty()) {
+        ProfScope ps{p, s, 1};
+        if ((rc = ps.begin()) != UKV_OK)
+            return rc;
+        HIP_TRY(launch_reduce((const ReduceRec *)(w + L.reduce), (uint32_t)plan.reduce.size(),
+                              plan.max_reduce_heads, a.partials, a.out, s),
+                "launch reduce kernel");
+        if ((rc = ps.end()) != UKV_OK)
+            return rc;
+    }
+    return UKV_OK;
+}
+
+int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
+    if (!p || !b) {
+        set_error("null pool or batch");
+        return UKV_EINVAL;
+    }
+    const uint32_t n = b->n_requests;
+    if (n == 0 && b->n_patches == 0)
+        return UKV_OK;
+    if (!b->page_table || (n && (!b->new_k || !b->new_v || !b->service_id || !b->ctx_len || !b->table_off ||
+                                 !b->new_off))) {
+        set_error("append needs page_table, new_k, new_v and the host arrays");
+        return UKV_EINVAL;
+    }
+    if (b->n_patches && (!b->patch_entry || !b->patch_page)) {
+        set_error("patch arrays missing");
+        return UKV_EINVAL;
+    }
+    for (uint32_t i = 0; i < b->n_patches; ++i)
+        if (b->patch_page[i] < 0 || (uint64_t)b->patch_page[i] >= p->n_pages) {
+            set_error("patch page id out of range");
+            return UKV_EINVAL;
+        }
+    for (uint32_t i = 0; i < n; ++i) {
+        if (b->service_id[i] >= p->n_services) {
+            set_error("service_id out of range");
+            return UKV_EINVAL;
+        }
+        if (b->new_off[i] & 7) {
+            set_error("new_off must be a multiple of 8 elements");
+            return UKV_EINVAL;
+        }
+        if (ukv_pages_for_tokens(p, b->service_id[i], b->ctx_len[i]) > p->n_pages) {
+            set_error("ctx_len exceeds what the pool can hold");
+            return UKV_EINVAL;
+        }
+    }
+    hipStream_t s = (hipStream_t)stream;
+    size_t o = 0;
+    const size_t off_cls = o;
+    o = align_up(o + sizeof(ClassTable));
+    const size_t off_recs = o;
+    o = align_up(o + (size_t)n * sizeof(AppendRec));
+    const size_t off_pe = o;
+    o = align_up(o + (size_t)b->n_patches * sizeof(uint64_t));
+    const size_t off_pp = o;
+    o = align_up(o + (size_t)b->n_patches * sizeof(int32_t));
+    const size_t total = o;
+    int rc = scratch_reserve(p, total, s);
+    if (rc != UKV_OK)
+        return rc;
+    ukv_pool::Stage *st = nullptr;
+    if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
+        return rc;
+    unsigned char *h = (unsigned char *)st->host;
+    std::memcpy(h + off_cls, &p->classes, sizeof(ClassTable));
+    AppendRec *recs = (AppendRec *)(h + off_recs);
+    for (uint32_t i = 0; i < n; ++i)
+        recs[i] = AppendRec{b->table_off[i], b->new_off[i], b->ctx_len[i], b->service_id[i]};
+    if (b->n_patches) {
+        std::memcpy(h + off_pe, b->patch_entry, (size_t)b->n_patches * sizeof(uint64_t));
+        std::memcpy(h + off_pp, b->patch_page, (size_t)b->n_patches * sizeof(int32_t));
+    }
+    if ((rc = stage_submit(st, p->dev_scratch, total, s)) != UKV_OK)
+        return rc;
+    unsigned char *d = (unsigned char *)p->dev_scratch;
+    ProfScope ps{p, s, 2};
+    if ((rc = ps.begin()) != UKV_OK)
+        return rc;
+    HIP_TRY(launch_patch(b->page_table, (const uint64_t *)(d + off_pe), (const int32_t *)(d + off_pp), b->n_patches,
+                         s),
+            "launch patch kernel");
+    HIP_TRY(launch_append(p->base, p->log2_page, b->page_table, (const AppendRec *)(d + off_recs), n,
+                          (const ClassRec *)(d + off_cls), b->new_k, b->new_v, s),
+            "launch append kernel");
+    return ps.end();
+}
+
+int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, const uint64_t *kv_off,
+               void *stream) {
+    if (!p || !b || !k_out || !v_out || !kv_off || !b->page_table) {
+        set_error("null argument");
+        return UKV_EINVAL;
+    }
+    const uint32_t n = b->n_requests;
+    if (n == 0)
+        return UKV_OK;
+    for (uint32_t i = 0; i < n; ++i)
+        if (b->service_id[i] >= p->n_services || (kv_off[i] & 7)) {
+            set_error("service_id out of range or kv_off not a multiple of 8");
+            return UKV_EINVAL;
+        }
+    hipStream_t s = (hipStream_t)stream;
+    const size_t off_recs = align_up(sizeof(ClassTable));
+    const size_t total = align_up(off_recs + (size_t)n * sizeof(GatherRec));
+    int rc = scratch_reserve(p, total, s);
+    if (rc != UKV_OK)
+        return rc;
+    ukv_pool::Stage *st = nullptr;
+    if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
+        return rc;
+    unsigned char *h = (unsigned char *)st->host;
+    std::memcpy(h, &p->classes, sizeof(ClassTable));
+    GatherRec *recs = (GatherRec *)(h + off_recs);
+    for (uint32_t i = 0; i < n; ++i)
+        recs[i] = GatherRec{b->table_off[i], kv_off[i], b->ctx_len[i], b->service_id[i]};
+    if ((rc = stage_submit(st, p->dev_scratch, total, s)) != UKV_OK)
+        return rc;
+    unsigned char *d = (unsigned char *)p->dev_scratch;
+    HIP_TRY(launch_gather(p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs), n,
+                          (const ClassRec *)d, k_out, v_out, s),
+            "launch gather kernel");
+    return UKV_OK;
+}
+
+int ukv_profile_read(ukv_pool_t *p, ukv_profile_t *out) {
+    if (!p || !out) {
+        set_error("null argument");
+        return UKV_EINVAL;
+    }
+    std::memset(out, 0, sizeof *out);
+    for (auto &e : p->ev_used) {
+        HIP_TRY(hipEventSynchronize(e.b), "hipEventSynchronize(profile)");
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, e.a, e.b), "hipEventElapsedTime");
+        if (e.which == 0) {
+            out->n_decode++;
+            out->decode_ms += ms;
+        } else if (e.which == 1) {
+            out->n_reduce++;
+            out->reduce_ms += ms;
+        } else {
+            out->n_append++;
+            out->append_ms += ms;
+        }
+        p->ev_free.push_back(e);
+    }
+    p->ev_used.clear();
+    return UKV_OK;
+}
+
+} // extern "C"

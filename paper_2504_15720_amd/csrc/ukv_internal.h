@@ -1,0 +1,162 @@
+// Internal declarations shared by the host code and the HIP kernels of libukv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "ukv.h"
+
+namespace ukv {
+
+// ---- records copied to the device with every decode call (plain data, 16-byte aligned) ----
+
+// One (request, head-slice) sequence.
+struct SeqRec {
+    uint64_t table_off;   // first page-table entry of the request
+    uint64_t q_off;       // element offset of the request's q (head 0)
+    uint64_t out_off;     // element offset of the request's out (head 0)
+    uint64_t part_off;    // float offset of this sequence's first partial (n_parts > 1)
+    uint32_t ctx_len;
+    uint32_t cls;         // service index
+    uint32_t head0;       // first kv head of the slice
+    uint32_t n_parts;     // work items this sequence was cut into
+    uint32_t part_stride; // floats per partial: n_heads_q * (head_dim + 2), rounded up to 4
+    uint32_t pad_[3];
+};
+static_assert(sizeof(SeqRec) == 64, "SeqRec layout");
+
+// One work item: tokens [t0, t1) of a sequence.  part == kDirect: the item is the whole
+// sequence and writes the final output.
+struct Item {
+    uint32_t seq, t0, t1, part;
+};
+static constexpr uint32_t kDirect = 0xffffffffu;
+
+// Per-service constants used by the kernels.
+struct ClassRec {
+    uint32_t n_q, n_kv, d, g;
+    uint32_t row_bytes, token_bytes;
+    uint32_t hs, ti;      // kv heads per slice, token lanes (for the configured block size)
+    float scale_log2e;    // softmax scale * log2(e)
+    uint32_t kind;        // index of the compiled (head_dim, group) variant
+    uint32_t pad_[2];
+};
+struct ClassTable {
+    ClassRec c[UKV_MAX_SERVICES];
+};
+
+enum Kind : uint32_t { kD64G1, kD64G2, kD64G4, kD64G8, kD128G1, kD128G2, kD128G4, kD128G8, kNumKinds };
+
+struct DecodeArgs {
+    const unsigned char *pool_base;
+    uint32_t log2_page;
+    const int32_t *page_table;
+    const void *q;      // bf16
+    float *out;
+    const ClassRec *classes;
+    const SeqRec *seqs;
+    const Item *items;
+    const uint32_t *span_first; // [n_spans + 1]
+    float *partials;
+};
+
+struct ReduceRec {
+    uint64_t part_off;
+    uint64_t out_off;     // element offset of the slice's first q head in out
+    uint32_t n_parts, part_stride, n_heads, d;
+};
+
+struct AppendRec {
+    uint64_t table_off;
+    uint64_t new_off;
+    uint32_t ctx_len;
+    uint32_t cls;
+};
+
+struct GatherRec {
+    uint64_t table_off;
+    uint64_t kv_off;
+    uint32_t ctx_len;
+    uint32_t cls;
+};
+
+// ---- kernel launchers (ukv_kernels.hip) ----
+hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s);
+hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,
+                         float *out, hipStream_t s);
+hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
+                        hipStream_t s);
+hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
+                         const AppendRec *recs, uint32_t n, const ClassRec *classes, const void *new_k,
+                         const void *new_v, hipStream_t s);
+hipError_t launch_gather(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
+                         const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_out, void *v_out,
+                         hipStream_t s);
+
+// ---- host planner (ukv_planner.cpp) ----
+struct Plan {
+    std::vector<SeqRec> seqs;
+    std::vector<Item> items;
+    std::vector<uint32_t> span_first;
+    std::vector<ReduceRec> reduce;
+    std::vector<uint32_t> item_span; // span index of each item (inspection only)
+    uint64_t partial_floats = 0;
+    uint64_t kv_bytes = 0;
+    uint32_t max_reduce_heads = 0;
+};
+
+struct Tunables {
+    int64_t max_spans = 2048;
+    int64_t min_span_bytes = 512 * 1024;
+    int64_t block_threads = 256;
+    int64_t heads_per_slice = 0;
+    int64_t profile = 0;
+};
+
+void set_error(const std::string &msg);
+
+} // namespace ukv
+
+// ---- the opaque pool object ----
+struct ukv_pool {
+    unsigned char *base = nullptr;
+    uint64_t n_pages = 0;
+    uint32_t page_bytes = 0, log2_page = 0;
+    uint32_t n_services = 0;
+    ukv_service_t services[UKV_MAX_SERVICES];
+    ukv::ClassTable classes;
+    ukv::Tunables tun;
+
+    // LIFO free list
+    std::vector<int32_t> free_stack;
+    std::vector<uint8_t> is_free;
+
+    // pinned staging ring + device scratch (created lazily on the first compute call)
+    struct Stage {
+        void *host = nullptr;
+        size_t cap = 0;
+        hipEvent_t ev = nullptr;
+        bool pending = false;
+    };
+    static constexpr int kStages = 8;
+    Stage stage[kStages];
+    int next_stage = 0;
+    void *dev_scratch = nullptr;
+    size_t dev_scratch_cap = 0;
+
+    // profiling
+    struct EvPair {
+        hipEvent_t a, b;
+        int which;
+    };
+    std::vector<EvPair> ev_used, ev_free;
+};
+
+namespace ukv {
+int derive_classes(ukv_pool *p);
+int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan);
+uint64_t max_partial_floats(const ukv_pool *p, uint32_t n_requests);
+} // namespace ukv

@@ -1,0 +1,409 @@
+// HIP kernels of the unified-KV decode path for gfx950 (CDNA4, wave64).
+//
+//   decode_kernel : split-KV decode attention over a mixed-service batch, one launch.
+//   reduce_kernel : merges the partial (max, sum, accumulator) triples of cut sequences.
+//   append_kernel : scatters each request's new K/V token into its pages (store side).
+//   patch_kernel  : writes new page-table entries.
+//   gather_kernel : test hook, paged -> contiguous copy.
+//
+// Decode is bound by HBM: every cached K/V byte is read once per step (decode phase, section
+// 2.1; merged blocks are chosen for read locality, section 4.4).  The design therefore keeps
+// every load a fully used 128-bit access: a row (one kv head of one token, K[d] | V[d]) is
+// read by d/8 adjacent lanes, 16 bytes each, so one wave instruction covers whole 128-byte
+// lines, and the lanes of a workgroup cover `hs` consecutive heads of `ti` consecutive
+// tokens, i.e. contiguous stretches of the request's byte stream inside 16 KiB pages.
+#include <hip/hip_runtime.h>
+
+#include "ukv_internal.h"
+
+namespace ukv {
+
+static constexpr int kTabWindow = 2048; // page-table entries staged in LDS at a time
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ void unpack8(const uint4 &w, float *f) {
+    f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x);
+    f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+    f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z);
+    f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LPR (8 or 16) adjacent lanes that share a row; every lane gets the total.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+    x += dpp_f<0xB1>(x);  // quad_perm [1,0,3,2]
+    x += dpp_f<0x4E>(x);  // quad_perm [2,3,0,1]
+    x += dpp_f<0x141>(x); // row_half_mirror
+    if (LPR == 16)
+        x += dpp_f<0x140>(x); // row_mirror
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Values that are the same in every lane of the workgroup, moved to scalar registers.
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
+__device__ __forceinline__ uint64_t uni(uint64_t x) {
+    return ((uint64_t)uni((uint32_t)(x >> 32)) << 32) | uni((uint32_t)x);
+}
+__device__ __forceinline__ float uni(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
+
+// Online-softmax update of one kv head's G query heads with U tokens.
+template <int G, int U, int LPR>
+__device__ __forceinline__ void update(const float (&qf)[G][8], const uint4 (&kr)[U], const uint4 (&vr)[U],
+                                       float (&m)[G], float (&l)[G], float (&acc)[G][8]) {
+    float kf[U][8], vf[U][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        unpack8(kr[u], kf[u]);
+        unpack8(vr[u], vf[u]);
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float sc[U];
+        float mx = m[g];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                d = fmaf(qf[g][e], kf[u][e], d);
+            sc[u] = row_sum<LPR>(d);
+            mx = fmaxf(mx, sc[u]);
+        }
+        const float alpha = fast_exp2(m[g] - mx); // m = -inf on the first batch gives 0
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            acc[g][e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float p = fast_exp2(sc[u] - mx);
+            psum += p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                acc[g][e] = fmaf(p, vf[u][e], acc[g][e]);
+        }
+        l[g] = fmaf(l[g], alpha, psum);
+        m[g] = mx;
+    }
+}
+
+template <int D, int G, int NT>
+__device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRec &s, const Item &it, int32_t *tab,
+                             float *mbuf) {
+    constexpr int LPR = D / 8;   // lanes per row
+    constexpr int NG = NT / LPR; // row groups in the workgroup
+    constexpr int U = (G >= 4) ? 2 : 4;
+    const int tid = threadIdx.x;
+    const int lir = tid % LPR, grp = tid / LPR;
+    const uint32_t HS = c.hs, TI = c.ti;
+    const uint32_t hh = grp % HS, tl = grp / HS;
+    const bool live = tl < TI;
+    const uint32_t kvh = s.head0 + hh;
+    const uint32_t lg = a.log2_page;
+    const uint64_t page_mask = (1ull << lg) - 1;
+
+    float qf[G][8];
+    {
+        const uint4 *qp = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.q) + s.q_off +
+                                                          (uint64_t)(kvh * G) * D + lir * 8);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint4 w = qp[g * LPR];
+            unpack8(w, qf[g]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                qf[g][e] *= c.scale_log2e;
+        }
+    }
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            acc[g][e] = 0.f;
+    }
+
+    const uint64_t T = c.token_bytes;
+    const uint64_t row0 = (uint64_t)kvh * c.row_bytes + (uint64_t)lir * 16;
+    const uint64_t slice_lo = (uint64_t)s.head0 * c.row_bytes;
+    const uint64_t slice_hi = (uint64_t)(s.head0 + HS) * c.row_bytes;
+
+    uint32_t w0 = it.t0;
+    while (w0 < it.t1) { // workgroup-uniform: one pass per page-table window
+        const uint64_t s_lo = ((uint64_t)w0 * T + slice_lo) >> lg;
+        const uint64_t lim = (s_lo + kTabWindow) << lg;
+        const uint64_t tmax = (lim - slice_hi) / T; // last token whose slice ends inside the window
+        const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)it.t1 ? tmax + 1 : (uint64_t)it.t1);
+        const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + slice_hi - 1) >> lg) - s_lo) + 1;
+        __syncthreads();
+        for (uint32_t e = tid; e < n_ent; e += NT)
+            tab[e] = a.page_table[s.table_off + s_lo + e];
+        __syncthreads();
+
+        if (live) {
+            auto row_ptr = [&](uint32_t t) -> const uint4 * {
+                const uint64_t off = (uint64_t)t * T + row0;
+                const int32_t pg = tab[(uint32_t)((off >> lg) - s_lo)];
+                return reinterpret_cast<const uint4 *>(a.pool_base + ((uint64_t)(uint32_t)pg << lg) +
+                                                       (off & page_mask));
+            };
+            uint32_t t = w0 + tl;
+            for (; (uint64_t)t + (uint64_t)(U - 1) * TI < w1; t += U * TI) {
+                uint4 kr[U], vr[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint4 *p = row_ptr(t + u * TI);
+                    kr[u] = p[0];
+                    vr[u] = p[LPR];
+                }
+                update<G, U, LPR>(qf, kr, vr, m, l, acc);
+            }
+            for (; t < w1; t += TI) {
+                uint4 kr[1], vr[1];
+                const uint4 *p = row_ptr(t);
+                kr[0] = p[0];
+                vr[0] = p[LPR];
+                update<G, 1, LPR>(qf, kr, vr, m, l, acc);
+            }
+        }
+        w0 = w1;
+    }
+
+    // merge the token lanes of each head (LDS), then write the final output or a partial
+    float *accb = mbuf;               // [NG][LPR*8]
+    float *mlb = mbuf + NG * LPR * 8; // [NG][2]
+    const bool direct = it.part == kDirect;
+    float *pbase = direct ? nullptr : a.partials + s.part_off + (uint64_t)it.part * s.part_stride;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (TI > 1) {
+            __syncthreads();
+            if (live && tl > 0) {
+                float4 *dst = reinterpret_cast<float4 *>(accb + grp * (LPR * 8) + lir * 8);
+                dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+                dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+                if (lir == 0) {
+                    mlb[grp * 2] = m[g];
+                    mlb[grp * 2 + 1] = l[g];
+                }
+            }
+            __syncthreads();
+            if (live && tl == 0) {
+                for (uint32_t j = 1; j < TI; ++j) {
+                    const uint32_t og = j * HS + hh;
+                    const float mo = mlb[og * 2], lo = mlb[og * 2 + 1];
+                    const float mx = fmaxf(m[g], mo);
+                    const float mxs = (mx == -INFINITY) ? 0.f : mx;
+                    const float wa = fast_exp2(m[g] - mxs), wb = fast_exp2(mo - mxs);
+                    const float4 *src = reinterpret_cast<const float4 *>(accb + og * (LPR * 8) + lir * 8);
+                    const float4 x0 = src[0], x1 = src[1];
+                    acc[g][0] = acc[g][0] * wa + x0.x * wb;
+                    acc[g][1] = acc[g][1] * wa + x0.y * wb;
+                    acc[g][2] = acc[g][2] * wa + x0.z * wb;
+                    acc[g][3] = acc[g][3] * wa + x0.w * wb;
+                    acc[g][4] = acc[g][4] * wa + x1.x * wb;
+                    acc[g][5] = acc[g][5] * wa + x1.y * wb;
+                    acc[g][6] = acc[g][6] * wa + x1.z * wb;
+                    acc[g][7] = acc[g][7] * wa + x1.w * wb;
+                    l[g] = l[g] * wa + lo * wb;
+                    m[g] = mx;
+                }
+            }
+        }
+        if (live && tl == 0) {
+            if (direct) {
+                const float inv = l[g] > 0.f ? 1.f / l[g] : 0.f;
+                float4 *dst = reinterpret_cast<float4 *>(a.out + s.out_off + (uint64_t)(kvh * G + g) * D + lir * 8);
+                dst[0] = make_float4(acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv);
+                dst[1] = make_float4(acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv);
+            } else {
+                const uint32_t hq = hh * G + g;
+                float4 *dst = reinterpret_cast<float4 *>(pbase + (uint64_t)hq * D + lir * 8);
+                dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+                dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+                if (lir == 0) {
+                    float *ml = pbase + (uint64_t)HS * G * D + hq * 2;
+                    ml[0] = m[g];
+                    ml[1] = l[g];
+                }
+            }
+        }
+    }
+}
+
+template <int NT>
+__global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
+    __shared__ int32_t tab[kTabWindow];
+    __shared__ __align__(16) float mbuf[NT * 8 + (NT / 8) * 2];
+    const uint32_t i0 = uni(a.span_first[blockIdx.x]), i1 = uni(a.span_first[blockIdx.x + 1]);
+    for (uint32_t i = i0; i < i1; ++i) {
+        Item it = a.items[i];
+        it.seq = uni(it.seq); it.t0 = uni(it.t0); it.t1 = uni(it.t1); it.part = uni(it.part);
+        SeqRec s = a.seqs[it.seq];
+        s.table_off = uni(s.table_off); s.q_off = uni(s.q_off); s.out_off = uni(s.out_off);
+        s.part_off = uni(s.part_off); s.cls = uni(s.cls); s.head0 = uni(s.head0);
+        s.part_stride = uni(s.part_stride);
+        ClassRec c = a.classes[s.cls];
+        c.token_bytes = uni(c.token_bytes); c.row_bytes = uni(c.row_bytes); c.hs = uni(c.hs); c.ti = uni(c.ti);
+        c.kind = uni(c.kind); c.scale_log2e = uni(c.scale_log2e);
+        switch (c.kind) { // workgroup-uniform: one compiled shape per (head_dim, group)
+        case kD64G1: process_item<64, 1, NT>(a, c, s, it, tab, mbuf); break;
+        case kD64G2: process_item<64, 2, NT>(a, c, s, it, tab, mbuf); break;
+        case kD64G4: process_item<64, 4, NT>(a, c, s, it, tab, mbuf); break;
+        case kD64G8: process_item<64, 8, NT>(a, c, s, it, tab, mbuf); break;
+        case kD128G1: process_item<128, 1, NT>(a, c, s, it, tab, mbuf); break;
+        case kD128G2: process_item<128, 2, NT>(a, c, s, it, tab, mbuf); break;
+        case kD128G4: process_item<128, 4, NT>(a, c, s, it, tab, mbuf); break;
+        case kD128G8: process_item<128, 8, NT>(a, c, s, it, tab, mbuf); break;
+        default: break;
+        }
+    }
+}
+
+// One 64-lane workgroup per (cut sequence, query head): out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M).
+__global__ void __launch_bounds__(64) reduce_kernel(const ReduceRec *recs, const float *partials, float *out) {
+    const ReduceRec r = recs[blockIdx.x];
+    const uint32_t hq = blockIdx.y;
+    if (hq >= r.n_heads)
+        return;
+    const float *base = partials + r.part_off;
+    const uint32_t ml_off = r.n_heads * r.d + hq * 2;
+    const uint32_t lane = threadIdx.x;
+    float M = -INFINITY;
+    for (uint32_t c = 0; c < r.n_parts; ++c) {
+        const float *p = base + (uint64_t)c * r.part_stride + ml_off;
+        if (p[1] > 0.f)
+            M = fmaxf(M, p[0]);
+    }
+    float L = 0.f, o0 = 0.f, o1 = 0.f;
+    const bool two = r.d > 64;
+    for (uint32_t c = 0; c < r.n_parts; ++c) {
+        const float *pc = base + (uint64_t)c * r.part_stride;
+        const float mc = pc[ml_off], lc = pc[ml_off + 1];
+        if (!(lc > 0.f))
+            continue;
+        const float w = fast_exp2(mc - M);
+        L = fmaf(lc, w, L);
+        if (lane < r.d)
+            o0 = fmaf(pc[hq * r.d + lane], w, o0);
+        if (two)
+            o1 = fmaf(pc[hq * r.d + 64 + lane], w, o1);
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    float *dst = out + r.out_off + (uint64_t)hq * r.d;
+    if (lane < r.d)
+        dst[lane] = o0 * inv;
+    if (two)
+        dst[64 + lane] = o1 * inv;
+}
+
+__global__ void patch_kernel(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        page_table[entry[i]] = page[i];
+}
+
+// One workgroup per request; each lane moves 16-byte pieces of the new token row.
+__global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, uint32_t lg, const int32_t *page_table,
+                                                     const AppendRec *recs, const ClassRec *classes,
+                                                     const uint16_t *new_k, const uint16_t *new_v) {
+    const AppendRec r = recs[blockIdx.x];
+    if (r.ctx_len == 0)
+        return;
+    const ClassRec c = classes[r.cls];
+    const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
+    const uint32_t n_pieces = c.token_bytes / 16;
+    const uint64_t stream0 = (uint64_t)(r.ctx_len - 1) * c.token_bytes;
+    const uint64_t page_mask = (1ull << lg) - 1;
+    for (uint32_t pc = threadIdx.x; pc < n_pieces; pc += blockDim.x) {
+        const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
+        const uint16_t *src = (w < half ? new_k : new_v) + r.new_off + (uint64_t)h * c.d + (w % half) * 8;
+        const uint64_t off = stream0 + (uint64_t)pc * 16;
+        const int32_t pg = page_table[r.table_off + (off >> lg)];
+        uint4 *dst = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
+        *dst = *reinterpret_cast<const uint4 *>(src);
+    }
+}
+
+// grid (request, y): workgroups of one request stride over its tokens.
+__global__ void __launch_bounds__(256) gather_kernel(const unsigned char *pool_base, uint32_t lg,
+                                                     const int32_t *page_table, const GatherRec *recs,
+                                                     const ClassRec *classes, uint16_t *k_out, uint16_t *v_out) {
+    const GatherRec r = recs[blockIdx.x];
+    const ClassRec c = classes[r.cls];
+    const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
+    const uint32_t n_pieces = c.token_bytes / 16;
+    const uint64_t page_mask = (1ull << lg) - 1;
+    for (uint32_t t = blockIdx.y; t < r.ctx_len; t += gridDim.y) {
+        const uint64_t stream0 = (uint64_t)t * c.token_bytes;
+        for (uint32_t pc = threadIdx.x; pc < n_pieces; pc += blockDim.x) {
+            const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
+            const uint64_t off = stream0 + (uint64_t)pc * 16;
+            const int32_t pg = page_table[r.table_off + (off >> lg)];
+            const uint4 v = *reinterpret_cast<const uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) +
+                                                             (off & page_mask));
+            uint16_t *dst = (w < half ? k_out : v_out) + r.kv_off + ((uint64_t)t * c.n_kv + h) * c.d + (w % half) * 8;
+            *reinterpret_cast<uint4 *>(dst) = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s) {
+    if (n_spans == 0)
+        return hipSuccess;
+    if (block_threads == 512)
+        hipLaunchKernelGGL(decode_kernel<512>, dim3(n_spans), dim3(512), 0, s, a);
+    else
+        hipLaunchKernelGGL(decode_kernel<256>, dim3(n_spans), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,
+                         float *out, hipStream_t s) {
+    if (n_recs == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(reduce_kernel, dim3(n_recs, max_heads), dim3(64), 0, s, recs, partials, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
+                        hipStream_t s) {
+    if (n == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(patch_kernel, dim3((n + 255) / 256), dim3(256), 0, s, page_table, entry, page, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
+                         const AppendRec *recs, uint32_t n, const ClassRec *classes, const void *new_k,
+                         const void *new_v, hipStream_t s) {
+    if (n == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(append_kernel, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table, recs, classes,
+                       static_cast<const uint16_t *>(new_k), static_cast<const uint16_t *>(new_v));
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
+                         const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_out, void *v_out,
+                         hipStream_t s) {
+    if (n == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(gather_kernel, dim3(n, 32), dim3(256), 0, s, pool_base, log2_page, page_table, recs, classes,
+                       static_cast<uint16_t *>(k_out), static_cast<uint16_t *>(v_out));
+    return hipGetLastError();
+}
+
+} // namespace ukv

@@ -1,0 +1,151 @@
+// Host planner for the split-KV decode launch: cuts a mixed-service batch into work items of
+// (request, head-slice, token range) and groups them into equal-cost spans, one per workgroup.
+// The decode phase reads every cached K/V byte once per step (section 2.1), so cost is counted
+// in KV bytes; long-tailed context lengths are balanced by cutting at token granularity.
+#include <algorithm>
+
+#include "ukv_internal.h"
+
+namespace ukv {
+
+static constexpr uint64_t kItemOverheadBytes = 16 * 1024; // q load, merge and output, as KV bytes
+static constexpr uint64_t kMinItemTokens = 16;
+
+static inline uint32_t round_up4(uint32_t x) { return (x + 3u) & ~3u; }
+
+static uint32_t part_stride_of(const ClassRec &c) { return round_up4(c.hs * c.g * (c.d + 2)); }
+
+static uint32_t spans_bound(const ukv_pool *p) { return (uint32_t)(2 * p->tun.max_spans + 2); }
+
+uint64_t max_partial_floats(const ukv_pool *p, uint32_t /*n_requests*/) {
+    uint32_t stride = 0;
+    for (uint32_t s = 0; s < p->n_services; ++s)
+        stride = std::max(stride, part_stride_of(p->classes.c[s]));
+    // every span boundary cuts at most one sequence, adding at most two partials
+    return (uint64_t)2 * spans_bound(p) * stride;
+}
+
+int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
+    if (!p || !b) {
+        set_error("null pool or batch");
+        return UKV_EINVAL;
+    }
+    const uint32_t n = b->n_requests;
+    if (n && (!b->service_id || !b->ctx_len || !b->table_off || !b->q_off || !b->out_off)) {
+        set_error("batch host arrays must be non-null");
+        return UKV_EINVAL;
+    }
+    plan = Plan();
+    uint64_t total_cost = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t cls = b->service_id[i];
+        if (cls >= p->n_services) {
+            set_error("service_id out of range");
+            return UKV_EINVAL;
+        }
+        if ((b->q_off[i] & 7) || (b->out_off[i] & 3)) {
+            set_error("q_off must be a multiple of 8 elements and out_off of 4");
+            return UKV_EINVAL;
+        }
+        const ClassRec &c = p->classes.c[cls];
+        const uint64_t ctx = b->ctx_len[i];
+        if (ukv_pages_for_tokens(p, cls, ctx) > p->n_pages) {
+            set_error("ctx_len exceeds what the pool can hold");
+            return UKV_EINVAL;
+        }
+        plan.kv_bytes += ctx * c.token_bytes;
+        for (uint32_t h0 = 0; h0 < c.n_kv; h0 += c.hs) {
+            SeqRec s{};
+            s.table_off = b->table_off[i];
+            s.q_off = b->q_off[i];
+            s.out_off = b->out_off[i];
+            s.ctx_len = (uint32_t)ctx;
+            s.cls = cls;
+            s.head0 = h0;
+            s.part_stride = part_stride_of(c);
+            plan.seqs.push_back(s);
+            total_cost += kItemOverheadBytes + ctx * c.hs * c.row_bytes;
+        }
+    }
+    if (plan.seqs.empty()) {
+        plan.span_first.push_back(0);
+        return UKV_OK;
+    }
+
+    uint64_t n_spans_target = total_cost / (uint64_t)p->tun.min_span_bytes;
+    n_spans_target = std::max<uint64_t>(1, std::min<uint64_t>(n_spans_target, (uint64_t)p->tun.max_spans));
+    const uint64_t C = (total_cost + n_spans_target - 1) / n_spans_target;
+
+    std::vector<uint32_t> seq_first_item(plan.seqs.size() + 1, 0);
+    plan.span_first.push_back(0);
+    int64_t fill = 0;
+    auto close_span = [&](bool carry) {
+        if (plan.span_first.back() != plan.items.size())
+            plan.span_first.push_back((uint32_t)plan.items.size());
+        fill = carry ? std::max<int64_t>(0, fill - (int64_t)C) : 0;
+    };
+    for (uint32_t k = 0; k < plan.seqs.size(); ++k) {
+        const SeqRec &s = plan.seqs[k];
+        const ClassRec &c = p->classes.c[s.cls];
+        const uint64_t cost = (uint64_t)c.hs * c.row_bytes;
+        seq_first_item[k] = (uint32_t)plan.items.size();
+        uint64_t t = 0, rem = s.ctx_len;
+        if (rem == 0) {
+            plan.items.push_back(Item{k, 0, 0, kDirect});
+            plan.item_span.push_back((uint32_t)plan.span_first.size() - 1);
+            fill += (int64_t)kItemOverheadBytes;
+            if (fill >= (int64_t)C)
+                close_span(true);
+            continue;
+        }
+        while (rem > 0) {
+            const int64_t avail = (int64_t)C - fill - (int64_t)kItemOverheadBytes;
+            if (fill > 0 && avail < (int64_t)(std::min<uint64_t>(kMinItemTokens, rem) * cost)) {
+                close_span(false); // too little room left: start the next span instead of a sliver
+                continue;
+            }
+            uint64_t take = avail > 0 ? (uint64_t)avail / cost : 0;
+            take = std::max<uint64_t>(take, 1);
+            if (take >= rem || rem - take < kMinItemTokens)
+                take = rem;
+            plan.items.push_back(Item{k, (uint32_t)t, (uint32_t)(t + take), 0});
+            plan.item_span.push_back((uint32_t)plan.span_first.size() - 1);
+            fill += (int64_t)(kItemOverheadBytes + take * cost);
+            t += take;
+            rem -= take;
+            if (fill >= (int64_t)C)
+                close_span(true);
+        }
+    }
+    seq_first_item[plan.seqs.size()] = (uint32_t)plan.items.size();
+    if (plan.span_first.back() != plan.items.size())
+        plan.span_first.push_back((uint32_t)plan.items.size());
+
+    // partial slots and the merge list
+    for (uint32_t k = 0; k < plan.seqs.size(); ++k) {
+        SeqRec &s = plan.seqs[k];
+        const ClassRec &c = p->classes.c[s.cls];
+        const uint32_t i0 = seq_first_item[k], i1 = seq_first_item[k + 1];
+        s.n_parts = i1 - i0;
+        if (s.n_parts <= 1) {
+            plan.items[i0].part = kDirect;
+            continue;
+        }
+        s.part_off = plan.partial_floats;
+        for (uint32_t it = i0; it < i1; ++it)
+            plan.items[it].part = it - i0;
+        plan.partial_floats += (uint64_t)s.n_parts * s.part_stride;
+        ReduceRec r{};
+        r.part_off = s.part_off;
+        r.out_off = s.out_off + (uint64_t)s.head0 * c.g * c.d;
+        r.n_parts = s.n_parts;
+        r.part_stride = s.part_stride;
+        r.n_heads = c.hs * c.g;
+        r.d = c.d;
+        plan.reduce.push_back(r);
+        plan.max_reduce_heads = std::max(plan.max_reduce_heads, r.n_heads);
+    }
+    return UKV_OK;
+}
+
+} // namespace ukv

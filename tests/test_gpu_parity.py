@@ -1,0 +1,229 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: append, page-table patches and gather are bit-exact; attention outputs (fp32 accumulation
+over bf16 K/V) agree with the fp64 oracle within max |err| <= 2e-3.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import paper_2504_15720_amd as U
+from oracle import oracle
+from synth import SHAPES, Service, make_batch, make_config
+from tests.ukv_harness import DeviceBatch
+
+pytestmark = pytest.mark.gpu
+ATOL = 2e-3
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _check_attention(db, b, tag):
+    db.decode()
+    got = db.out_host().astype(np.float64)
+    ref = oracle.attention(b, b.pool)
+    assert np.all(np.isfinite(got)), f"{tag}: non-finite output"
+    err = float(np.max(np.abs(got - ref)))
+    say(f"  {tag}: max|err| = {err:.3e}")
+    assert err <= ATOL, f"{tag}: max |err| {err}"
+    return err
+
+
+def _check_gather(db, b):
+    k, v, kv_off, sizes = db.gather()
+    for i in range(b.n_requests):
+        s = b.service_of(i)
+        n = int(b.ctx_len[i])
+        if n == 0:
+            continue
+        rk, rv = oracle.gather(b.pool, b.page_bytes, b.table_of(i), s.n_kv_heads, s.head_dim, n)
+        o = int(kv_off[i])
+        assert np.array_equal(k[o:o + int(sizes[i])], rk.reshape(-1)), f"gather K mismatch, request {i}"
+        assert np.array_equal(v[o:o + int(sizes[i])], rv.reshape(-1)), f"gather V mismatch, request {i}"
+
+
+def _decode_steps(db, b, steps, seed, check_every=1):
+    """steps x (grow, append, attention) with the oracle mirroring the pool image on the host."""
+    rng = np.random.default_rng(seed)
+    for step in range(steps):
+        entry, ids = b.grow_one_token()
+        lib_ids = U.ukv_pages_alloc(db.pool, ids.size) if ids.size else np.zeros(0, np.int32)
+        assert np.array_equal(lib_ids, ids), "library free list diverged from the synthetic stack"
+        q, nk, nv = b.draw_step_inputs(rng)
+        b.q = q
+        db.set_q(q)
+        db.set_new(nk, nv)
+        oracle.append(b, b.pool, nk, nv)
+        db.append(db.desc(entry, ids))
+        if step % check_every == 0 or step == steps - 1:
+            _check_attention(db, b, f"step {step}")
+    assert np.array_equal(db.table_t.cpu().numpy(), b.page_table), "device page table differs"
+    assert np.array_equal(db.pool_host(), b.pool), "pool image differs after append"
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("block", [256, 512])
+def test_mini_configs_match_oracle(cfg, block):
+    say(f"mini cfg {cfg} block {block}")
+    b = make_config(cfg, mini=True)
+    db = DeviceBatch(b)
+    try:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, block)
+        db.resize_workspace()
+        _check_attention(db, b, "whole-request items")
+        _check_gather(db, b)
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 48 * 1024)      # many cuts -> reduce pass
+        _check_attention(db, b, "cut into many items")
+        steps = max(1, int(b.notes["steps"]))
+        _decode_steps(db, b, min(steps, 4), seed=cfg)
+    finally:
+        db.close()
+
+
+def test_edge_cases_empty_single_and_ragged():
+    say("edge cases")
+    services = [SHAPES["7b"], SHAPES["13b"], SHAPES["8b"], SHAPES["70b"], SHAPES["tiny"], SHAPES["h12"]]
+    sid = np.array([0, 1, 2, 3, 4, 5, 0, 1, 2, 3, 4, 5, 1, 5])
+    ctx = np.array([0, 0, 0, 0, 0, 0, 1, 1, 1, 1, 1, 1, 257, 1031])
+    rng = np.random.default_rng(99)
+    b = make_batch(services, sid, ctx, 2048, "permutation", rng, reserve_tokens=2, pool_seed=5)
+    db = DeviceBatch(b)
+    try:
+        _check_attention(db, b, "ctx 0/1/ragged")
+        got = db.out_host()
+        for i in range(6):
+            s = b.service_of(i); o = int(b.out_off[i])
+            assert np.all(got[o:o + s.n_q_heads * s.head_dim] == 0.0)
+        for i in range(6, 12):        # one token: output is that token's V exactly
+            s = b.service_of(i); o = int(b.out_off[i])
+            _, v = oracle.gather(b.pool, b.page_bytes, b.table_of(i), s.n_kv_heads, s.head_dim, 1)
+            vf = (v.astype(np.uint32) << 16).view(np.float32)[0]
+            assert np.array_equal(got[o:o + s.n_q_heads * s.head_dim].reshape(s.n_kv_heads, s.group, s.head_dim),
+                                  np.repeat(vf[:, None, :], s.group, axis=1))
+        _decode_steps(db, b, 2, seed=3)       # 0 -> 1 -> 2 tokens, including first-page allocation
+    finally:
+        db.close()
+
+
+def test_bytes_past_ctx_len_are_never_read_into_the_result():
+    say("poison test")
+    b = make_config(5, mini=True)
+    ref = oracle.attention(b, b.pool)
+    # poison every element that is not a valid token of some request with NaN / Inf patterns
+    valid = np.zeros(b.pool.size, bool)
+    for i in range(b.n_requests):
+        s = b.service_of(i)
+        n_bytes = int(b.ctx_len[i]) * s.token_bytes
+        tab = b.table_of(i)
+        for slot in range(-(-n_bytes // b.page_bytes)):
+            lo = int(tab[slot]) * b.page_bytes // 2
+            cnt = min(b.page_bytes, n_bytes - slot * b.page_bytes) // 2
+            valid[lo:lo + cnt] = True
+    poison = np.where(np.arange(b.pool.size) % 2 == 0, 0x7FC0, 0xFF80).astype(np.uint16)
+    b.pool = np.where(valid, b.pool, poison)
+    assert np.array_equal(oracle.attention(b, b.pool), ref)
+    db = DeviceBatch(b)
+    try:
+        for block in (256, 512):
+            U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, block)
+            _check_attention(db, b, f"poisoned pool, block {block}")
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 32 * 1024)
+        _check_attention(db, b, "poisoned pool, many cuts")
+    finally:
+        db.close()
+
+
+def test_append_changes_only_the_new_token_bytes():
+    say("append sentinel test")
+    b = make_config(5, mini=True)
+    b.pool[:] = 0xABCD
+    db = DeviceBatch(b)
+    try:
+        _decode_steps_no_attention(db, b, 3)
+    finally:
+        db.close()
+
+
+def _decode_steps_no_attention(db, b, steps):
+    rng = np.random.default_rng(8)
+    for _ in range(steps):
+        entry, ids = b.grow_one_token()
+        assert np.array_equal(U.ukv_pages_alloc(db.pool, ids.size) if ids.size else ids, ids)
+        _, nk, nv = b.draw_step_inputs(rng)
+        db.set_new(nk, nv)
+        oracle.append(b, b.pool, nk, nv)
+        db.append(db.desc(entry, ids))
+    got = db.pool_host()
+    assert np.array_equal(got, b.pool)
+    untouched = got == 0xABCD
+    expected_new = sum(2 * b.service_of(i).n_kv_heads * b.service_of(i).head_dim for i in range(b.n_requests)) * steps
+    assert abs(int((~untouched).sum()) - expected_new) <= expected_new // 1000 + 4
+
+
+def test_page_renaming_gives_bit_identical_output():
+    say("page renaming")
+    b = make_config(3, mini=True)
+    db = DeviceBatch(b)
+    db.decode()
+    first = db.out_host().copy()
+    db.close()
+    perm = np.random.default_rng(4).permutation(b.n_pages)
+    epp = b.page_bytes // 2
+    pool2 = np.empty_like(b.pool)
+    pool2.reshape(b.n_pages, epp)[perm] = b.pool.reshape(b.n_pages, epp)
+    b.pool = pool2
+    b.page_table = np.where(b.page_table >= 0, perm[np.maximum(b.page_table, 0)], -1).astype(np.int32)
+    db2 = DeviceBatch(b)
+    try:
+        db2.decode()
+        assert np.array_equal(db2.out_host(), first)
+    finally:
+        db2.close()
+
+
+def test_errors_from_the_compute_calls():
+    b = make_config(1, mini=True)
+    db = DeviceBatch(b)
+    try:
+        with pytest.raises(U.UkvError) as e:
+            U.ukv_decode_attention(db.pool, db.desc(), db.ws_t.data_ptr(), 1024, db.stream())
+        assert e.value.code == U.UKV_ENOSPC
+        with pytest.raises(U.UkvError) as e:
+            U.ukv_decode_attention(db.pool, db.desc(), db.ws_t.data_ptr() + 8, db.ws_bytes - 8, db.stream())
+        assert e.value.code == U.UKV_EINVAL
+        with pytest.raises(U.UkvError) as e:
+            db.append(db.desc([0], [b.n_pages + 5]))
+        assert e.value.code == U.UKV_EINVAL
+    finally:
+        db.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_full_size_configs_match_oracle(cfg):
+    say(f"full cfg {cfg}")
+    b = make_config(cfg)
+    say(f"  generated: {b.n_requests} requests, {b.kv_bytes() / 1e9:.2f} GB of KV, pool {b.n_pages} pages")
+    db = DeviceBatch(b)
+    try:
+        steps = int(b.notes["steps"])
+        if steps:
+            _decode_steps(db, b, steps, seed=100 + cfg)
+        else:
+            _check_attention(db, b, "attention")
+    finally:
+        db.close()
+
+
+def test_full_size_config5_sixteen_steps():
+    say("full cfg 5, 16 x (append + attention)")
+    b = make_config(5)
+    say(f"  generated: {b.n_requests} requests, {b.kv_bytes() / 1e9:.2f} GB of KV, pool {b.n_pages} pages")
+    db = DeviceBatch(b)
+    try:
+        _decode_steps(db, b, 16, seed=105, check_every=5)
+    finally:
+        db.close()

@@ -1,0 +1,93 @@
+"""Glue shared by the GPU tests, smoke check and benchmark: puts a synthetic batch on the
+device and drives the C-ABI binding.  It performs no arithmetic of the method."""
+from __future__ import annotations
+
+import numpy as np
+
+import paper_2504_15720_amd as U
+
+
+def replay_stack_log(pool: int, log) -> None:
+    """Bring the library's free list to the state of a synthetic PageStack by replaying its operations."""
+    for op, arg in log:
+        if op == "alloc":
+            U.ukv_pages_alloc(pool, int(arg))
+        else:
+            U.ukv_pages_free(pool, arg)
+
+
+class DeviceBatch:
+    """Device copies of a synthetic batch + the pool handle."""
+
+    def __init__(self, b, device="cuda:0", profile=False):
+        import torch
+        self.torch = torch
+        self.b = b
+        self.dev = torch.device(device)
+        assert b.pool is not None
+        n_el = b.n_pages * b.page_bytes // 2
+        self._pool_raw = torch.empty(n_el + b.page_bytes // 2, dtype=torch.int16, device=self.dev)
+        skip = (-self._pool_raw.data_ptr() % b.page_bytes) // 2          # page-align the pool base
+        self.pool_t = self._pool_raw[skip:skip + n_el]
+        self.pool_t.copy_(torch.from_numpy(b.pool.view(np.int16)))
+        assert self.pool_t.data_ptr() % b.page_bytes == 0
+        self.pool = U.ukv_pool_create(self.pool_t.data_ptr(), b.n_pages * b.page_bytes, b.page_bytes, b.services)
+        replay_stack_log(self.pool, b.stack.log)
+        self.table_t = torch.from_numpy(b.page_table.copy()).to(self.dev)
+        self.q_t = torch.from_numpy(b.q.view(np.int16).copy()).to(self.dev)
+        self.out_t = torch.full((b.out_elems,), float("nan"), dtype=torch.float32, device=self.dev)
+        self.newk_t = torch.zeros(b.new_elems, dtype=torch.int16, device=self.dev)
+        self.newv_t = torch.zeros(b.new_elems, dtype=torch.int16, device=self.dev)
+        self.ws_bytes = U.ukv_decode_workspace_bytes(self.pool, b.n_requests)
+        self.ws_t = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        if profile:
+            U.ukv_set_param(self.pool, U.UKV_PARAM_PROFILE, 1)
+
+    def close(self):
+        if self.pool:
+            self.torch.cuda.synchronize()
+            U.ukv_pool_destroy(self.pool)
+            self.pool = 0
+
+    def resize_workspace(self):
+        self.ws_bytes = U.ukv_decode_workspace_bytes(self.pool, self.b.n_requests)
+        self.ws_t = self.torch.empty(self.ws_bytes, dtype=self.torch.uint8, device=self.dev)
+
+    def stream(self) -> int:
+        return self.torch.cuda.current_stream().cuda_stream
+
+    def desc(self, patch_entry=None, patch_page=None) -> "U.BatchDesc":
+        b = self.b
+        return U.BatchDesc(b.service_id, b.ctx_len, b.table_off, self.table_t.data_ptr(), self.q_t.data_ptr(),
+                           b.q_off, self.out_t.data_ptr(), b.out_off, self.newk_t.data_ptr(),
+                           self.newv_t.data_ptr(), b.new_off, patch_entry, patch_page)
+
+    def set_q(self, q_bits: np.ndarray):
+        self.q_t.copy_(self.torch.from_numpy(q_bits.view(np.int16)))
+
+    def set_new(self, k_bits: np.ndarray, v_bits: np.ndarray):
+        self.newk_t.copy_(self.torch.from_numpy(k_bits.view(np.int16)))
+        self.newv_t.copy_(self.torch.from_numpy(v_bits.view(np.int16)))
+
+    def decode(self, desc=None):
+        U.ukv_decode_attention(self.pool, desc or self.desc(), self.ws_t.data_ptr(), self.ws_bytes, self.stream())
+
+    def append(self, desc):
+        U.ukv_append(self.pool, desc, self.stream())
+
+    def out_host(self) -> np.ndarray:
+        return self.out_t.cpu().numpy()
+
+    def pool_host(self) -> np.ndarray:
+        return self.pool_t.cpu().numpy().view(np.uint16)
+
+    def gather(self):
+        b = self.b
+        tok_elems = np.array([b.services[s].n_kv_heads * b.services[s].head_dim for s in b.service_id], np.int64)
+        sizes = b.ctx_len.astype(np.int64) * tok_elems
+        kv_off = (np.cumsum(sizes) - sizes).astype(np.uint64)
+        total = int(sizes.sum())
+        k = self.torch.zeros(max(total, 8), dtype=self.torch.int16, device=self.dev)
+        v = self.torch.zeros(max(total, 8), dtype=self.torch.int16, device=self.dev)
+        U.ukv_gather(self.pool, self.desc(), k.data_ptr(), v.data_ptr(), kv_off, self.stream())
+        return k.cpu().numpy().view(np.uint16), v.cpu().numpy().view(np.uint16), kv_off, sizes
