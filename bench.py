@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the unified-KV decode hot path on one MI355X.
+
+A step is one pass of the whole path over one mixed-service batch: grow every request by one
+token (host: page allocation from the library's free list), `ukv_append` (page-table patches +
+K/V scatter) and `ukv_decode_attention` (split-KV decode launch + merge launch).  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  value      whole-step KV throughput: sum over steps of ctx_len*token_bytes / wall time
+  roofline   the decode kernel alone: algorithmic KV bytes per launch / its mean duration,
+             measured with HIP events on the launch stream inside the timed region
+  cpu_baseline  the fp64 oracle timed on the host cores on a bounded sample of the same batch
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
+WORKLOAD_NAMES = {
+    1: "cfg1: one service 8/8 heads d=64, 8 requests, ctx U[64,512]",
+    2: "cfg2: Llama-2-7B-shaped layer 32/32 d=128, 64 requests, ctx U[128,4096], 4 GiB pool",
+    3: "cfg3: two services (32/32 d=128 + 40/40 d=128) sharing one pool, 128 requests, "
+       "ctx lognormal(median 1024, max 8192), 16 KiB pages interleaved, 4 GiB pool",
+    4: "cfg4: GQA mix (32/8 + 64/8, d=128), 256 requests, ctx lognormal(median 2048, max 32768), "
+       "churned 4 GiB pool",
+    5: "cfg5: four services (12/12 d=64, 32/32, 40/40, 32/8 d=128), 512 requests, "
+       "ctx lognormal(median 1024, max 16384), churned 8 GiB pool",
+}
+
+
+def read_traffic(cfg: int):
+    """HBM bytes per decode launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"decode_kernel_cfg{cfg}_pmc.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(batch, kv_bytes_total: int, target_s: float = 15.0):
+    """Time the oracle (attention) on a bounded sample of the batch's requests."""
+    import numpy as np
+    from oracle import oracle
+    n = batch.n_requests
+    order = np.random.default_rng(0).permutation(n)
+    tb = batch.token_bytes()
+    probe = order[:min(n, 8)]
+    t0 = time.perf_counter()
+    oracle.attention(batch, batch.pool, requests=probe)
+    dt = time.perf_counter() - t0
+    probe_bytes = int((batch.ctx_len[probe].astype(np.int64) * tb[probe]).sum())
+    rate = probe_bytes / max(dt, 1e-9)
+    want = rate * target_s
+    csum = np.cumsum(batch.ctx_len[order].astype(np.int64) * tb[order])
+    k = int(np.searchsorted(csum, want)) + 1
+    sample = order[:min(n, max(k, len(probe)))]
+    t0 = time.perf_counter()
+    oracle.attention(batch, batch.pool, requests=sample)
+    dt = time.perf_counter() - t0
+    sb = int((batch.ctx_len[sample].astype(np.int64) * tb[sample]).sum())
+    return {
+        "value": sb / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+        "sample": f"{len(sample)} of {n} requests of the same batch ({sb / 1e9:.3f} GB of KV, one attention "
+                  f"step, {dt:.1f} s, fp64, OpenMP over requests)",
+        "tokens_per_s": len(sample) / dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default: the two-service batch)")
+    ap.add_argument("--block", type=int, default=0, help="decode workgroup size override (256/512)")
+    ap.add_argument("--max-spans", type=int, default=0)
+    ap.add_argument("--min-span-bytes", type=int, default=0)
+    ap.add_argument("--heads-per-slice", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attention-only", action="store_true", help="skip grow+append in the step (diagnostic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; every GPU box here has one and the path uses no "
+              "collectives. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2504_15720_amd as U
+    from synth import make_config
+    from tests.ukv_harness import DeviceBatch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
+    t_gen = time.perf_counter()
+    # tables must have room for every step's new token
+    b = make_config(args.config, reserve_tokens=args.steps + args.warmup + 1)
+    t_gen = time.perf_counter() - t_gen
+    db = DeviceBatch(b, profile=True)
+    if args.block:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, args.block)
+    if args.max_spans:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MAX_SPANS, args.max_spans)
+    if args.min_span_bytes:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, args.min_span_bytes)
+    if args.heads_per_slice:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_HEADS_PER_SLICE, args.heads_per_slice)
+    db.resize_workspace()
+    rng = np.random.default_rng(1)
+    _, nk, nv = b.draw_step_inputs(rng)
+    db.set_new(nk, nv)
+
+    kv_bytes = []
+
+    def step():
+        if args.attention_only:
+            desc = db.desc()
+        else:
+            entry, ids = b.grow_one_token()
+            if ids.size:
+                lib_ids = U.ukv_pages_alloc(db.pool, ids.size)
+                assert np.array_equal(lib_ids, ids)
+            desc = db.desc(entry, ids)
+            db.append(desc)
+        db.decode(desc)
+        kv_bytes.append(b.kv_bytes())
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    U.ukv_profile_read(db.pool)          # drop warm-up kernel times
+    kv_bytes.clear()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = U.ukv_profile_read(db.pool)
+
+    total_kv = float(sum(kv_bytes))
+    kv_per_step = total_kv / args.steps
+    value = total_kv / wall / 1e9
+    dec_ms = prof.decode_ms / max(prof.n_decode, 1)
+    red_ms = prof.reduce_ms / max(prof.n_reduce, 1) if prof.n_reduce else 0.0
+    app_ms = prof.append_ms / max(prof.n_append, 1) if prof.n_append else 0.0
+    achieved = kv_per_step / (dec_ms * 1e-3) / 1e9
+    info, _ = U.ukv_plan_decode(db.pool, db.desc(), want_items=False)
+
+    line = {
+        "metric": "decode-attention KV GB/s, mixed-service batch, 1 GPU",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "n_requests": b.n_requests,
+                   "kv_bytes_per_step": int(kv_per_step), "pool_pages": b.n_pages,
+                   "stated_pool_pages": b.notes.get("stated_pages"), "page_bytes": b.page_bytes,
+                   "step": "attention only" if args.attention_only else "grow + append + attention",
+                   "kv_storage": "bf16", "decode_workgroups": info.n_spans, "work_items": info.n_items,
+                   "block_threads": U.ukv_get_param(db.pool, U.UKV_PARAM_BLOCK_THREADS)},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "tokens_per_s": round(b.n_requests * args.steps / wall, 1),
+        "kernel_ms": {"decode": round(dec_ms, 4), "reduce": round(red_ms, 4), "append": round(app_ms, 4)},
+        "attention_kernels_gbs": round(kv_per_step / ((dec_ms + red_ms) * 1e-3) / 1e9, 2),
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": read_traffic(args.config)},
+        "setup_s": round(t_gen, 1),
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(b, int(kv_per_step))
+        line["cpu_baseline"]["value"] = round(line["cpu_baseline"]["value"], 4)
+        line["cpu_baseline"]["tokens_per_s"] = round(line["cpu_baseline"]["tokens_per_s"], 2)
+    db.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,5 +52,21 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+CALIB_SRC = os.path.join(HERE, "calib", "hbm_calib.hip")
+CALIB_BIN = os.path.join(HERE, "calib", "hbm_calib")
+
+
+def build_calib() -> str:
+    """The streaming copy/read program used to calibrate the profiler's HBM byte counters."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument"] + \
+        DEVICE_FLAGS + [CALIB_SRC, "-o", CALIB_BIN]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on hbm_calib.hip:\n" + r.stdout)
+    return CALIB_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_calib())

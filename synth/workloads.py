@@ -384,8 +384,12 @@ CONFIGS: Dict[int, dict] = {
 }
 
 
-def make_config(index: int, *, mini: bool = False, fill_pool: bool = True, seed: Optional[int] = None) -> Batch:
-    """Draw workload `index` (1..5).  mini=True shrinks counts and lengths, same recipe."""
+def make_config(index: int, *, mini: bool = False, fill_pool: bool = True, seed: Optional[int] = None,
+                reserve_tokens: Optional[int] = None) -> Batch:
+    """Draw workload `index` (1..5).  mini=True shrinks counts and lengths, same recipe.
+
+    reserve_tokens: table entries are reserved for this many future tokens per request
+    (default: the workload's own decode steps, at least 4)."""
     c = dict(CONFIGS[index])
     if mini:
         c.update(c["mini"])
@@ -408,7 +412,8 @@ def make_config(index: int, *, mini: bool = False, fill_pool: bool = True, seed:
         n_pages = c["grow_pool_if_needed"]
     notes["pages_needed"] = need
     churn = dict(mix=mix, law=c["law"]) if c["churn"] else None
-    b = make_batch(services, sid, lens, n_pages, c["placement"], rng, reserve_tokens=c["steps"], churn=churn,
+    b = make_batch(services, sid, lens, n_pages, c["placement"], rng,
+                   reserve_tokens=max(c["steps"], 4) if reserve_tokens is None else reserve_tokens, churn=churn,
                    fill_pool=fill_pool, pool_seed=seed + 1000, name=c["name"] + ("-mini" if mini else ""))
     b.notes.update(notes)
     b.notes["steps"] = c["steps"]
