@@ -26,7 +26,7 @@
  *     work and return without synchronising.  One pool must be driven from one stream at
  *     a time: calls on the same pool share staging and scratch buffers.
  *   - The library never allocates or frees the pool memory itself.  It owns its host
- *     object, the free list, pinned staging buffers and a small device scratch.
+ *     object, the free list and pinned, device-mapped staging buffers (per-call records).
  *   - There is no CPU fallback: without a usable HIP device the compute calls fail with
  *     UKV_EHIP.
  */
@@ -132,7 +132,8 @@ size_t ukv_decode_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests);
  *   out[i][a][:] = sum_t softmax_t(scale * q[i][a] . K[t][a/G]) * V[t][a/G],  t < ctx_len[i],
  * fp32 accumulation over bf16 inputs, fp32 output; ctx_len == 0 gives zeros.  Bytes of the
  * pool past ctx_len never influence the result.  The batch is cut into token ranges that
- * run as one split-KV launch over all services plus a merge launch.
+ * run as one split-KV launch over all services; the workgroup that finishes a cut request
+ * last merges its partial results (or a second launch does, see UKV_PARAM_FUSED_MERGE).
  * workspace: DEVICE, 256-byte aligned, ws_bytes >= ukv_decode_workspace_bytes(); else UKV_ENOSPC.
  * Uses service_id, ctx_len, table_off, page_table, q, q_off, out, out_off. */
 int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes,
@@ -163,6 +164,7 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_BLOCK_THREADS 3    /* 256 or 512 */
 #define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
 #define UKV_PARAM_PROFILE 5          /* 1 = time kernels with HIP events (see ukv_profile_read) */
+#define UKV_PARAM_FUSED_MERGE 6      /* 1 (default) = merge partials inside the decode launch; 0 = second launch */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
 int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 

@@ -2,6 +2,7 @@
 // WRITE_SIZE counters to bytes and (2) show what a simple reader reaches on this GPU.
 //   hbm_calib copy <MiB> [iters]   : out[i] = in[i], reads N and writes N bytes per launch
 //   hbm_calib read <MiB> [iters]   : every lane sums its 128-bit loads; one 4-byte store per workgroup
+//   hbm_calib readnt <MiB> [iters] : the same with non-temporal (streaming) loads
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -23,12 +24,21 @@ __global__ void __launch_bounds__(256) copy_kernel(const uint4 *__restrict__ in,
         out[i] = in[i];
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld(const uint4 *p) {
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
+    return NT ? __builtin_nontemporal_load(q) : *q;
+}
+
+template <bool NT>
 __global__ void __launch_bounds__(256) read_kernel(const uint4 *__restrict__ in, unsigned *__restrict__ out, size_t n) {
     const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
     unsigned acc = 0;
     size_t i = ((size_t)blockIdx.x * blockDim.x) * 4 + threadIdx.x;
     for (; i + 3 * 256 < n; i += stride) {
-        const uint4 a = in[i], b = in[i + 256], c = in[i + 512], d = in[i + 768];
+        const u32x4 a = ld<NT>(in + i), b = ld<NT>(in + i + 256), c = ld<NT>(in + i + 512), d = ld<NT>(in + i + 768);
         acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     __shared__ unsigned sh[256];
@@ -44,10 +54,11 @@ __global__ void __launch_bounds__(256) read_kernel(const uint4 *__restrict__ in,
 
 int main(int argc, char **argv) {
     if (argc < 3) {
-        std::fprintf(stderr, "usage: hbm_calib copy|read <MiB> [iters] [workgroups]\n");
+        std::fprintf(stderr, "usage: hbm_calib copy|read|readnt <MiB> [iters] [workgroups]\n");
         return 2;
     }
     const bool copy = std::strcmp(argv[1], "copy") == 0;
+    const bool nt = std::strcmp(argv[1], "readnt") == 0;
     const size_t bytes = (size_t)std::atoll(argv[2]) << 20;
     const int iters = argc > 3 ? std::atoi(argv[3]) : 10;
     const int wgs = argc > 4 ? std::atoi(argv[4]) : 256 * 16;
@@ -68,8 +79,10 @@ int main(int argc, char **argv) {
         CHECK(hipEventRecord(a, 0));
         if (copy)
             hipLaunchKernelGGL(copy_kernel, dim3(wgs), dim3(256), 0, 0, in, out, n);
+        else if (nt)
+            hipLaunchKernelGGL(read_kernel<true>, dim3(wgs), dim3(256), 0, 0, in, (unsigned *)out, n);
         else
-            hipLaunchKernelGGL(read_kernel, dim3(wgs), dim3(256), 0, 0, in, (unsigned *)out, n);
+            hipLaunchKernelGGL(read_kernel<false>, dim3(wgs), dim3(256), 0, 0, in, (unsigned *)out, n);
         CHECK(hipGetLastError());
         CHECK(hipEventRecord(b, 0));
         CHECK(hipEventSynchronize(b));
@@ -82,7 +95,7 @@ int main(int argc, char **argv) {
     }
     const double moved = copy ? 2.0 * bytes : (double)bytes;
     std::printf("%s bytes_read=%zu bytes_written=%zu iters=%d mean_ms=%.4f best_ms=%.4f mean_GBs=%.1f best_GBs=%.1f\n",
-                copy ? "copy" : "read", bytes, copy ? bytes : (size_t)wgs * 4, iters, sum / iters, best,
+                copy ? "copy" : (nt ? "readnt" : "read"), bytes, copy ? bytes : (size_t)wgs * 4, iters, sum / iters, best,
                 moved / (sum / iters * 1e-3) / 1e9, moved / (best * 1e-3) / 1e9);
     CHECK(hipFree(in));
     CHECK(hipFree(out));

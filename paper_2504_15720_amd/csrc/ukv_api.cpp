@@ -1,6 +1,7 @@
 // C-ABI entry points that enqueue device work: append, decode attention, gather.
-// Host side only marshals: it plans, stages the plan in pinned memory, copies it with one
-// asynchronous transfer and launches the kernels on the caller's stream.
+// Host side only marshals: it plans, writes the plan into a pinned, device-mapped staging slot,
+// and launches the kernels on the caller's stream (a small copy kernel moves the decode plan
+// into the workspace; the append and gather kernels read their few records in place).
 #include <algorithm>
 #include <cstring>
 
@@ -39,43 +40,28 @@ int stage_acquire(ukv_pool *p, size_t bytes, ukv_pool::Stage **out) {
         st.host = nullptr;
         st.cap = 0;
         const size_t cap = std::max<size_t>(align_up(bytes * 2, 4096), 64 * 1024);
-        HIP_TRY(hipHostMalloc(&st.host, cap, hipHostMallocDefault), "hipHostMalloc");
+        HIP_TRY(hipHostMalloc(&st.host, cap, hipHostMallocMapped), "hipHostMalloc");
+        HIP_TRY(hipHostGetDevicePointer(&st.mapped, st.host, 0), "hipHostGetDevicePointer");
         st.cap = cap;
     }
     *out = &st;
     return UKV_OK;
 }
 
-int stage_submit(ukv_pool::Stage *st, void *dst, size_t bytes, hipStream_t s) {
-    HIP_TRY(hipMemcpyAsync(dst, st->host, bytes, hipMemcpyHostToDevice, s), "hipMemcpyAsync(plan)");
+// The slot may be rewritten once everything enqueued so far (its readers included) has run.
+int stage_release_after(ukv_pool::Stage *st, hipStream_t s) {
     HIP_TRY(hipEventRecord(st->ev, s), "hipEventRecord(staging)");
     st->pending = true;
     return UKV_OK;
 }
 
-int scratch_reserve(ukv_pool *p, size_t bytes, hipStream_t s) {
-    if (p->dev_scratch_cap >= bytes)
-        return UKV_OK;
-    if (p->dev_scratch) {
-        HIP_TRY(hipStreamSynchronize(s), "hipStreamSynchronize");
-        HIP_TRY(hipFree(p->dev_scratch), "hipFree");
-        p->dev_scratch = nullptr;
-        p->dev_scratch_cap = 0;
-    }
-    const size_t cap = std::max<size_t>(align_up(bytes * 2, 4096), 256 * 1024);
-    HIP_TRY(hipMalloc(&p->dev_scratch, cap), "hipMalloc(scratch)");
-    p->dev_scratch_cap = cap;
-    return UKV_OK;
-}
-
-// Profiling: a pair of events around one kernel launch.
-struct ProfScope {
+// Profiling: the kernel's own start/stop timestamps, attached to its dispatch (no extra
+// barriers on the stream).  get() hands out a pair when profiling is on, else nulls.
+struct ProfPair {
     ukv_pool *p;
-    hipStream_t s;
     int which;
-    ukv_pool::EvPair ev{};
-    bool on = false;
-    int begin() {
+    ukv_pool::EvPair ev{nullptr, nullptr, 0};
+    int get() {
         if (!p->tun.profile)
             return UKV_OK;
         if (!p->ev_free.empty()) {
@@ -86,21 +72,16 @@ struct ProfScope {
             HIP_TRY(hipEventCreate(&ev.b), "hipEventCreate");
         }
         ev.which = which;
-        HIP_TRY(hipEventRecord(ev.a, s), "hipEventRecord");
-        on = true;
         return UKV_OK;
     }
-    int end() {
-        if (!on)
-            return UKV_OK;
-        HIP_TRY(hipEventRecord(ev.b, s), "hipEventRecord");
-        p->ev_used.push_back(ev);
-        return UKV_OK;
+    void done() {
+        if (ev.a)
+            p->ev_used.push_back(ev);
     }
 };
 
 struct BlobLayout {
-    size_t classes, seqs, items, spans, reduce, total;
+    size_t classes, seqs, items, spans, reduce, counters, total;
 };
 
 BlobLayout blob_layout(size_t n_seqs, size_t n_items, size_t n_spans, size_t n_reduce) {
@@ -116,6 +97,8 @@ BlobLayout blob_layout(size_t n_seqs, size_t n_items, size_t n_spans, size_t n_r
     o = align_up(o + (n_spans + 1) * sizeof(uint32_t));
     b.reduce = o;
     o = align_up(o + n_reduce * sizeof(ReduceRec));
+    b.counters = o;
+    o = align_up(o + n_seqs * sizeof(uint32_t));
     b.total = o;
     return b;
 }
@@ -223,8 +206,9 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
     std::memcpy(h + L.spans, plan.span_first.data(), plan.span_first.size() * sizeof(uint32_t));
     if (!plan.reduce.empty())
         std::memcpy(h + L.reduce, plan.reduce.data(), plan.reduce.size() * sizeof(ReduceRec));
-    rc = stage_submit(st, workspace, L.total, s);
-    if (rc != UKV_OK)
+    std::memset(h + L.counters, 0, L.total - L.counters);
+    HIP_TRY(launch_stage_copy(workspace, st->mapped, L.total, s), "launch plan upload");
+    if ((rc = stage_release_after(st, s)) != UKV_OK)
         return rc;
 
     unsigned char *w = (unsigned char *)workspace;
@@ -239,24 +223,25 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
     a.items = (const Item *)(w + L.items);
     a.span_first = (const uint32_t *)(w + L.spans);
     a.partials = (float *)(w + part_off);
+    const bool fused = p->tun.fused_merge != 0;
+    a.counters = fused ? (uint32_t *)(w + L.counters) : nullptr;
 
     {
-        ProfScope ps{p, s, 0};
-        if ((rc = ps.begin()) != UKV_OK)
+        ProfPair pp{p, 0};
+        if ((rc = pp.get()) != UKV_OK)
             return rc;
-        HIP_TRY(launch_decode(a, n_spans, (uint32_t)p->tun.block_threads, s), "launch decode kernel");
-        if ((rc = ps.end()) != UKV_OK)
-            return rc;
+        HIP_TRY(launch_decode(a, n_spans, (uint32_t)p->tun.block_threads, s, pp.ev.a, pp.ev.b),
+                "launch decode kernel");
+        pp.done();
     }
-    if (!plan.reduce.empty()) {
-        ProfScope ps{p, s, 1};
-        if ((rc = ps.begin()) != UKV_OK)
+    if (!fused && !plan.reduce.empty()) {
+        ProfPair pp{p, 1};
+        if ((rc = pp.get()) != UKV_OK)
             return rc;
         HIP_TRY(launch_reduce((const ReduceRec *)(w + L.reduce), (uint32_t)plan.reduce.size(),
-                              plan.max_reduce_heads, a.partials, a.out, s),
+                              plan.max_reduce_heads, a.partials, a.out, s, pp.ev.a, pp.ev.b),
                 "launch reduce kernel");
-        if ((rc = ps.end()) != UKV_OK)
-            return rc;
+        pp.done();
     }
     return UKV_OK;
 }
@@ -308,9 +293,7 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
     const size_t off_pp = o;
     o = align_up(o + (size_t)b->n_patches * sizeof(int32_t));
     const size_t total = o;
-    int rc = scratch_reserve(p, total, s);
-    if (rc != UKV_OK)
-        return rc;
+    int rc;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -323,19 +306,19 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
         std::memcpy(h + off_pe, b->patch_entry, (size_t)b->n_patches * sizeof(uint64_t));
         std::memcpy(h + off_pp, b->patch_page, (size_t)b->n_patches * sizeof(int32_t));
     }
-    if ((rc = stage_submit(st, p->dev_scratch, total, s)) != UKV_OK)
-        return rc;
-    unsigned char *d = (unsigned char *)p->dev_scratch;
-    ProfScope ps{p, s, 2};
-    if ((rc = ps.begin()) != UKV_OK)
-        return rc;
+    // the records are small: the kernels read them straight from the pinned, device-mapped slot
+    unsigned char *d = (unsigned char *)st->mapped;
     HIP_TRY(launch_patch(b->page_table, (const uint64_t *)(d + off_pe), (const int32_t *)(d + off_pp), b->n_patches,
                          s),
             "launch patch kernel");
+    ProfPair pp{p, 2};
+    if ((rc = pp.get()) != UKV_OK)
+        return rc;
     HIP_TRY(launch_append(p->base, p->log2_page, b->page_table, (const AppendRec *)(d + off_recs), n,
-                          (const ClassRec *)(d + off_cls), b->new_k, b->new_v, s),
+                          (const ClassRec *)(d + off_cls), b->new_k, b->new_v, s, pp.ev.a, pp.ev.b),
             "launch append kernel");
-    return ps.end();
+    pp.done();
+    return stage_release_after(st, s);
 }
 
 int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, const uint64_t *kv_off,
@@ -355,9 +338,7 @@ int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, co
     hipStream_t s = (hipStream_t)stream;
     const size_t off_recs = align_up(sizeof(ClassTable));
     const size_t total = align_up(off_recs + (size_t)n * sizeof(GatherRec));
-    int rc = scratch_reserve(p, total, s);
-    if (rc != UKV_OK)
-        return rc;
+    int rc;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -366,13 +347,11 @@ int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, co
     GatherRec *recs = (GatherRec *)(h + off_recs);
     for (uint32_t i = 0; i < n; ++i)
         recs[i] = GatherRec{b->table_off[i], kv_off[i], b->ctx_len[i], b->service_id[i]};
-    if ((rc = stage_submit(st, p->dev_scratch, total, s)) != UKV_OK)
-        return rc;
-    unsigned char *d = (unsigned char *)p->dev_scratch;
+    unsigned char *d = (unsigned char *)st->mapped;
     HIP_TRY(launch_gather(p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs), n,
                           (const ClassRec *)d, k_out, v_out, s),
             "launch gather kernel");
-    return UKV_OK;
+    return stage_release_after(st, s);
 }
 
 int ukv_profile_read(ukv_pool_t *p, ukv_profile_t *out) {

@@ -61,6 +61,7 @@ struct DecodeArgs {
     const Item *items;
     const uint32_t *span_first; // [n_spans + 1]
     float *partials;
+    uint32_t *counters; // per sequence: finished items (fused merge); null = merge in a second launch
 };
 
 struct ReduceRec {
@@ -84,14 +85,16 @@ struct GatherRec {
 };
 
 // ---- kernel launchers (ukv_kernels.hip) ----
-hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s);
+hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
+                         hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,
-                         float *out, hipStream_t s);
+                         float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s);
 hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                          const AppendRec *recs, uint32_t n, const ClassRec *classes, const void *new_k,
-                         const void *new_v, hipStream_t s);
+                         const void *new_v, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_gather(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                          const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_out, void *v_out,
                          hipStream_t s);
@@ -114,6 +117,7 @@ struct Tunables {
     int64_t block_threads = 256;
     int64_t heads_per_slice = 0;
     int64_t profile = 0;
+    int64_t fused_merge = 1;
 };
 
 void set_error(const std::string &msg);
@@ -134,9 +138,10 @@ struct ukv_pool {
     std::vector<int32_t> free_stack;
     std::vector<uint8_t> is_free;
 
-    // pinned staging ring + device scratch (created lazily on the first compute call)
+    // pinned, device-mapped staging ring (created lazily on the first compute call)
     struct Stage {
         void *host = nullptr;
+        void *mapped = nullptr; // device-side address of the same pinned memory
         size_t cap = 0;
         hipEvent_t ev = nullptr;
         bool pending = false;
@@ -144,8 +149,6 @@ struct ukv_pool {
     static constexpr int kStages = 8;
     Stage stage[kStages];
     int next_stage = 0;
-    void *dev_scratch = nullptr;
-    size_t dev_scratch_cap = 0;
 
     // profiling
     struct EvPair {

@@ -13,6 +13,7 @@
 // lines, and the lanes of a workgroup cover `hs` consecutive heads of `ti` consecutive
 // tokens, i.e. contiguous stretches of the request's byte stream inside 16 KiB pages.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "ukv_internal.h"
 
@@ -44,6 +45,14 @@ __device__ __forceinline__ float row_sum(float x) {
     if (LPR == 16)
         x += dpp_f<0x140>(x); // row_mirror
     return x;
+}
+
+// 128-bit load of K or V payload.  Every KV byte is used exactly once per launch, so the load
+// is marked non-temporal (streaming): it keeps the L2 for page tables, q and partials.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_kv(const uint4 *p) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -93,6 +102,57 @@ __device__ __forceinline__ void update(const float (&qf)[G][8], const uint4 (&kr
         }
         l[g] = fmaf(l[g], alpha, psum);
         m[g] = mx;
+    }
+}
+
+// Partials cross workgroups (and therefore XCDs, each with its own L2) inside one launch.  They
+// are written and read with device-scope relaxed atomics, which go through to the point of
+// coherence, so no cache-wide write-back/invalidate fence is needed: the writer waits for its
+// stores to complete before it counts the item, the reader starts after it has seen the count.
+__device__ __forceinline__ void st_part2(float *p, float a, float b) {
+    const uint64_t v = ((uint64_t)__float_as_uint(b) << 32) | __float_as_uint(a);
+    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_part2(const float *p) {
+    const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+}
+
+// Merge of the partials of one cut sequence (all its query heads), executed by the workgroup
+// that finished the sequence's last item:  with M = max_c m_c,
+//   out = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M).
+template <int NT>
+__device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_heads, uint32_t D, uint32_t q_head0) {
+    const float *base = a.partials + s.part_off;
+    const uint32_t chunks = D / 4, units = n_heads * chunks;
+    for (uint32_t u = threadIdx.x; u < units; u += NT) {
+        const uint32_t hq = u / chunks, c4 = u % chunks;
+        const float *ml = base + (uint64_t)n_heads * D + hq * 2;
+        float M = -INFINITY;
+        for (uint32_t c = 0; c < s.n_parts; ++c) {
+            const float2 p = ld_part2(ml + (uint64_t)c * s.part_stride);
+            if (p.y > 0.f)
+                M = fmaxf(M, p.x);
+        }
+        float L = 0.f;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t c = 0; c < s.n_parts; ++c) {
+            const float2 p = ld_part2(ml + (uint64_t)c * s.part_stride);
+            if (!(p.y > 0.f))
+                continue;
+            const float w = fast_exp2(p.x - M);
+            const float *xa = base + (uint64_t)c * s.part_stride + (uint64_t)hq * D + c4 * 4;
+            const float2 x0 = ld_part2(xa), x1 = ld_part2(xa + 2);
+            L = fmaf(p.y, w, L);
+            o.x = fmaf(x0.x, w, o.x);
+            o.y = fmaf(x0.y, w, o.y);
+            o.z = fmaf(x1.x, w, o.z);
+            o.w = fmaf(x1.y, w, o.w);
+        }
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        *reinterpret_cast<float4 *>(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4) =
+            make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
     }
 }
 
@@ -164,16 +224,16 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const uint4 *p = row_ptr(t + u * TI);
-                    kr[u] = p[0];
-                    vr[u] = p[LPR];
+                    kr[u] = ld_kv(p);
+                    vr[u] = ld_kv(p + LPR);
                 }
                 update<G, U, LPR>(qf, kr, vr, m, l, acc);
             }
             for (; t < w1; t += TI) {
                 uint4 kr[1], vr[1];
                 const uint4 *p = row_ptr(t);
-                kr[0] = p[0];
-                vr[0] = p[LPR];
+                kr[0] = ld_kv(p);
+                vr[0] = ld_kv(p + LPR);
                 update<G, 1, LPR>(qf, kr, vr, m, l, acc);
             }
         }
@@ -229,16 +289,27 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
                 dst[1] = make_float4(acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv);
             } else {
                 const uint32_t hq = hh * G + g;
-                float4 *dst = reinterpret_cast<float4 *>(pbase + (uint64_t)hq * D + lir * 8);
-                dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
-                dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
-                if (lir == 0) {
-                    float *ml = pbase + (uint64_t)HS * G * D + hq * 2;
-                    ml[0] = m[g];
-                    ml[1] = l[g];
-                }
+                float *dst = pbase + (uint64_t)hq * D + lir * 8;
+                st_part2(dst, acc[g][0], acc[g][1]);
+                st_part2(dst + 2, acc[g][2], acc[g][3]);
+                st_part2(dst + 4, acc[g][4], acc[g][5]);
+                st_part2(dst + 6, acc[g][6], acc[g][7]);
+                if (lir == 0)
+                    st_part2(pbase + (uint64_t)HS * G * D + hq * 2, m[g], l[g]);
             }
         }
+    }
+
+    // fused merge: the workgroup that completes a cut sequence last combines its partials
+    if (!direct && a.counters != nullptr) {
+        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this lane's partial stores have completed
+        __syncthreads();
+        uint32_t *flag = reinterpret_cast<uint32_t *>(tab);
+        if (tid == 0)
+            flag[0] = __hip_atomic_fetch_add(a.counters + it.seq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (flag[0] == s.n_parts - 1)
+            merge_parts<NT>(a, s, HS * G, D, s.head0 * G);
     }
 }
 
@@ -253,7 +324,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
         SeqRec s = a.seqs[it.seq];
         s.table_off = uni(s.table_off); s.q_off = uni(s.q_off); s.out_off = uni(s.out_off);
         s.part_off = uni(s.part_off); s.cls = uni(s.cls); s.head0 = uni(s.head0);
-        s.part_stride = uni(s.part_stride);
+        s.part_stride = uni(s.part_stride); s.n_parts = uni(s.n_parts);
         ClassRec c = a.classes[s.cls];
         c.token_bytes = uni(c.token_bytes); c.row_bytes = uni(c.row_bytes); c.hs = uni(c.hs); c.ti = uni(c.ti);
         c.kind = uni(c.kind); c.scale_log2e = uni(c.scale_log2e);
@@ -359,22 +430,40 @@ __global__ void __launch_bounds__(256) gather_kernel(const unsigned char *pool_b
     }
 }
 
+// Plan upload: copies 16-byte pieces from pinned, device-mapped host memory into the workspace.
+__global__ void __launch_bounds__(256) stage_copy_kernel(uint4 *dst, const uint4 *src, uint32_t n16) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n16)
+        dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------ launchers
-hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s) {
+// ev0/ev1 (may be null) receive the kernel's own start/stop timestamps.
+hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, hipStream_t s) {
+    const uint32_t n16 = (uint32_t)((bytes + 15) / 16);
+    if (n16 == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(stage_copy_kernel, dim3((n16 + 255) / 256), dim3(256), 0, s, static_cast<uint4 *>(dst),
+                       static_cast<const uint4 *>(src_mapped), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
+                         hipEvent_t ev0, hipEvent_t ev1) {
     if (n_spans == 0)
         return hipSuccess;
     if (block_threads == 512)
-        hipLaunchKernelGGL(decode_kernel<512>, dim3(n_spans), dim3(512), 0, s, a);
+        hipExtLaunchKernelGGL(decode_kernel<512>, dim3(n_spans), dim3(512), 0, s, ev0, ev1, 0, a);
     else
-        hipLaunchKernelGGL(decode_kernel<256>, dim3(n_spans), dim3(256), 0, s, a);
+        hipExtLaunchKernelGGL(decode_kernel<256>, dim3(n_spans), dim3(256), 0, s, ev0, ev1, 0, a);
     return hipGetLastError();
 }
 
 hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,
-                         float *out, hipStream_t s) {
+                         float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
-    hipLaunchKernelGGL(reduce_kernel, dim3(n_recs, max_heads), dim3(64), 0, s, recs, partials, out);
+    hipExtLaunchKernelGGL(reduce_kernel, dim3(n_recs, max_heads), dim3(64), 0, s, ev0, ev1, 0, recs, partials, out);
     return hipGetLastError();
 }
 
@@ -388,10 +477,10 @@ hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_
 
 hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                          const AppendRec *recs, uint32_t n, const ClassRec *classes, const void *new_k,
-                         const void *new_v, hipStream_t s) {
+                         const void *new_v, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     if (n == 0)
         return hipSuccess;
-    hipLaunchKernelGGL(append_kernel, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table, recs, classes,
+    hipExtLaunchKernelGGL(append_kernel, dim3(n), dim3(256), 0, s, ev0, ev1, 0, pool_base, log2_page, page_table, recs, classes,
                        static_cast<const uint16_t *>(new_k), static_cast<const uint16_t *>(new_v));
     return hipGetLastError();
 }

@@ -147,8 +147,6 @@ int ukv_pool_destroy(ukv_pool_t *p) {
             (void)hipEventDestroy(e.a);
             (void)hipEventDestroy(e.b);
         }
-    if (p->dev_scratch && hipFree(p->dev_scratch) != hipSuccess)
-        rc = UKV_EHIP;
     delete p;
     return rc;
 }
@@ -245,6 +243,9 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
     case UKV_PARAM_PROFILE:
         p->tun.profile = value ? 1 : 0;
         return UKV_OK;
+    case UKV_PARAM_FUSED_MERGE:
+        p->tun.fused_merge = value ? 1 : 0;
+        return UKV_OK;
     default:
         return fail(UKV_EINVAL, "unknown parameter");
     }
@@ -259,6 +260,7 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_BLOCK_THREADS: *value = p->tun.block_threads; return UKV_OK;
     case UKV_PARAM_HEADS_PER_SLICE: *value = p->tun.heads_per_slice; return UKV_OK;
     case UKV_PARAM_PROFILE: *value = p->tun.profile; return UKV_OK;
+    case UKV_PARAM_FUSED_MERGE: *value = p->tun.fused_merge; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

@@ -76,8 +76,11 @@ def test_mini_configs_match_oracle(cfg, block):
         db.resize_workspace()
         _check_attention(db, b, "whole-request items")
         _check_gather(db, b)
-        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 48 * 1024)      # many cuts -> reduce pass
-        _check_attention(db, b, "cut into many items")
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 48 * 1024)      # many cuts -> merge of partials
+        _check_attention(db, b, "cut into many items, merge fused into the decode launch")
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
+        _check_attention(db, b, "cut into many items, merge in a second launch")
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)
         steps = max(1, int(b.notes["steps"]))
         _decode_steps(db, b, min(steps, 4), seed=cfg)
     finally:
