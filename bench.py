@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--max-spans", type=int, default=0)
     ap.add_argument("--min-span-bytes", type=int, default=0)
     ap.add_argument("--heads-per-slice", type=int, default=0)
+    ap.add_argument("--slots", type=int, default=0)
+    ap.add_argument("--no-taper", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="skip grow+append in the step (diagnostic)")
     args = ap.parse_args()
@@ -111,6 +113,10 @@ def main():
         U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, args.min_span_bytes)
     if args.heads_per_slice:
         U.ukv_set_param(db.pool, U.UKV_PARAM_HEADS_PER_SLICE, args.heads_per_slice)
+    if args.slots:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_SLOTS, args.slots)
+    if args.no_taper:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_TAPER, 0)
     db.resize_workspace()
     rng = np.random.default_rng(1)
     _, nk, nv = b.draw_step_inputs(rng)

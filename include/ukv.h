@@ -165,6 +165,8 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
 #define UKV_PARAM_PROFILE 5          /* 1 = time kernels with HIP events (see ukv_profile_read) */
 #define UKV_PARAM_FUSED_MERGE 6      /* 1 (default) = merge partials inside the decode launch; 0 = second launch */
+#define UKV_PARAM_SLOTS 7            /* decode workgroups resident at once; 0 (default) = ask the device */
+#define UKV_PARAM_TAPER 8            /* 1 (default) = spans shrink batch by batch; 0 = equal spans */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
 int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 

@@ -184,6 +184,12 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
         return UKV_EINVAL;
     }
     hipStream_t s = (hipStream_t)stream;
+    if (p->tun.slots_auto) { // once per pool (and after a block-size change): what the device keeps resident
+        const int r = decode_resident_workgroups((uint32_t)p->tun.block_threads);
+        if (r > 0)
+            p->tun.slots = r;
+        p->tun.slots_auto = false;
+    }
     Plan plan;
     int rc = build_plan(p, b, plan);
     if (rc != UKV_OK)

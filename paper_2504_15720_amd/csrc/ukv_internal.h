@@ -85,6 +85,7 @@ struct GatherRec {
 };
 
 // ---- kernel launchers (ukv_kernels.hip) ----
+int decode_resident_workgroups(uint32_t block_threads); // occupancy x compute units; 0 on failure
 hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1);
@@ -114,10 +115,13 @@ struct Plan {
 struct Tunables {
     int64_t max_spans = 2048;
     int64_t min_span_bytes = 512 * 1024;
-    int64_t block_threads = 256;
+    int64_t block_threads = 512;
     int64_t heads_per_slice = 0;
     int64_t profile = 0;
     int64_t fused_merge = 1;
+    int64_t slots = 512; // workgroups resident at once (refreshed from the device at the first launch)
+    int64_t taper = 1;
+    bool slots_auto = true;
 };
 
 void set_error(const std::string &msg);

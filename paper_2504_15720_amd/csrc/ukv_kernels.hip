@@ -122,37 +122,71 @@ __device__ __forceinline__ float2 ld_part2(const float *p) {
 // Merge of the partials of one cut sequence (all its query heads), executed by the workgroup
 // that finished the sequence's last item:  with M = max_c m_c,
 //   out = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M).
+// The (m, l) pairs are staged in LDS a chunk of parts at a time, so that each output element
+// only streams its accumulators, several parts in flight; chunks combine by the same rule.
 template <int NT>
-__device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_heads, uint32_t D, uint32_t q_head0) {
+__device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_heads, uint32_t D, uint32_t q_head0,
+                            float *lds) {
+    constexpr uint32_t kPairs = NT * 4; // (m, l) pairs that fit the LDS buffer
     const float *base = a.partials + s.part_off;
-    const uint32_t chunks = D / 4, units = n_heads * chunks;
-    for (uint32_t u = threadIdx.x; u < units; u += NT) {
-        const uint32_t hq = u / chunks, c4 = u % chunks;
-        const float *ml = base + (uint64_t)n_heads * D + hq * 2;
-        float M = -INFINITY;
-        for (uint32_t c = 0; c < s.n_parts; ++c) {
-            const float2 p = ld_part2(ml + (uint64_t)c * s.part_stride);
-            if (p.y > 0.f)
-                M = fmaxf(M, p.x);
-        }
-        float L = 0.f;
+    const float *ml_base = base + (uint64_t)n_heads * D;
+    const uint32_t chunks4 = D / 4, units = n_heads * chunks4;
+    const uint32_t cmax = kPairs / n_heads;
+    for (uint32_t u0 = 0; u0 < units; u0 += NT) { // workgroup-uniform
+        const uint32_t u = u0 + threadIdx.x;
+        const bool act = u < units;
+        const uint32_t hq = act ? u / chunks4 : 0, c4 = act ? u % chunks4 : 0;
+        float Mr = -INFINITY, Lr = 0.f;
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (uint32_t c = 0; c < s.n_parts; ++c) {
-            const float2 p = ld_part2(ml + (uint64_t)c * s.part_stride);
-            if (!(p.y > 0.f))
+        for (uint32_t c0 = 0; c0 < s.n_parts; c0 += cmax) {
+            const uint32_t nc = min(cmax, s.n_parts - c0);
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < nc * n_heads; i += NT) {
+                const uint32_t c = i / n_heads, h = i % n_heads;
+                const float2 p = ld_part2(ml_base + (uint64_t)(c0 + c) * s.part_stride + h * 2);
+                lds[2 * i] = p.y > 0.f ? p.x : -INFINITY; // an empty part carries no weight
+                lds[2 * i + 1] = p.y;
+            }
+            __syncthreads();
+            if (!act)
                 continue;
-            const float w = fast_exp2(p.x - M);
-            const float *xa = base + (uint64_t)c * s.part_stride + (uint64_t)hq * D + c4 * 4;
-            const float2 x0 = ld_part2(xa), x1 = ld_part2(xa + 2);
-            L = fmaf(p.y, w, L);
-            o.x = fmaf(x0.x, w, o.x);
-            o.y = fmaf(x0.y, w, o.y);
-            o.z = fmaf(x1.x, w, o.z);
-            o.w = fmaf(x1.y, w, o.w);
+            float Mc = Mr;
+            for (uint32_t c = 0; c < nc; ++c)
+                Mc = fmaxf(Mc, lds[2 * (c * n_heads + hq)]);
+            if (Mc == -INFINITY)
+                continue;
+            const float f = fast_exp2(Mr - Mc);
+            Lr *= f;
+            o.x *= f; o.y *= f; o.z *= f; o.w *= f;
+            Mr = Mc;
+            const float *xa = base + (uint64_t)c0 * s.part_stride + (uint64_t)hq * D + c4 * 4;
+            for (uint32_t c = 0; c < nc; c += 4) {
+                float2 x0[4], x1[4];
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k) {
+                    const uint32_t cc = min(c + k, nc - 1); // clamp: a repeated load, zero weight below
+                    x0[k] = ld_part2(xa + (uint64_t)cc * s.part_stride);
+                    x1[k] = ld_part2(xa + (uint64_t)cc * s.part_stride + 2);
+                }
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k) {
+                    if (c + k >= nc)
+                        break;
+                    const uint32_t i = (c + k) * n_heads + hq;
+                    const float w = fast_exp2(lds[2 * i] - Mr);
+                    Lr = fmaf(lds[2 * i + 1], w, Lr);
+                    o.x = fmaf(x0[k].x, w, o.x);
+                    o.y = fmaf(x0[k].y, w, o.y);
+                    o.z = fmaf(x1[k].x, w, o.z);
+                    o.w = fmaf(x1[k].y, w, o.w);
+                }
+            }
         }
-        const float inv = L > 0.f ? 1.f / L : 0.f;
-        *reinterpret_cast<float4 *>(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4) =
-            make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+        if (act) {
+            const float inv = Lr > 0.f ? 1.f / Lr : 0.f;
+            *reinterpret_cast<float4 *>(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4) =
+                make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+        }
     }
 }
 
@@ -309,7 +343,7 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
             flag[0] = __hip_atomic_fetch_add(a.counters + it.seq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (flag[0] == s.n_parts - 1)
-            merge_parts<NT>(a, s, HS * G, D, s.head0 * G);
+            merge_parts<NT>(a, s, HS * G, D, s.head0 * G, mbuf);
     }
 }
 
@@ -438,6 +472,19 @@ __global__ void __launch_bounds__(256) stage_copy_kernel(uint4 *dst, const uint4
 }
 
 // ------------------------------------------------------------------ launchers
+int decode_resident_workgroups(uint32_t block_threads) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return 0;
+    hipError_t e = block_threads == 512
+                       ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<512>, 512, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<256>, 256, 0);
+    if (e != hipSuccess || per_cu <= 0 || cus <= 0)
+        return 0;
+    return per_cu * cus;
+}
+
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps.
 hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, hipStream_t s) {
     const uint32_t n16 = (uint32_t)((bytes + 15) / 16);

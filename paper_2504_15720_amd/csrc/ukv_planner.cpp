@@ -72,9 +72,34 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         return UKV_OK;
     }
 
-    uint64_t n_spans_target = total_cost / (uint64_t)p->tun.min_span_bytes;
-    n_spans_target = std::max<uint64_t>(1, std::min<uint64_t>(n_spans_target, (uint64_t)p->tun.max_spans));
-    const uint64_t C = (total_cost + n_spans_target - 1) / n_spans_target;
+    // Span sizes.  Workgroups are dispatched in order onto `slots` resident positions, so equal
+    // spans would leave the last round partly empty.  With tapering, each batch of `slots` spans
+    // takes half of the remaining cost (factoring self-scheduling): rounds shrink geometrically
+    // down to min_span_bytes and the tail of the launch is one small round.
+    std::vector<uint64_t> targets;
+    {
+        const uint64_t min_span = (uint64_t)p->tun.min_span_bytes, max_spans = (uint64_t)p->tun.max_spans;
+        const uint64_t slots = (uint64_t)std::max<int64_t>(1, p->tun.slots);
+        if (!p->tun.taper) {
+            uint64_t n = std::max<uint64_t>(1, std::min<uint64_t>(total_cost / min_span, max_spans));
+            targets.assign(1, (total_cost + n - 1) / n);
+        } else {
+            uint64_t R = total_cost;
+            while (R > 0 && targets.size() < max_spans) {
+                const uint64_t c = std::max<uint64_t>(min_span, R / (2 * slots));
+                uint64_t batch = std::min<uint64_t>(slots, (R + c - 1) / c);
+                batch = std::min<uint64_t>(batch, max_spans - targets.size());
+                targets.insert(targets.end(), batch, c);
+                R -= std::min<uint64_t>(R, batch * c);
+            }
+            if (R > 0) { // span budget exhausted: spread what is left over the last batch
+                const uint64_t tail = std::min<uint64_t>(slots, targets.size());
+                for (uint64_t j = targets.size() - tail; j < targets.size(); ++j)
+                    targets[j] += (R + tail - 1) / tail;
+            }
+        }
+    }
+    uint64_t C = targets[0];
 
     std::vector<uint32_t> seq_first_item(plan.seqs.size() + 1, 0);
     plan.span_first.push_back(0);
@@ -83,6 +108,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         if (plan.span_first.back() != plan.items.size())
             plan.span_first.push_back((uint32_t)plan.items.size());
         fill = carry ? std::max<int64_t>(0, fill - (int64_t)C) : 0;
+        C = targets[std::min<size_t>(plan.span_first.size() - 1, targets.size() - 1)];
     };
     for (uint32_t k = 0; k < plan.seqs.size(); ++k) {
         const SeqRec &s = plan.seqs[k];

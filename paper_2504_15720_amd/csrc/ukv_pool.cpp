@@ -20,32 +20,37 @@ static int fail(int code, const std::string &msg) {
 // Choose how a workgroup of `block_threads` lanes covers a service's token rows.
 // A row (one kv head of one token) is read by head_dim/8 lanes, 16 bytes each, so a workgroup
 // has NG = block_threads / (head_dim/8) row groups: hs kv heads times ti tokens per iteration.
-// Prefer full occupancy of the groups, then the widest slice (longest contiguous reads).
+// Among the divisors of n_kv_heads that keep (nearly) all groups busy, take the slice closest
+// to 4 KiB of contiguous stream per token: wide enough for full-line streaming reads, narrow
+// enough that a request splits into several independent sequences whose partial results are
+// small and are merged by different workgroups.
 static void choose_slicing(uint32_t n_kv, uint32_t d, uint32_t block_threads, int64_t forced, uint32_t *hs_out,
                            uint32_t *ti_out) {
     const uint32_t ng = block_threads / (d / 8);
-    uint32_t best_hs = 1, best_ti = ng;
-    double best_util = -1.0;
     if (forced > 0 && forced <= (int64_t)ng && n_kv % (uint32_t)forced == 0) {
         *hs_out = (uint32_t)forced;
         *ti_out = ng / (uint32_t)forced;
         return;
     }
+    const double want = 4096.0 / (4.0 * d); // heads per 4 KiB
+    uint32_t best_hs = 1;
+    double best_util = -1.0, best_dist = 0.0;
     for (uint32_t hs = 1; hs <= n_kv && hs <= ng; ++hs) {
         if (n_kv % hs)
             continue;
-        const uint32_t ti = ng / hs;
-        double util = (double)(hs * ti) / ng;
+        double util = (double)(hs * (ng / hs)) / ng;
         if (util > 0.9)
-            util = 1.0; // close enough: let the wider slice win
-        if (util > best_util + 1e-9 || (std::fabs(util - best_util) < 1e-9 && hs > best_hs)) {
+            util = 1.0;
+        const double dist = std::fabs(std::log((double)hs / want));
+        if (util > best_util + 1e-9 || (std::fabs(util - best_util) < 1e-9 && dist < best_dist - 1e-9) ||
+            (std::fabs(util - best_util) < 1e-9 && std::fabs(dist - best_dist) < 1e-9 && hs > best_hs)) {
             best_util = util;
+            best_dist = dist;
             best_hs = hs;
-            best_ti = ti;
         }
     }
     *hs_out = best_hs;
-    *ti_out = best_ti;
+    *ti_out = ng / best_hs;
 }
 
 int derive_classes(ukv_pool *p) {
@@ -234,6 +239,7 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
         if (value != 256 && value != 512)
             return fail(UKV_EINVAL, "block_threads must be 256 or 512");
         p->tun.block_threads = value;
+        p->tun.slots_auto = true;
         return derive_classes(p);
     case UKV_PARAM_HEADS_PER_SLICE:
         if (value < 0)
@@ -245,6 +251,16 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
         return UKV_OK;
     case UKV_PARAM_FUSED_MERGE:
         p->tun.fused_merge = value ? 1 : 0;
+        return UKV_OK;
+    case UKV_PARAM_SLOTS:
+        if (value < 0 || value > (1 << 20))
+            return fail(UKV_EINVAL, "slots out of range");
+        p->tun.slots_auto = value == 0;
+        if (value > 0)
+            p->tun.slots = value;
+        return UKV_OK;
+    case UKV_PARAM_TAPER:
+        p->tun.taper = value ? 1 : 0;
         return UKV_OK;
     default:
         return fail(UKV_EINVAL, "unknown parameter");
@@ -261,6 +277,8 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_HEADS_PER_SLICE: *value = p->tun.heads_per_slice; return UKV_OK;
     case UKV_PARAM_PROFILE: *value = p->tun.profile; return UKV_OK;
     case UKV_PARAM_FUSED_MERGE: *value = p->tun.fused_merge; return UKV_OK;
+    case UKV_PARAM_SLOTS: *value = p->tun.slots; return UKV_OK;
+    case UKV_PARAM_TAPER: *value = p->tun.taper; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

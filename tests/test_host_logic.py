@@ -137,11 +137,23 @@ def test_plan_full_size_configs_balance_and_fit_workspace():
     for cfg in (3, 4):
         b = make_config(cfg, fill_pool=False)
         p = _pool(b.services, n_pages=b.n_pages)
-        info, items = _check_plan(b, p)
         tb = np.array([U.ukv_pool_info(p, int(s)).head_row_bytes for s in b.service_id], np.int64)
-        cost = (items[:, 4] - items[:, 3]).astype(np.int64) * items[:, 2] * tb[items[:, 0]]
-        per_span = np.bincount(items[:, 5], weights=cost, minlength=info.n_spans)
+
+        def per_span_cost():
+            info, items = _check_plan(b, p)
+            cost = (items[:, 4] - items[:, 3]).astype(np.int64) * items[:, 2] * tb[items[:, 0]]
+            return np.bincount(items[:, 5], weights=cost, minlength=info.n_spans)
+
+        U.ukv_set_param(p, U.UKV_PARAM_TAPER, 0)          # equal spans
+        per_span = per_span_cost()
         assert per_span.max() < 1.25 * per_span.mean()
+        U.ukv_set_param(p, U.UKV_PARAM_TAPER, 1)          # batches of `slots` spans, each half the rest
+        U.ukv_set_param(p, U.UKV_PARAM_SLOTS, 512)
+        per_span = per_span_cost()
+        first, second = per_span[:512], per_span[512:1024]
+        assert 0.4 < second.mean() / first.mean() < 0.6
+        assert per_span[-256:].mean() < 0.5 * first.mean()
+        assert abs(first.sum() / per_span.sum() - 0.5) < 0.05
         U.ukv_pool_destroy(p)
 
 
@@ -162,10 +174,11 @@ def test_plan_handles_empty_contexts_and_bad_batches():
 
 def test_params_roundtrip_and_validation():
     p = _pool([SHAPES["13b"]])
-    assert U.ukv_get_param(p, U.UKV_PARAM_BLOCK_THREADS) == 256
+    assert U.ukv_get_param(p, U.UKV_PARAM_BLOCK_THREADS) == 512
+    assert U.ukv_pool_info(p, 0).heads_per_slice == 8 and U.ukv_pool_info(p, 0).token_lanes == 4
+    U.ukv_set_param(p, U.UKV_PARAM_BLOCK_THREADS, 256)
     assert U.ukv_pool_info(p, 0).heads_per_slice == 8 and U.ukv_pool_info(p, 0).token_lanes == 2
     U.ukv_set_param(p, U.UKV_PARAM_BLOCK_THREADS, 512)
-    assert U.ukv_pool_info(p, 0).heads_per_slice * U.ukv_pool_info(p, 0).token_lanes <= 32
     U.ukv_set_param(p, U.UKV_PARAM_HEADS_PER_SLICE, 20)
     assert U.ukv_pool_info(p, 0).heads_per_slice == 20
     with pytest.raises(U.UkvError):
