@@ -35,13 +35,16 @@ WORKLOAD_NAMES = {
 
 
 def read_traffic(cfg: int):
-    """HBM bytes per decode launch from the committed rocprofv3 --pmc summary, if there is one."""
+    """HBM bytes per decode launch from the committed rocprofv3 --pmc summary, if there is one
+    (bytes of the profiled run, and their ratio to that run's algorithmic bytes)."""
     path = os.path.join(ROOT, "profiles", f"decode_kernel_cfg{cfg}_pmc.txt")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        text = open(path).read()
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+        r = re.search(r"^traffic_over_algorithmic:\s*([0-9.eE+]+)", text, re.M)
+        return (float(m.group(1)) if m else None), (float(r.group(1)) if r else None)
     except OSError:
-        return None
+        return None, None
 
 
 def cpu_baseline(batch, kv_bytes_total: int, target_s: float = 15.0):
@@ -175,7 +178,8 @@ def main():
         "attention_kernels_gbs": round(kv_per_step / ((dec_ms + red_ms) * 1e-3) / 1e9, 2),
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": read_traffic(args.config)},
+                     "traffic": read_traffic(args.config)[0],
+                     "traffic_over_algorithmic": read_traffic(args.config)[1]},
         "setup_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:
