@@ -48,7 +48,7 @@ struct ClassTable {
     ClassRec c[UKV_MAX_SERVICES];
 };
 
-enum Kind : uint32_t { kD64G1, kD64G2, kD64G4, kD64G8, kD128G1, kD128G2, kD128G4, kD128G8, kNumKinds };
+enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kNumKinds };
 
 struct DecodeArgs {
     const unsigned char *pool_base;

@@ -49,10 +49,35 @@ __device__ __forceinline__ float row_sum(float x) {
 
 // 128-bit load of K or V payload.  Every KV byte is used exactly once per launch, so the load
 // is marked non-temporal (streaming): it keeps the L2 for page tables, q and partials.
+// Pointers that reach the item functions through LDS have lost their address space; these
+// casts put it back (global memory), so loads are global_load, not flat_load (which would also
+// tie them to the LDS wait counter).
+#define UKV_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ const UKV_GLOBAL T *as_global(const T *p) {
+    return (const UKV_GLOBAL T *)(p);
+}
+template <class T>
+__device__ __forceinline__ UKV_GLOBAL T *as_global(T *p) {
+    return (UKV_GLOBAL T *)(p);
+}
+
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4g __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 ld_kv(const uint4 *p) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    const u32x4 v = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
     return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ u32x4 ld_kv4(const void *p) {
+    return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
+}
+// plain 128-bit global load / store
+__device__ __forceinline__ uint4 ld_g16(const void *p) {
+    const u32x4 v = *as_global(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_g16(float *p, float x, float y, float z, float w) {
+    *as_global(reinterpret_cast<f32x4g *>(p)) = (f32x4g){x, y, z, w};
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -63,6 +88,71 @@ __device__ __forceinline__ uint64_t uni(uint64_t x) {
     return ((uint64_t)uni((uint32_t)(x >> 32)) << 32) | uni((uint32_t)x);
 }
 __device__ __forceinline__ float uni(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
+
+// Workgroup state in LDS.  The kernel body only picks items; the per-kind item functions are
+// separate (non-inlined) functions so that the register allocation of one kind does not inflate
+// the others; they take their (workgroup-uniform) inputs from s_ctx and move them to SGPRs.
+static constexpr int kMaxBlock = 512;
+struct ItemCtx {
+    DecodeArgs a;
+    SeqRec s;
+    ClassRec c;
+    Item it;
+};
+__shared__ int32_t s_tab[kTabWindow];                                  // page-table window
+__shared__ __align__(16) float s_mbuf[kMaxBlock * 8 + (kMaxBlock / 8) * 2]; // merge buffer
+__shared__ __align__(16) ItemCtx s_ctx;
+
+__device__ __forceinline__ DecodeArgs ctx_args() {
+    DecodeArgs a;
+    a.pool_base = reinterpret_cast<const unsigned char *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.pool_base)));
+    a.log2_page = uni(s_ctx.a.log2_page);
+    a.page_table = reinterpret_cast<const int32_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.page_table)));
+    a.q = reinterpret_cast<const void *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.q)));
+    a.out = reinterpret_cast<float *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.out)));
+    a.classes = nullptr;
+    a.seqs = nullptr;
+    a.items = nullptr;
+    a.span_first = nullptr;
+    a.partials = reinterpret_cast<float *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.partials)));
+    a.counters = reinterpret_cast<uint32_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.counters)));
+    return a;
+}
+__device__ __forceinline__ SeqRec ctx_seq() {
+    SeqRec s;
+    s.table_off = uni(s_ctx.s.table_off);
+    s.q_off = uni(s_ctx.s.q_off);
+    s.out_off = uni(s_ctx.s.out_off);
+    s.part_off = uni(s_ctx.s.part_off);
+    s.ctx_len = uni(s_ctx.s.ctx_len);
+    s.cls = uni(s_ctx.s.cls);
+    s.head0 = uni(s_ctx.s.head0);
+    s.n_parts = uni(s_ctx.s.n_parts);
+    s.part_stride = uni(s_ctx.s.part_stride);
+    return s;
+}
+__device__ __forceinline__ ClassRec ctx_class() {
+    ClassRec c;
+    c.n_q = uni(s_ctx.c.n_q);
+    c.n_kv = uni(s_ctx.c.n_kv);
+    c.d = uni(s_ctx.c.d);
+    c.g = uni(s_ctx.c.g);
+    c.row_bytes = uni(s_ctx.c.row_bytes);
+    c.token_bytes = uni(s_ctx.c.token_bytes);
+    c.hs = uni(s_ctx.c.hs);
+    c.ti = uni(s_ctx.c.ti);
+    c.scale_log2e = uni(s_ctx.c.scale_log2e);
+    c.kind = uni(s_ctx.c.kind);
+    return c;
+}
+__device__ __forceinline__ Item ctx_item() {
+    Item it;
+    it.seq = uni(s_ctx.it.seq);
+    it.t0 = uni(s_ctx.it.t0);
+    it.t1 = uni(s_ctx.it.t1);
+    it.part = uni(s_ctx.it.part);
+    return it;
+}
 
 // Online-softmax update of one kv head's G query heads with U tokens.
 template <int G, int U, int LPR>
@@ -111,10 +201,10 @@ __device__ __forceinline__ void update(const float (&qf)[G][8], const uint4 (&kr
 // stores to complete before it counts the item, the reader starts after it has seen the count.
 __device__ __forceinline__ void st_part2(float *p, float a, float b) {
     const uint64_t v = ((uint64_t)__float_as_uint(b) << 32) | __float_as_uint(a);
-    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global(reinterpret_cast<uint64_t *>(p)), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float2 ld_part2(const float *p) {
-    const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED,
+    const uint64_t v = __hip_atomic_load(as_global(reinterpret_cast<const uint64_t *>(p)), __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT);
     return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
 }
@@ -184,18 +274,41 @@ __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_hea
         }
         if (act) {
             const float inv = Lr > 0.f ? 1.f / Lr : 0.f;
-            *reinterpret_cast<float4 *>(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4) =
-                make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+            st_g16(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4, o.x * inv, o.y * inv, o.z * inv,
+                   o.w * inv);
         }
     }
 }
 
+// After an item's partials are written: count the item, and if it was the sequence's last one,
+// merge.  Workgroup-uniform; no-op for whole-sequence items and for the two-launch variant.
+template <int NT>
+__device__ __forceinline__ void finish_item(const DecodeArgs &a, const SeqRec &s, const Item &it, uint32_t n_heads,
+                                            uint32_t D, uint32_t q_head0, int32_t *tab, float *mbuf) {
+    if (it.part == kDirect || a.counters == nullptr)
+        return;
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this lane's partial stores have completed
+    __syncthreads();
+    uint32_t *flag = reinterpret_cast<uint32_t *>(tab);
+    if (threadIdx.x == 0)
+        flag[0] = __hip_atomic_fetch_add(as_global(a.counters + it.seq), 1u, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (flag[0] == s.n_parts - 1)
+        merge_parts<NT>(a, s, n_heads, D, q_head0, mbuf);
+}
+
 template <int D, int G, int NT>
-__device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRec &s, const Item &it, int32_t *tab,
-                             float *mbuf) {
+__device__ __attribute__((noinline)) void process_item() {
+    const DecodeArgs a = ctx_args();
+    const SeqRec s = ctx_seq();
+    const ClassRec c = ctx_class();
+    const Item it = ctx_item();
+    int32_t *tab = s_tab;
+    float *mbuf = s_mbuf;
     constexpr int LPR = D / 8;   // lanes per row
     constexpr int NG = NT / LPR; // row groups in the workgroup
-    constexpr int U = (G >= 4) ? 2 : 4;
+    constexpr int U = 4;
     const int tid = threadIdx.x;
     const int lir = tid % LPR, grp = tid / LPR;
     const uint32_t HS = c.hs, TI = c.ti;
@@ -211,7 +324,7 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
                                                           (uint64_t)(kvh * G) * D + lir * 8);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const uint4 w = qp[g * LPR];
+            const uint4 w = ld_g16(qp + g * LPR);
             unpack8(w, qf[g]);
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -242,7 +355,7 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
         const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + slice_hi - 1) >> lg) - s_lo) + 1;
         __syncthreads();
         for (uint32_t e = tid; e < n_ent; e += NT)
-            tab[e] = a.page_table[s.table_off + s_lo + e];
+            tab[e] = as_global(a.page_table)[s.table_off + s_lo + e];
         __syncthreads();
 
         if (live) {
@@ -318,9 +431,9 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
         if (live && tl == 0) {
             if (direct) {
                 const float inv = l[g] > 0.f ? 1.f / l[g] : 0.f;
-                float4 *dst = reinterpret_cast<float4 *>(a.out + s.out_off + (uint64_t)(kvh * G + g) * D + lir * 8);
-                dst[0] = make_float4(acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv);
-                dst[1] = make_float4(acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv);
+                float *dst = a.out + s.out_off + (uint64_t)(kvh * G + g) * D + lir * 8;
+                st_g16(dst, acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv);
+                st_g16(dst + 4, acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv);
             } else {
                 const uint32_t hq = hh * G + g;
                 float *dst = pbase + (uint64_t)hq * D + lir * 8;
@@ -334,43 +447,234 @@ __device__ void process_item(const DecodeArgs &a, const ClassRec &c, const SeqRe
         }
     }
 
-    // fused merge: the workgroup that completes a cut sequence last combines its partials
-    if (!direct && a.counters != nullptr) {
-        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this lane's partial stores have completed
-        __syncthreads();
-        uint32_t *flag = reinterpret_cast<uint32_t *>(tab);
-        if (tid == 0)
-            flag[0] = __hip_atomic_fetch_add(a.counters + it.seq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (flag[0] == s.n_parts - 1)
-            merge_parts<NT>(a, s, HS * G, D, s.head0 * G, mbuf);
+    finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, tab, mbuf);
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Grouped-query path (head_dim 128, G = 2, 4 or 8 query heads per kv head) on the matrix cores.
+//
+// With G query heads sharing one kv head the path does G flop per KV byte and the plain-ALU
+// formulation above becomes ALU-bound.  Here one wave owns one kv head and walks the item's
+// tokens in tiles of 16 (lane l: column j = l%16, k-block q = l/16):
+//   S^T[token][head]  = K[token][:] . Q[head][:]    4 x v_mfma_f32_16x16x32_bf16, A = K rows (16 tokens),
+//                                                   B = Q^T (heads padded to 16)
+//   O^T[d][head]     += V^T[d][token] . P^T[token][head]    8 x v_mfma_f32_16x16x16_bf16 (x2, see below)
+// The S^T result leaves lane (j, q) with the scores of head j for tokens 4q..4q+3, which is exactly
+// the k-block the second product wants from that lane, so P needs no cross-lane movement.  V is
+// loaded row-major (lane (i, q): 16-byte chunk i of tokens 4q..4q+3, i.e. whole 256-byte rows per
+// 16 lanes) and transposed inside the lane with byte permutes; output row (MFMA m, lane i) is
+// d = 8i + m.  P is split into bf16 high and low parts (two products), so the weights keep ~16
+// mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
+__device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float x) { // x finite, >= 0
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int NT>
+__device__ __attribute__((noinline)) void process_item_gqa() {
+    const DecodeArgs a = ctx_args();
+    const SeqRec s = ctx_seq();
+    const ClassRec c = ctx_class();
+    const Item it = ctx_item();
+    int32_t *tab = s_tab;
+    float *mbuf = s_mbuf;
+    constexpr int D = 128;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = uni((uint32_t)(tid >> 6));
+    const uint32_t HS = c.hs, G = c.g;
+    const bool live = wave < HS; // one wave per kv head of the slice; further waves idle
+    const uint32_t kvh = s.head0 + (live ? wave : 0);
+    const uint32_t j = lane & 15, q = lane >> 4;
+    const uint32_t lg = a.log2_page;
+    const uint64_t page_mask = (1ull << lg) - 1;
+
+    bf16x8_t qB[4];
+    {
+        const uint4 *qp = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.q) + s.q_off +
+                                                          (uint64_t)(kvh * G + (j < G ? j : 0)) * D) + q;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            uint4 w = ld_g16(qp + st * 4);
+            if (j >= G)
+                w = make_uint4(0, 0, 0, 0);
+            qB[st] = as_bf16x8(w);
+        }
     }
+    f32x4_t oacc[8];
+#pragma unroll
+    for (int mm = 0; mm < 8; ++mm)
+        oacc[mm] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    const uint64_t T = c.token_bytes;
+    const uint64_t row0 = (uint64_t)kvh * c.row_bytes;
+    const uint64_t slice_lo = (uint64_t)s.head0 * c.row_bytes;
+    const uint64_t slice_hi = (uint64_t)(s.head0 + HS) * c.row_bytes;
+
+    uint32_t w0 = it.t0;
+    while (w0 < it.t1) { // workgroup-uniform: one pass per page-table window
+        const uint64_t s_lo = ((uint64_t)w0 * T + slice_lo) >> lg;
+        const uint64_t lim = (s_lo + kTabWindow) << lg;
+        const uint64_t tmax = (lim - slice_hi) / T;
+        const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)it.t1 ? tmax + 1 : (uint64_t)it.t1);
+        const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + slice_hi - 1) >> lg) - s_lo) + 1;
+        __syncthreads();
+        for (uint32_t e = tid; e < n_ent; e += NT)
+            tab[e] = as_global(a.page_table)[s.table_off + s_lo + e];
+        __syncthreads();
+
+        if (live) {
+            const uint32_t last = w1 - 1;
+            // K rows: tokens tb+j and tb+16+j, chunk (step*4 + q) -> kA[half*4 + step]; V: chunk j of the
+            // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token and
+            // masked in the scores.  All ten page lookups are issued before the first is used.
+            auto row_ptr = [&](uint32_t t) -> const unsigned char * { // head-row of (token t, this kv head)
+                const uint64_t off = (uint64_t)t * T + row0;
+                const int32_t pg = tab[(uint32_t)((off >> lg) - s_lo)];
+                return a.pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask);
+            };
+            // K row of token tb+j, chunk (step*4 + q) -> kA[step]; V rows of tokens tb+4q+e, chunk j -> vr[e].
+            // Tokens past the range are clamped to its last token and masked in the scores.
+            auto load_tile = [&](uint32_t tb, u32x4 (&kA)[4], u32x4 (&vr)[4]) {
+                const unsigned char *pk = row_ptr(min(tb + j, last)) + q * 16;
+                const unsigned char *pv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    pv[e] = row_ptr(min(tb + 4 * q + e, last)) + 2 * D + j * 16;
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    kA[st] = ld_kv4(pk + st * 64);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    vr[e] = ld_kv4(pv[e]);
+            };
+            auto compute_tile = [&](uint32_t tb, const u32x4 (&kA)[4], const u32x4 (&vr)[4]) {
+                f32x4_t sT = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    sT = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[st], sT, 0, 0, 0);
+                float sc[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    sc[r] = (tb + 4 * q + r < w1) ? sT[r] * c.scale_log2e : -INFINITY;
+                float mt = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+                mt = fmaxf(mt, __shfl_xor(mt, 16));
+                mt = fmaxf(mt, __shfl_xor(mt, 32)); // the tile's first token is always valid: mt is finite
+                const float mn = fmaxf(m, mt);
+                const float alpha = fast_exp2(m - mn);
+                m = mn;
+                uint32_t ph[2], pl[2];
+                float psum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; e += 2) {
+                    const float p0 = fast_exp2(sc[e] - mn), p1 = fast_exp2(sc[e + 1] - mn);
+                    psum += p0 + p1;
+                    const uint32_t h0 = bf16_rne_bits(p0), h1 = bf16_rne_bits(p1);
+                    const uint32_t l0 = bf16_rne_bits(p0 - __uint_as_float(h0 << 16));
+                    const uint32_t l1 = bf16_rne_bits(p1 - __uint_as_float(h1 << 16));
+                    ph[e / 2] = h0 | (h1 << 16);
+                    pl[e / 2] = l0 | (l1 << 16);
+                }
+                l = fmaf(l, alpha, psum);
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+                    for (int mm = 0; mm < 8; ++mm)
+                        oacc[mm] *= alpha;
+                }
+                const s16x4_t Ph = __builtin_bit_cast(s16x4_t, make_uint2(ph[0], ph[1]));
+                const s16x4_t Pl = __builtin_bit_cast(s16x4_t, make_uint2(pl[0], pl[1]));
+#pragma unroll
+                for (int mm = 0; mm < 8; ++mm) {
+                    // element mm of each token's chunk: dword mm/2, low or high half
+                    const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
+                    const uint32_t v01 = __builtin_amdgcn_perm(vr[1][mm / 2], vr[0][mm / 2], sel);
+                    const uint32_t v23 = __builtin_amdgcn_perm(vr[3][mm / 2], vr[2][mm / 2], sel);
+                    const s16x4_t Vt = __builtin_bit_cast(s16x4_t, make_uint2(v01, v23));
+                    oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Vt, Ph, oacc[mm], 0, 0, 0);
+                    oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Vt, Pl, oacc[mm], 0, 0, 0);
+                }
+            };
+            // the next tile's loads are issued before the current tile is consumed
+            u32x4 kA0[4], vr0[4], kA1[4], vr1[4];
+            uint32_t tb = w0;
+            load_tile(tb, kA0, vr0);
+            while (true) {
+                if (tb + 16 < w1)
+                    load_tile(tb + 16, kA1, vr1);
+                compute_tile(tb, kA0, vr0);
+                tb += 16;
+                if (tb >= w1)
+                    break;
+                if (tb + 16 < w1)
+                    load_tile(tb + 16, kA0, vr0);
+                compute_tile(tb, kA1, vr1);
+                tb += 16;
+                if (tb >= w1)
+                    break;
+            }
+        }
+        w0 = w1;
+    }
+
+    // lane (j, q) holds O[head j][d = 32q + 8r + mm] in oacc[mm][r]; l is a per-lane partial sum
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const bool direct = it.part == kDirect;
+    if (live && j < G) {
+        if (direct) {
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            float *dst = a.out + s.out_off + (uint64_t)(kvh * G + j) * D + 32 * q;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                st_g16(dst + 8 * r, oacc[0][r] * inv, oacc[1][r] * inv, oacc[2][r] * inv, oacc[3][r] * inv);
+                st_g16(dst + 8 * r + 4, oacc[4][r] * inv, oacc[5][r] * inv, oacc[6][r] * inv, oacc[7][r] * inv);
+            }
+        } else {
+            float *pbase = a.partials + s.part_off + (uint64_t)it.part * s.part_stride;
+            const uint32_t hq = wave * G + j;
+            float *dst = pbase + (uint64_t)hq * D + 32 * q;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                st_part2(dst + 8 * r, oacc[0][r], oacc[1][r]);
+                st_part2(dst + 8 * r + 2, oacc[2][r], oacc[3][r]);
+                st_part2(dst + 8 * r + 4, oacc[4][r], oacc[5][r]);
+                st_part2(dst + 8 * r + 6, oacc[6][r], oacc[7][r]);
+            }
+            if (q == 0)
+                st_part2(pbase + (uint64_t)HS * G * D + hq * 2, m, l);
+        }
+    }
+    finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, tab, mbuf);
 }
 
 template <int NT>
 __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
-    __shared__ int32_t tab[kTabWindow];
-    __shared__ __align__(16) float mbuf[NT * 8 + (NT / 8) * 2];
     const uint32_t i0 = uni(a.span_first[blockIdx.x]), i1 = uni(a.span_first[blockIdx.x + 1]);
+    if (threadIdx.x == 0)
+        s_ctx.a = a;
     for (uint32_t i = i0; i < i1; ++i) {
-        Item it = a.items[i];
-        it.seq = uni(it.seq); it.t0 = uni(it.t0); it.t1 = uni(it.t1); it.part = uni(it.part);
-        SeqRec s = a.seqs[it.seq];
-        s.table_off = uni(s.table_off); s.q_off = uni(s.q_off); s.out_off = uni(s.out_off);
-        s.part_off = uni(s.part_off); s.cls = uni(s.cls); s.head0 = uni(s.head0);
-        s.part_stride = uni(s.part_stride); s.n_parts = uni(s.n_parts);
-        ClassRec c = a.classes[s.cls];
-        c.token_bytes = uni(c.token_bytes); c.row_bytes = uni(c.row_bytes); c.hs = uni(c.hs); c.ti = uni(c.ti);
-        c.kind = uni(c.kind); c.scale_log2e = uni(c.scale_log2e);
-        switch (c.kind) { // workgroup-uniform: one compiled shape per (head_dim, group)
-        case kD64G1: process_item<64, 1, NT>(a, c, s, it, tab, mbuf); break;
-        case kD64G2: process_item<64, 2, NT>(a, c, s, it, tab, mbuf); break;
-        case kD64G4: process_item<64, 4, NT>(a, c, s, it, tab, mbuf); break;
-        case kD64G8: process_item<64, 8, NT>(a, c, s, it, tab, mbuf); break;
-        case kD128G1: process_item<128, 1, NT>(a, c, s, it, tab, mbuf); break;
-        case kD128G2: process_item<128, 2, NT>(a, c, s, it, tab, mbuf); break;
-        case kD128G4: process_item<128, 4, NT>(a, c, s, it, tab, mbuf); break;
-        case kD128G8: process_item<128, 8, NT>(a, c, s, it, tab, mbuf); break;
+        __syncthreads(); // the previous item is done with s_ctx
+        if (threadIdx.x == 0) {
+            const Item it = a.items[i];
+            const SeqRec s = a.seqs[it.seq];
+            s_ctx.it = it;
+            s_ctx.s = s;
+            s_ctx.c = a.classes[s.cls];
+        }
+        __syncthreads();
+        switch (uni(s_ctx.c.kind)) { // workgroup-uniform: one compiled function per (head_dim, group) kind
+        case kD64G1: process_item<64, 1, NT>(); break;
+        case kD64G2: process_item<64, 2, NT>(); break;
+        case kD128G1: process_item<128, 1, NT>(); break;
+        case kD128GQA: process_item_gqa<NT>(); break;
         default: break;
         }
     }

@@ -65,20 +65,24 @@ int derive_classes(ukv_pool *p) {
         c.token_bytes = c.row_bytes * sv.n_kv_heads;
         const double scale = sv.scale != 0.0f ? (double)sv.scale : 1.0 / std::sqrt((double)sv.head_dim);
         c.scale_log2e = (float)(scale * 1.4426950408889634);
-        uint32_t gi;
-        switch (c.g) {
-        case 1: gi = 0; break;
-        case 2: gi = 1; break;
-        case 4: gi = 2; break;
-        case 8: gi = 3; break;
-        default: return fail(UKV_EINVAL, "unsupported query group size (need 1, 2, 4 or 8)");
-        }
-        if (c.d == 64)
-            c.kind = kD64G1 + gi;
-        else if (c.d == 128)
-            c.kind = kD128G1 + gi;
+        const bool g_ok = c.g == 1 || c.g == 2 || c.g == 4 || c.g == 8;
+        if (c.d == 128 && g_ok)
+            c.kind = c.g == 1 ? kD128G1 : kD128GQA;
+        else if (c.d == 64 && (c.g == 1 || c.g == 2))
+            c.kind = c.g == 1 ? kD64G1 : kD64G2;
         else
-            return fail(UKV_EINVAL, "unsupported head_dim (need 64 or 128)");
+            return fail(UKV_EINVAL, "unsupported shape: head_dim 128 with group 1/2/4/8, or head_dim 64 with group 1/2");
+        if (c.kind == kD128GQA) {
+            // matrix-core path: one wave per kv head of the slice, all waves on the same tokens
+            const uint32_t waves = (uint32_t)p->tun.block_threads / 64;
+            uint32_t hs = 1;
+            for (uint32_t h = 1; h <= c.n_kv && h <= waves; ++h)
+                if (c.n_kv % h == 0)
+                    hs = h;
+            c.hs = hs;
+            c.ti = 1;
+            continue;
+        }
         choose_slicing(c.n_kv, c.d, (uint32_t)p->tun.block_threads, p->tun.heads_per_slice, &c.hs, &c.ti);
     }
     return UKV_OK;
