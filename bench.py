@@ -88,6 +88,7 @@ def main():
     ap.add_argument("--heads-per-slice", type=int, default=0)
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
+    ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="skip grow+append in the step (diagnostic)")
     args = ap.parse_args()
@@ -120,6 +121,8 @@ def main():
         U.ukv_set_param(db.pool, U.UKV_PARAM_SLOTS, args.slots)
     if args.no_taper:
         U.ukv_set_param(db.pool, U.UKV_PARAM_TAPER, 0)
+    if args.unfused_merge:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
     db.resize_workspace()
     rng = np.random.default_rng(1)
     _, nk, nv = b.draw_step_inputs(rng)

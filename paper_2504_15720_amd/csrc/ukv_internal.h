@@ -23,7 +23,7 @@ struct SeqRec {
     uint32_t cls;         // service index
     uint32_t head0;       // first kv head of the slice
     uint32_t n_parts;     // work items this sequence was cut into
-    uint32_t part_stride; // floats per partial: n_heads_q * (head_dim + 2), rounded up to 4
+    uint32_t part_stride; // floats per partial: n_heads_q * (head_dim + 2), rounded up to 32 (one line)
     uint32_t pad_[3];
 };
 static_assert(sizeof(SeqRec) == 64, "SeqRec layout");
@@ -68,6 +68,8 @@ struct ReduceRec {
     uint64_t part_off;
     uint64_t out_off;     // element offset of the slice's first q head in out
     uint32_t n_parts, part_stride, n_heads, d;
+    uint32_t layout_g; // 0 = ALU-path partial layout, else the group size of the matrix-core path
+    uint32_t pad_[3];
 };
 
 struct AppendRec {

@@ -209,6 +209,24 @@ __device__ __forceinline__ float2 ld_part2(const float *p) {
     return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
 }
 
+// Layout of the accumulators inside one partial.  It follows the writers' register layouts so
+// that every 64-bit store instruction of a wave covers contiguous memory (whole 128-byte lines):
+//   layout_g == 0 (ALU path): per query head D floats; lane lir of the row group holds columns
+//     8*lir + 2k + {0,1} and stores pair k at  hq*D + k*(D/4) + 2*lir.
+//   layout_g == G (matrix-core path): per kv head G*128 floats; lane (j, q) holds columns
+//     32q + 8r + 2pp + {0,1} of head j and stores pair (r, pp) at  hh*G*128 + ((4r+pp)*4G + q*G + j)*2.
+// Returns the float offset of the pair holding columns 4*c4 + 2h, 4*c4 + 2h + 1 of query head hq.
+__device__ __forceinline__ uint32_t part_pair_off(uint32_t layout_g, uint32_t D, uint32_t hq, uint32_t c4,
+                                                  uint32_t h) {
+    if (layout_g == 0) {
+        const uint32_t lir = c4 >> 1, k = ((c4 & 1) << 1) + h;
+        return hq * D + k * (D >> 2) + 2 * lir;
+    }
+    const uint32_t G = layout_g, hh = hq / G, j = hq % G;
+    const uint32_t q = c4 >> 3, r = (c4 & 7) >> 1, pp = ((c4 & 1) << 1) + h;
+    return hh * (G * 128) + (((r << 2) + pp) * (4 * G) + q * G + j) * 2;
+}
+
 // Merge of the partials of one cut sequence (all its query heads), executed by the workgroup
 // that finished the sequence's last item:  with M = max_c m_c,
 //   out = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M).
@@ -216,7 +234,7 @@ __device__ __forceinline__ float2 ld_part2(const float *p) {
 // only streams its accumulators, several parts in flight; chunks combine by the same rule.
 template <int NT>
 __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_heads, uint32_t D, uint32_t q_head0,
-                            float *lds) {
+                            uint32_t layout_g, float *lds) {
     constexpr uint32_t kPairs = NT * 4; // (m, l) pairs that fit the LDS buffer
     const float *base = a.partials + s.part_off;
     const float *ml_base = base + (uint64_t)n_heads * D;
@@ -249,14 +267,15 @@ __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_hea
             Lr *= f;
             o.x *= f; o.y *= f; o.z *= f; o.w *= f;
             Mr = Mc;
-            const float *xa = base + (uint64_t)c0 * s.part_stride + (uint64_t)hq * D + c4 * 4;
+            const float *xa = base + (uint64_t)c0 * s.part_stride;
+            const uint32_t off0 = part_pair_off(layout_g, D, hq, c4, 0), off1 = part_pair_off(layout_g, D, hq, c4, 1);
             for (uint32_t c = 0; c < nc; c += 4) {
                 float2 x0[4], x1[4];
 #pragma unroll
                 for (uint32_t k = 0; k < 4; ++k) {
                     const uint32_t cc = min(c + k, nc - 1); // clamp: a repeated load, zero weight below
-                    x0[k] = ld_part2(xa + (uint64_t)cc * s.part_stride);
-                    x1[k] = ld_part2(xa + (uint64_t)cc * s.part_stride + 2);
+                    x0[k] = ld_part2(xa + (uint64_t)cc * s.part_stride + off0);
+                    x1[k] = ld_part2(xa + (uint64_t)cc * s.part_stride + off1);
                 }
 #pragma unroll
                 for (uint32_t k = 0; k < 4; ++k) {
@@ -284,7 +303,8 @@ __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_hea
 // merge.  Workgroup-uniform; no-op for whole-sequence items and for the two-launch variant.
 template <int NT>
 __device__ __forceinline__ void finish_item(const DecodeArgs &a, const SeqRec &s, const Item &it, uint32_t n_heads,
-                                            uint32_t D, uint32_t q_head0, int32_t *tab, float *mbuf) {
+                                            uint32_t D, uint32_t q_head0, uint32_t layout_g, int32_t *tab,
+                                            float *mbuf) {
     if (it.part == kDirect || a.counters == nullptr)
         return;
     __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this lane's partial stores have completed
@@ -295,7 +315,7 @@ __device__ __forceinline__ void finish_item(const DecodeArgs &a, const SeqRec &s
                                          __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (flag[0] == s.n_parts - 1)
-        merge_parts<NT>(a, s, n_heads, D, q_head0, mbuf);
+        merge_parts<NT>(a, s, n_heads, D, q_head0, layout_g, mbuf);
 }
 
 template <int D, int G, int NT>
@@ -436,18 +456,18 @@ __device__ __attribute__((noinline)) void process_item() {
                 st_g16(dst + 4, acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv);
             } else {
                 const uint32_t hq = hh * G + g;
-                float *dst = pbase + (uint64_t)hq * D + lir * 8;
+                float *dst = pbase + (uint64_t)hq * D + lir * 2; // pair k at + k*(D/4): see part_pair_off
                 st_part2(dst, acc[g][0], acc[g][1]);
-                st_part2(dst + 2, acc[g][2], acc[g][3]);
-                st_part2(dst + 4, acc[g][4], acc[g][5]);
-                st_part2(dst + 6, acc[g][6], acc[g][7]);
+                st_part2(dst + (D / 4), acc[g][2], acc[g][3]);
+                st_part2(dst + 2 * (D / 4), acc[g][4], acc[g][5]);
+                st_part2(dst + 3 * (D / 4), acc[g][6], acc[g][7]);
                 if (lir == 0)
                     st_part2(pbase + (uint64_t)HS * G * D + hq * 2, m[g], l[g]);
             }
         }
     }
 
-    finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, tab, mbuf);
+    finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, 0, tab, mbuf);
 }
 
 
@@ -640,19 +660,17 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
         } else {
             float *pbase = a.partials + s.part_off + (uint64_t)it.part * s.part_stride;
             const uint32_t hq = wave * G + j;
-            float *dst = pbase + (uint64_t)hq * D + 32 * q;
+            float *dst = pbase + (uint64_t)wave * (G * D) + (q * G + j) * 2; // pair (r, pp): see part_pair_off
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                st_part2(dst + 8 * r, oacc[0][r], oacc[1][r]);
-                st_part2(dst + 8 * r + 2, oacc[2][r], oacc[3][r]);
-                st_part2(dst + 8 * r + 4, oacc[4][r], oacc[5][r]);
-                st_part2(dst + 8 * r + 6, oacc[6][r], oacc[7][r]);
-            }
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int pp = 0; pp < 4; ++pp)
+                    st_part2(dst + (r * 4 + pp) * (8 * G), oacc[2 * pp][r], oacc[2 * pp + 1][r]);
             if (q == 0)
                 st_part2(pbase + (uint64_t)HS * G * D + hq * 2, m, l);
         }
     }
-    finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, tab, mbuf);
+    finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, G, tab, mbuf);
 }
 
 template <int NT>
@@ -705,9 +723,9 @@ __global__ void __launch_bounds__(64) reduce_kernel(const ReduceRec *recs, const
         const float w = fast_exp2(mc - M);
         L = fmaf(lc, w, L);
         if (lane < r.d)
-            o0 = fmaf(pc[hq * r.d + lane], w, o0);
+            o0 = fmaf(pc[part_pair_off(r.layout_g, r.d, hq, lane >> 2, (lane >> 1) & 1) + (lane & 1)], w, o0);
         if (two)
-            o1 = fmaf(pc[hq * r.d + 64 + lane], w, o1);
+            o1 = fmaf(pc[part_pair_off(r.layout_g, r.d, hq, (64 + lane) >> 2, (lane >> 1) & 1) + (lane & 1)], w, o1);
     }
     const float inv = L > 0.f ? 1.f / L : 0.f;
     float *dst = out + r.out_off + (uint64_t)hq * r.d;

@@ -11,9 +11,8 @@ namespace ukv {
 static constexpr uint64_t kItemOverheadBytes = 16 * 1024; // q load, merge and output, as KV bytes
 static constexpr uint64_t kMinItemTokens = 16;
 
-static inline uint32_t round_up4(uint32_t x) { return (x + 3u) & ~3u; }
-
-static uint32_t part_stride_of(const ClassRec &c) { return round_up4(c.hs * c.g * (c.d + 2)); }
+// partials of different items never share a 128-byte line
+static uint32_t part_stride_of(const ClassRec &c) { return (c.hs * c.g * (c.d + 2) + 31u) & ~31u; }
 
 static uint32_t spans_bound(const ukv_pool *p) { return (uint32_t)(2 * p->tun.max_spans + 2); }
 
@@ -168,6 +167,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         r.part_stride = s.part_stride;
         r.n_heads = c.hs * c.g;
         r.d = c.d;
+        r.layout_g = c.kind == kD128GQA ? c.g : 0;
         plan.reduce.push_back(r);
         plan.max_reduce_heads = std::max(plan.max_reduce_heads, r.n_heads);
     }
