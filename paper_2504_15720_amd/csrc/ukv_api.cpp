@@ -144,20 +144,12 @@ int ukv_plan_decode(const ukv_pool_t *p, const ukv_batch_t *b, ukv_plan_info_t *
     info->plan_bytes = blob_layout(plan.seqs.size(), plan.items.size(), info->n_spans, plan.reduce.size()).total;
     info->kv_bytes = plan.kv_bytes;
     if (items_out) {
-        // request index of each sequence: sequences are emitted request by request
-        std::vector<uint32_t> seq_req(plan.seqs.size());
-        uint32_t k = 0;
-        for (uint32_t i = 0; i < b->n_requests; ++i) {
-            const ClassRec &c = p->classes.c[b->service_id[i]];
-            for (uint32_t h0 = 0; h0 < c.n_kv; h0 += c.hs)
-                seq_req[k++] = i;
-        }
         const uint32_t n = std::min<uint32_t>(n_items_cap, info->n_items);
         for (uint32_t it = 0; it < n; ++it) {
             const Item &x = plan.items[it];
             const SeqRec &s = plan.seqs[x.seq];
             uint32_t *row = items_out + (size_t)it * 6;
-            row[0] = seq_req[x.seq];
+            row[0] = plan.seq_req[x.seq];
             row[1] = s.head0;
             row[2] = p->classes.c[s.cls].hs;
             row[3] = x.t0;

@@ -109,6 +109,7 @@ struct Plan {
     std::vector<uint32_t> span_first;
     std::vector<ReduceRec> reduce;
     std::vector<uint32_t> item_span; // span index of each item (inspection only)
+    std::vector<uint32_t> seq_req;   // request index of each sequence
     uint64_t partial_floats = 0;
     uint64_t kv_bytes = 0;
     uint32_t max_reduce_heads = 0;

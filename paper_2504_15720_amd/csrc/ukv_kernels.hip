@@ -232,6 +232,46 @@ __device__ __forceinline__ uint32_t part_pair_off(uint32_t layout_g, uint32_t D,
 //   out = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M).
 // The (m, l) pairs are staged in LDS a chunk of parts at a time, so that each output element
 // only streams its accumulators, several parts in flight; chunks combine by the same rule.
+static constexpr uint32_t kMergeBatch = 8; // parts whose accumulators are in flight per thread
+
+// One output float4 (query head hq, columns 4*c4..) from the parts [c0, c0+nc) whose (m, l)
+// pairs are staged in lds[2*(c*n_heads + hq)]; (Mr, Lr, o) carry the running maximum, sum and
+// accumulator across chunks of parts.
+__device__ __forceinline__ void merge_unit(const float *xa, uint32_t part_stride, const float *lds, uint32_t n_heads,
+                                           uint32_t nc, uint32_t hq, uint32_t off0, uint32_t off1, float &Mr,
+                                           float &Lr, float4 &o) {
+    float Mc = Mr;
+    for (uint32_t c = 0; c < nc; ++c)
+        Mc = fmaxf(Mc, lds[2 * (c * n_heads + hq)]);
+    if (Mc == -INFINITY)
+        return;
+    const float f = fast_exp2(Mr - Mc);
+    Lr *= f;
+    o.x *= f; o.y *= f; o.z *= f; o.w *= f;
+    Mr = Mc;
+    for (uint32_t c = 0; c < nc; c += kMergeBatch) {
+        float2 x0[kMergeBatch], x1[kMergeBatch];
+#pragma unroll
+        for (uint32_t k = 0; k < kMergeBatch; ++k) {
+            const uint32_t cc = min(c + k, nc - 1); // clamp: a repeated load, skipped below
+            x0[k] = ld_part2(xa + (uint64_t)cc * part_stride + off0);
+            x1[k] = ld_part2(xa + (uint64_t)cc * part_stride + off1);
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kMergeBatch; ++k) {
+            if (c + k >= nc)
+                break;
+            const uint32_t i = (c + k) * n_heads + hq;
+            const float w = fast_exp2(lds[2 * i] - Mr);
+            Lr = fmaf(lds[2 * i + 1], w, Lr);
+            o.x = fmaf(x0[k].x, w, o.x);
+            o.y = fmaf(x0[k].y, w, o.y);
+            o.z = fmaf(x1[k].x, w, o.z);
+            o.w = fmaf(x1[k].y, w, o.w);
+        }
+    }
+}
+
 template <int NT>
 __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_heads, uint32_t D, uint32_t q_head0,
                             uint32_t layout_g, float *lds) {
@@ -240,6 +280,32 @@ __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_hea
     const float *ml_base = base + (uint64_t)n_heads * D;
     const uint32_t chunks4 = D / 4, units = n_heads * chunks4;
     const uint32_t cmax = kPairs / n_heads;
+    auto stage_ml = [&](uint32_t c0, uint32_t nc) {
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < nc * n_heads; i += NT) {
+            const uint32_t c = i / n_heads, h = i % n_heads;
+            const float2 p = ld_part2(ml_base + (uint64_t)(c0 + c) * s.part_stride + h * 2);
+            lds[2 * i] = p.y > 0.f ? p.x : -INFINITY; // an empty part carries no weight
+            lds[2 * i + 1] = p.y;
+        }
+        __syncthreads();
+    };
+    auto write_out = [&](uint32_t hq, uint32_t c4, float Lr, const float4 &o) {
+        const float inv = Lr > 0.f ? 1.f / Lr : 0.f;
+        st_g16(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4, o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+    };
+    if (s.n_parts <= cmax) { // usual case: all (m, l) pairs fit, staged once for every output element
+        stage_ml(0, s.n_parts);
+        for (uint32_t u = threadIdx.x; u < units; u += NT) {
+            const uint32_t hq = u / chunks4, c4 = u % chunks4;
+            float Mr = -INFINITY, Lr = 0.f;
+            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+            merge_unit(base, s.part_stride, lds, n_heads, s.n_parts, hq, part_pair_off(layout_g, D, hq, c4, 0),
+                       part_pair_off(layout_g, D, hq, c4, 1), Mr, Lr, o);
+            write_out(hq, c4, Lr, o);
+        }
+        return;
+    }
     for (uint32_t u0 = 0; u0 < units; u0 += NT) { // workgroup-uniform
         const uint32_t u = u0 + threadIdx.x;
         const bool act = u < units;
@@ -248,54 +314,13 @@ __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_hea
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
         for (uint32_t c0 = 0; c0 < s.n_parts; c0 += cmax) {
             const uint32_t nc = min(cmax, s.n_parts - c0);
-            __syncthreads();
-            for (uint32_t i = threadIdx.x; i < nc * n_heads; i += NT) {
-                const uint32_t c = i / n_heads, h = i % n_heads;
-                const float2 p = ld_part2(ml_base + (uint64_t)(c0 + c) * s.part_stride + h * 2);
-                lds[2 * i] = p.y > 0.f ? p.x : -INFINITY; // an empty part carries no weight
-                lds[2 * i + 1] = p.y;
-            }
-            __syncthreads();
-            if (!act)
-                continue;
-            float Mc = Mr;
-            for (uint32_t c = 0; c < nc; ++c)
-                Mc = fmaxf(Mc, lds[2 * (c * n_heads + hq)]);
-            if (Mc == -INFINITY)
-                continue;
-            const float f = fast_exp2(Mr - Mc);
-            Lr *= f;
-            o.x *= f; o.y *= f; o.z *= f; o.w *= f;
-            Mr = Mc;
-            const float *xa = base + (uint64_t)c0 * s.part_stride;
-            const uint32_t off0 = part_pair_off(layout_g, D, hq, c4, 0), off1 = part_pair_off(layout_g, D, hq, c4, 1);
-            for (uint32_t c = 0; c < nc; c += 4) {
-                float2 x0[4], x1[4];
-#pragma unroll
-                for (uint32_t k = 0; k < 4; ++k) {
-                    const uint32_t cc = min(c + k, nc - 1); // clamp: a repeated load, zero weight below
-                    x0[k] = ld_part2(xa + (uint64_t)cc * s.part_stride + off0);
-                    x1[k] = ld_part2(xa + (uint64_t)cc * s.part_stride + off1);
-                }
-#pragma unroll
-                for (uint32_t k = 0; k < 4; ++k) {
-                    if (c + k >= nc)
-                        break;
-                    const uint32_t i = (c + k) * n_heads + hq;
-                    const float w = fast_exp2(lds[2 * i] - Mr);
-                    Lr = fmaf(lds[2 * i + 1], w, Lr);
-                    o.x = fmaf(x0[k].x, w, o.x);
-                    o.y = fmaf(x0[k].y, w, o.y);
-                    o.z = fmaf(x1[k].x, w, o.z);
-                    o.w = fmaf(x1[k].y, w, o.w);
-                }
-            }
+            stage_ml(c0, nc);
+            if (act)
+                merge_unit(base + (uint64_t)c0 * s.part_stride, s.part_stride, lds, n_heads, nc, hq,
+                           part_pair_off(layout_g, D, hq, c4, 0), part_pair_off(layout_g, D, hq, c4, 1), Mr, Lr, o);
         }
-        if (act) {
-            const float inv = Lr > 0.f ? 1.f / Lr : 0.f;
-            st_g16(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4, o.x * inv, o.y * inv, o.z * inv,
-                   o.w * inv);
-        }
+        if (act)
+            write_out(hq, c4, Lr, o);
     }
 }
 
@@ -476,16 +501,16 @@ __device__ __attribute__((noinline)) void process_item() {
 //
 // With G query heads sharing one kv head the path does G flop per KV byte and the plain-ALU
 // formulation above becomes ALU-bound.  Here one wave owns one kv head and walks the item's
-// tokens in tiles of 16 (lane l: column j = l%16, k-block q = l/16):
-//   S^T[token][head]  = K[token][:] . Q[head][:]    4 x v_mfma_f32_16x16x32_bf16, A = K rows (16 tokens),
-//                                                   B = Q^T (heads padded to 16)
-//   O^T[d][head]     += V^T[d][token] . P^T[token][head]    8 x v_mfma_f32_16x16x16_bf16 (x2, see below)
-// The S^T result leaves lane (j, q) with the scores of head j for tokens 4q..4q+3, which is exactly
-// the k-block the second product wants from that lane, so P needs no cross-lane movement.  V is
-// loaded row-major (lane (i, q): 16-byte chunk i of tokens 4q..4q+3, i.e. whole 256-byte rows per
-// 16 lanes) and transposed inside the lane with byte permutes; output row (MFMA m, lane i) is
-// d = 8i + m.  P is split into bf16 high and low parts (two products), so the weights keep ~16
-// mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
+// tokens in tiles of 32, with v_mfma_f32_16x16x32_bf16 (lane l: column j = l%16, k-block q = l/16):
+//   S^T[token][head]  = K[token][:] . Q[head][:]      A = K rows (16 tokens), B = Q^T (heads padded to 16)
+//   O^T[d][head]     += V^T[d][token] . P^T[token][head]
+// The S^T results leave lane (j, q) with 8 scores of head j (tokens 4q..4q+3 of each 16-token
+// half), which is exactly the k-block the second product wants from that lane once its token
+// order is taken as tau(q, e) = e < 4 ? 4q+e : 16+4q+(e-4); so P needs no cross-lane movement.
+// V is loaded row-major (lane (i, q): 16-byte chunk i of the 8 tokens tau(q, .), i.e. whole
+// 256-byte rows per 16 lanes) and transposed inside the lane with byte permutes; output row
+// (MFMA m, lane i) is d = 8i + m.  P is split into bf16 high and low parts (two products), so the
+// weights keep ~16 mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -561,40 +586,46 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
                 const int32_t pg = tab[(uint32_t)((off >> lg) - s_lo)];
                 return a.pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask);
             };
-            // K row of token tb+j, chunk (step*4 + q) -> kA[step]; V rows of tokens tb+4q+e, chunk j -> vr[e].
-            // Tokens past the range are clamped to its last token and masked in the scores.
-            auto load_tile = [&](uint32_t tb, u32x4 (&kA)[4], u32x4 (&vr)[4]) {
-                const unsigned char *pk = row_ptr(min(tb + j, last)) + q * 16;
-                const unsigned char *pv[4];
+            // K rows: tokens tb+j and tb+16+j, chunk (step*4 + q) -> kA[half*4 + step]; V: chunk j of the
+            // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token and masked
+            // in the scores.
+            auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
+            auto load_tile = [&](uint32_t tb, u32x4 (&kA)[8], u32x4 (&vr)[8]) {
+                const unsigned char *p0 = row_ptr(min(tb + j, last)) + q * 16;
+                const unsigned char *p1 = row_ptr(min(tb + 16 + j, last)) + q * 16;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    pv[e] = row_ptr(min(tb + 4 * q + e, last)) + 2 * D + j * 16;
+                for (int st = 0; st < 4; ++st) {
+                    kA[st] = ld_kv4(p0 + st * 64);
+                    kA[4 + st] = ld_kv4(p1 + st * 64);
+                }
 #pragma unroll
-                for (int st = 0; st < 4; ++st)
-                    kA[st] = ld_kv4(pk + st * 64);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    vr[e] = ld_kv4(pv[e]);
+                for (int e = 0; e < 8; ++e)
+                    vr[e] = ld_kv4(row_ptr(min(tau(tb, e), last)) + 2 * D + j * 16);
             };
-            auto compute_tile = [&](uint32_t tb, const u32x4 (&kA)[4], const u32x4 (&vr)[4]) {
-                f32x4_t sT = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            auto compute_tile = [&](uint32_t tb, const u32x4 (&kA)[8], const u32x4 (&vr)[8]) {
+                f32x4_t s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f}, s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int st = 0; st < 4; ++st)
-                    sT = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[st], sT, 0, 0, 0);
-                float sc[4];
+                for (int st = 0; st < 4; ++st) {
+                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[st], s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[4 + st]), qB[st], s1, 0, 0, 0);
+                }
+                float sc[8];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    sc[r] = (tb + 4 * q + r < w1) ? sT[r] * c.scale_log2e : -INFINITY;
-                float mt = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+                for (int r = 0; r < 4; ++r) {
+                    sc[r] = (tb + 4 * q + r < w1) ? s0[r] * c.scale_log2e : -INFINITY;
+                    sc[4 + r] = (tb + 16 + 4 * q + r < w1) ? s1[r] * c.scale_log2e : -INFINITY;
+                }
+                float mt = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
+                                 fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
                 mt = fmaxf(mt, __shfl_xor(mt, 16));
                 mt = fmaxf(mt, __shfl_xor(mt, 32)); // the tile's first token is always valid: mt is finite
                 const float mn = fmaxf(m, mt);
                 const float alpha = fast_exp2(m - mn);
                 m = mn;
-                uint32_t ph[2], pl[2];
+                uint32_t ph[4], pl[4];
                 float psum = 0.f;
 #pragma unroll
-                for (int e = 0; e < 4; e += 2) {
+                for (int e = 0; e < 8; e += 2) {
                     const float p0 = fast_exp2(sc[e] - mn), p1 = fast_exp2(sc[e + 1] - mn);
                     psum += p0 + p1;
                     const uint32_t h0 = bf16_rne_bits(p0), h1 = bf16_rne_bits(p1);
@@ -609,36 +640,25 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
                     for (int mm = 0; mm < 8; ++mm)
                         oacc[mm] *= alpha;
                 }
-                const s16x4_t Ph = __builtin_bit_cast(s16x4_t, make_uint2(ph[0], ph[1]));
-                const s16x4_t Pl = __builtin_bit_cast(s16x4_t, make_uint2(pl[0], pl[1]));
+                const bf16x8_t Ph = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                const bf16x8_t Pl = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
 #pragma unroll
                 for (int mm = 0; mm < 8; ++mm) {
                     // element mm of each token's chunk: dword mm/2, low or high half
                     const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
-                    const uint32_t v01 = __builtin_amdgcn_perm(vr[1][mm / 2], vr[0][mm / 2], sel);
-                    const uint32_t v23 = __builtin_amdgcn_perm(vr[3][mm / 2], vr[2][mm / 2], sel);
-                    const s16x4_t Vt = __builtin_bit_cast(s16x4_t, make_uint2(v01, v23));
-                    oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Vt, Ph, oacc[mm], 0, 0, 0);
-                    oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Vt, Pl, oacc[mm], 0, 0, 0);
+                    uint32_t vt[4];
+#pragma unroll
+                    for (int pr = 0; pr < 4; ++pr)
+                        vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][mm / 2], vr[2 * pr][mm / 2], sel);
+                    const bf16x8_t Vt = as_bf16x8(make_uint4(vt[0], vt[1], vt[2], vt[3]));
+                    oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Ph, oacc[mm], 0, 0, 0);
+                    oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Pl, oacc[mm], 0, 0, 0);
                 }
             };
-            // the next tile's loads are issued before the current tile is consumed
-            u32x4 kA0[4], vr0[4], kA1[4], vr1[4];
-            uint32_t tb = w0;
-            load_tile(tb, kA0, vr0);
-            while (true) {
-                if (tb + 16 < w1)
-                    load_tile(tb + 16, kA1, vr1);
-                compute_tile(tb, kA0, vr0);
-                tb += 16;
-                if (tb >= w1)
-                    break;
-                if (tb + 16 < w1)
-                    load_tile(tb + 16, kA0, vr0);
-                compute_tile(tb, kA1, vr1);
-                tb += 16;
-                if (tb >= w1)
-                    break;
+            for (uint32_t tb = w0; tb < w1; tb += 32) {
+                u32x4 kA[8], vr[8];
+                load_tile(tb, kA, vr);
+                compute_tile(tb, kA, vr);
             }
         }
         w0 = w1;

@@ -63,12 +63,34 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             s.head0 = h0;
             s.part_stride = part_stride_of(c);
             plan.seqs.push_back(s);
+            plan.seq_req.push_back(i);
             total_cost += kItemOverheadBytes + ctx * c.hs * c.row_bytes;
         }
     }
     if (plan.seqs.empty()) {
         plan.span_first.push_back(0);
         return UKV_OK;
+    }
+    {
+        // Longest sequences first: they are cut into the most parts, and their merge should run
+        // while other workgroups still have work, not at the tail of the launch.  Stable, so the
+        // slices of one request stay adjacent (they read the same pages).
+        std::vector<uint32_t> order(plan.seqs.size());
+        for (uint32_t k = 0; k < order.size(); ++k)
+            order[k] = k;
+        auto cost_of = [&](uint32_t k) {
+            const ClassRec &c = p->classes.c[plan.seqs[k].cls];
+            return (uint64_t)plan.seqs[k].ctx_len * c.hs * c.row_bytes;
+        };
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return cost_of(x) > cost_of(y); });
+        std::vector<SeqRec> seqs(order.size());
+        std::vector<uint32_t> req(order.size());
+        for (uint32_t k = 0; k < order.size(); ++k) {
+            seqs[k] = plan.seqs[order[k]];
+            req[k] = plan.seq_req[order[k]];
+        }
+        plan.seqs.swap(seqs);
+        plan.seq_req.swap(req);
     }
 
     // Span sizes.  Workgroups are dispatched in order onto `slots` resident positions, so equal
