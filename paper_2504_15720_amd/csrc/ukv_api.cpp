@@ -4,6 +4,7 @@
 // into the workspace; the append and gather kernels read their few records in place).
 #include <algorithm>
 #include <cstring>
+#include <unordered_map>
 
 #include "ukv_internal.h"
 
@@ -297,23 +298,47 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
         return rc;
     unsigned char *h = (unsigned char *)st->host;
     std::memcpy(h + off_cls, &p->classes, sizeof(ClassTable));
+    // Entries patched by this call are handed to the append workgroups directly, so that patching
+    // and appending can share one launch; a token touching more than four pages takes two launches.
+    std::unordered_map<uint64_t, int32_t> patched;
+    for (uint32_t i = 0; i < b->n_patches; ++i)
+        patched[b->patch_entry[i]] = b->patch_page[i];
+    bool one_launch = true;
     AppendRec *recs = (AppendRec *)(h + off_recs);
-    for (uint32_t i = 0; i < n; ++i)
-        recs[i] = AppendRec{b->table_off[i], b->new_off[i], b->ctx_len[i], b->service_id[i]};
+    for (uint32_t i = 0; i < n; ++i) {
+        recs[i] = AppendRec{b->table_off[i], b->new_off[i], b->ctx_len[i], b->service_id[i], {-1, -1, -1, -1}};
+        if (b->ctx_len[i] == 0 || patched.empty())
+            continue;
+        const uint64_t T = p->classes.c[b->service_id[i]].token_bytes;
+        const uint64_t first = ((uint64_t)(b->ctx_len[i] - 1) * T) >> p->log2_page;
+        const uint64_t last = ((uint64_t)b->ctx_len[i] * T - 1) >> p->log2_page;
+        if (last - first >= 4)
+            one_launch = false;
+        for (uint64_t k = 0; k <= last - first && k < 4; ++k) {
+            auto it = patched.find(b->table_off[i] + first + k);
+            if (it != patched.end())
+                recs[i].page[k] = it->second;
+        }
+    }
     if (b->n_patches) {
         std::memcpy(h + off_pe, b->patch_entry, (size_t)b->n_patches * sizeof(uint64_t));
         std::memcpy(h + off_pp, b->patch_page, (size_t)b->n_patches * sizeof(int32_t));
     }
     // the records are small: the kernels read them straight from the pinned, device-mapped slot
     unsigned char *d = (unsigned char *)st->mapped;
-    HIP_TRY(launch_patch(b->page_table, (const uint64_t *)(d + off_pe), (const int32_t *)(d + off_pp), b->n_patches,
-                         s),
-            "launch patch kernel");
+    uint32_t patches_in_append = b->n_patches;
+    if (!one_launch) {
+        HIP_TRY(launch_patch(b->page_table, (const uint64_t *)(d + off_pe), (const int32_t *)(d + off_pp),
+                             b->n_patches, s),
+                "launch patch kernel");
+        patches_in_append = 0;
+    }
     ProfPair pp{p, 2};
     if ((rc = pp.get()) != UKV_OK)
         return rc;
     HIP_TRY(launch_append(p->base, p->log2_page, b->page_table, (const AppendRec *)(d + off_recs), n,
-                          (const ClassRec *)(d + off_cls), b->new_k, b->new_v, s, pp.ev.a, pp.ev.b),
+                          (const ClassRec *)(d + off_cls), b->new_k, b->new_v, (const uint64_t *)(d + off_pe),
+                          (const int32_t *)(d + off_pp), patches_in_append, s, pp.ev.a, pp.ev.b),
             "launch append kernel");
     pp.done();
     return stage_release_after(st, s);

@@ -77,6 +77,8 @@ struct AppendRec {
     uint64_t new_off;
     uint32_t ctx_len;
     uint32_t cls;
+    int32_t page[4]; // page ids of the first four pages the new token touches, where the same call
+                     // patches those table entries; -1 = read the table
 };
 
 struct GatherRec {
@@ -95,9 +97,10 @@ hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_he
                          float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s);
-hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
-                         const AppendRec *recs, uint32_t n, const ClassRec *classes, const void *new_k,
-                         const void *new_v, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,
+                         uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
+                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
+                         hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_gather(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                          const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_out, void *v_out,
                          hipStream_t s);

@@ -2,8 +2,9 @@
 //
 //   decode_kernel : split-KV decode attention over a mixed-service batch, one launch.
 //   reduce_kernel : merges the partial (max, sum, accumulator) triples of cut sequences.
-//   append_kernel : scatters each request's new K/V token into its pages (store side).
-//   patch_kernel  : writes new page-table entries.
+//   append_kernel : scatters each request's new K/V token into its pages (store side) and
+//                   writes the call's new page-table entries.
+//   patch_kernel  : page-table entries alone (used when a token spans more than four pages).
 //   gather_kernel : test hook, paged -> contiguous copy.
 //
 // Decode is bound by HBM: every cached K/V byte is read once per step (decode phase, section
@@ -761,10 +762,21 @@ __global__ void patch_kernel(int32_t *page_table, const uint64_t *entry, const i
         page_table[entry[i]] = page[i];
 }
 
-// One workgroup per request; each lane moves 16-byte pieces of the new token row.
-__global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, uint32_t lg, const int32_t *page_table,
-                                                     const AppendRec *recs, const ClassRec *classes,
-                                                     const uint16_t *new_k, const uint16_t *new_v) {
+// Workgroups [0, n_requests): one per request; each lane moves 16-byte pieces of the new token
+// row.  Page ids of table entries that are being patched in the same call come with the record
+// (r.page[k] >= 0 for the k-th page the token touches), so no workgroup reads an entry another one
+// is writing.  Workgroups [n_requests, ...): write the patched page-table entries.
+__global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, uint32_t lg, int32_t *page_table,
+                                                     const AppendRec *recs, uint32_t n_requests,
+                                                     const ClassRec *classes, const uint16_t *new_k,
+                                                     const uint16_t *new_v, const uint64_t *patch_entry,
+                                                     const int32_t *patch_page, uint32_t n_patches) {
+    if (blockIdx.x >= n_requests) {
+        const uint32_t i = (blockIdx.x - n_requests) * blockDim.x + threadIdx.x;
+        if (i < n_patches)
+            page_table[patch_entry[i]] = patch_page[i];
+        return;
+    }
     const AppendRec r = recs[blockIdx.x];
     if (r.ctx_len == 0)
         return;
@@ -772,12 +784,17 @@ __global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, u
     const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
     const uint32_t n_pieces = c.token_bytes / 16;
     const uint64_t stream0 = (uint64_t)(r.ctx_len - 1) * c.token_bytes;
+    const uint64_t first_slot = stream0 >> lg;
     const uint64_t page_mask = (1ull << lg) - 1;
     for (uint32_t pc = threadIdx.x; pc < n_pieces; pc += blockDim.x) {
         const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
         const uint16_t *src = (w < half ? new_k : new_v) + r.new_off + (uint64_t)h * c.d + (w % half) * 8;
         const uint64_t off = stream0 + (uint64_t)pc * 16;
-        const int32_t pg = page_table[r.table_off + (off >> lg)];
+        const uint64_t slot = off >> lg;
+        const uint32_t k = (uint32_t)(slot - first_slot);
+        int32_t pg = k < 4 ? r.page[k] : -1;
+        if (pg < 0)
+            pg = page_table[r.table_off + slot];
         uint4 *dst = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
         *dst = *reinterpret_cast<const uint4 *>(src);
     }
@@ -864,13 +881,16 @@ hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_
     return hipGetLastError();
 }
 
-hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
-                         const AppendRec *recs, uint32_t n, const ClassRec *classes, const void *new_k,
-                         const void *new_v, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
-    if (n == 0)
+hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,
+                         uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
+                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
+                         hipEvent_t ev0, hipEvent_t ev1) {
+    const uint32_t blocks = n + (n_patches + 255) / 256;
+    if (blocks == 0)
         return hipSuccess;
-    hipExtLaunchKernelGGL(append_kernel, dim3(n), dim3(256), 0, s, ev0, ev1, 0, pool_base, log2_page, page_table, recs, classes,
-                       static_cast<const uint16_t *>(new_k), static_cast<const uint16_t *>(new_v));
+    hipExtLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, s, ev0, ev1, 0, pool_base, log2_page, page_table,
+                          recs, n, classes, static_cast<const uint16_t *>(new_k),
+                          static_cast<const uint16_t *>(new_v), patch_entry, patch_page, n_patches);
     return hipGetLastError();
 }
 

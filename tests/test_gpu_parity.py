@@ -112,6 +112,32 @@ def test_edge_cases_empty_single_and_ragged():
         db.close()
 
 
+def test_small_pages_and_group_sizes_outside_the_workloads():
+    """1 KiB pages (token rows of 4 to 20 pages: page-table windows, the two-launch append) and the
+    group sizes the five workloads do not use (G = 2 at both head dims)."""
+    say("small pages, G=2 shapes")
+    services = [SHAPES["13b"], SHAPES["70b"], Service(16, 8, 128), Service(8, 4, 64), SHAPES["h12"],
+                Service(4, 1, 128)]
+    sid = np.array([0, 1, 2, 3, 4, 5, 0, 1, 2, 3, 4, 5])
+    ctx = np.array([37, 1200, 515, 64, 3, 700, 1, 33, 16, 17, 300, 31])
+    rng = np.random.default_rng(123)
+    b = make_batch(services, sid, ctx, 64 * 1024, "permutation", rng, page_bytes=1024, reserve_tokens=3,
+                   pool_seed=9)
+    db = DeviceBatch(b)
+    try:
+        for block in (512, 256):
+            U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, block)
+            db.resize_workspace()
+            _check_attention(db, b, f"block {block}")
+            U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 16 * 1024)
+            _check_attention(db, b, f"block {block}, many cuts")
+            U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 512 * 1024)
+        _check_gather(db, b)
+        _decode_steps(db, b, 3, seed=11)
+    finally:
+        db.close()
+
+
 def test_bytes_past_ctx_len_are_never_read_into_the_result():
     say("poison test")
     b = make_config(5, mini=True)
