@@ -29,13 +29,18 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def bind(cdll):
+    """Declare the return types of the oracle's entry points on a loaded library."""
+    for name in ("ukv_oracle_gather", "ukv_oracle_append", "ukv_oracle_attention",
+                 "ukv_oracle_attention_range", "ukv_oracle_merge", "ukv_oracle_threads"):
+        getattr(cdll, name).restype = C.c_int
+    return cdll
+
+
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
-        for name in ("ukv_oracle_gather", "ukv_oracle_append", "ukv_oracle_attention",
-                     "ukv_oracle_attention_range", "ukv_oracle_merge", "ukv_oracle_threads"):
-            getattr(_lib, name).restype = C.c_int
+        _lib = bind(C.CDLL(build()))
     return _lib
 
 

@@ -214,6 +214,36 @@ def test_page_renaming_gives_bit_identical_output():
         db2.close()
 
 
+def test_many_calls_in_flight_on_a_side_stream():
+    """More calls than staging slots are enqueued without synchronising, on a non-default stream;
+    every call's output must still be that call's (plans and records are not overwritten early)."""
+    import torch
+    say("24 calls in flight on a side stream")
+    b = make_config(5, mini=True)
+    db = DeviceBatch(b, profile=True)
+    try:
+        rng = np.random.default_rng(31)
+        qs = [b.draw_step_inputs(rng)[0] for _ in range(24)]
+        q_dev = [torch.from_numpy(q.view(np.int16)).to(db.dev) for q in qs]
+        outs = []
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for k in range(24):
+                db.q_t.copy_(q_dev[k], non_blocking=True)
+                db.decode()
+                outs.append(db.out_t.clone())
+        torch.cuda.synchronize()
+        prof = U.ukv_profile_read(db.pool)
+        assert prof.n_decode == 24 and prof.decode_ms > 0.0
+        for k in (0, 7, 8, 9, 23):
+            ref = oracle.attention(b, b.pool, q=qs[k])
+            err = float(np.max(np.abs(outs[k].cpu().numpy().astype(np.float64) - ref)))
+            assert err <= ATOL, f"call {k}: max |err| {err}"
+    finally:
+        db.close()
+
+
 def test_errors_from_the_compute_calls():
     b = make_config(1, mini=True)
     db = DeviceBatch(b)
