@@ -89,6 +89,9 @@ def main():
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
     ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")
+    ap.add_argument("--layout", choices=["merged", "split"], default="merged",
+                    help="split = one block stream and table per (request, kv head), the alternative of section 4.4")
+    ap.add_argument("--split-page-bytes", type=int, default=0, help="block size of the split layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="skip grow+append in the step (diagnostic)")
     args = ap.parse_args()
@@ -106,7 +109,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     t_gen = time.perf_counter()
     # tables must have room for every step's new token
-    b = make_config(args.config, reserve_tokens=args.steps + args.warmup + 1)
+    b = make_config(args.config, reserve_tokens=args.steps + args.warmup + 1, fill_pool=args.layout == "merged")
+    if args.layout == "split":
+        from synth import to_split_layout
+        b = to_split_layout(b, pool_seed=7, page_bytes=args.split_page_bytes or None)
     t_gen = time.perf_counter() - t_gen
     db = DeviceBatch(b, profile=True)
     if args.block:
@@ -173,6 +179,8 @@ def main():
                    "kv_bytes_per_step": int(kv_per_step), "pool_pages": b.n_pages,
                    "stated_pool_pages": b.notes.get("stated_pages"), "page_bytes": b.page_bytes,
                    "step": "attention only" if args.attention_only else "grow + append + attention",
+                   "layout": args.layout, "block_table_entries": int(b.pages_owned().sum()),
+                   "pages_in_use": int(b.stack.used_pages),
                    "kv_storage": "bf16", "decode_workgroups": info.n_spans, "work_items": info.n_items,
                    "block_threads": U.ukv_get_param(db.pool, U.UKV_PARAM_BLOCK_THREADS)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),

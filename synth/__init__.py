@@ -18,4 +18,5 @@ from .workloads import (  # noqa: F401
     normal_bf16,
     lockstep_order,
     pages_for_tokens,
+    to_split_layout,
 )

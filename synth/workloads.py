@@ -418,4 +418,57 @@ def make_config(index: int, *, mini: bool = False, fill_pool: bool = True, seed:
     b.notes.update(notes)
     b.notes["steps"] = c["steps"]
     b.notes["seed"] = seed
+    b.notes["reserve_tokens"] = max(c["steps"], 4) if reserve_tokens is None else reserve_tokens
     return b
+
+
+# --------------------------------------------------------------------------
+# the split-block alternative (section 4.4): one block stream per (request, kv head)
+# --------------------------------------------------------------------------
+def to_split_layout(b: Batch, *, fill_pool: bool = True, pool_seed: int = 0,
+                    page_bytes: Optional[int] = None) -> Batch:
+    """The same requests laid out with split cache blocks: every kv head of every request owns
+    its own blocks and its own block table (what section 4.4 calls the split method).
+
+    Expressed with the same descriptor: request i of a service (Q, H, d) becomes H requests of a
+    one-kv-head service (Q/H, 1, d); q, out and new-token offsets point into the same arrays as
+    before, so results are comparable element by element.  Pages are handed out from a fresh LIFO
+    stack over a pool of the same byte size with all (request, head) streams growing in lock-step.
+    page_bytes: block size of the split layout (default: the merged layout's page size).
+    """
+    page_bytes = b.page_bytes if page_bytes is None else page_bytes
+    n_pages = b.n_pages * b.page_bytes // page_bytes
+    services = [Service(s.group, 1, s.head_dim, s.scale) for s in b.services]
+    H = np.array([s.n_kv_heads for s in b.services], dtype=np.int64)[b.service_id]
+    G = np.array([s.group for s in b.services], dtype=np.int64)[b.service_id]
+    d = np.array([s.head_dim for s in b.services], dtype=np.int64)[b.service_id]
+    req = np.repeat(np.arange(b.n_requests), H)
+    first = np.cumsum(H) - H
+    head = np.arange(req.size) - np.repeat(first, H)
+    sid = b.service_id[req]
+    ctx = b.ctx_len[req]
+    tb = (4 * d)[req]
+    reserve = int(b.notes.get("reserve_tokens", 4))
+    npg = pages_for_tokens(ctx, tb, page_bytes)
+    cap = np.maximum(pages_for_tokens(ctx.astype(np.int64) + reserve, tb, page_bytes), 1)
+    table_off = (np.cumsum(cap) - cap).astype(np.uint64)
+    page_table = np.full(int(cap.sum()), -1, dtype=np.int32)
+    stack = PageStack(n_pages)
+    if int(npg.sum()) > stack.free_pages:
+        raise MemoryError(f"split layout needs {int(npg.sum())} pages, pool has {stack.free_pages}")
+    got = _alloc_lockstep(stack, npg, tb, page_bytes)
+    for k in range(req.size):
+        page_table[int(table_off[k]):int(table_off[k]) + got[k].size] = got[k]
+    q_off = (b.q_off[req].astype(np.int64) + head * (G * d)[req]).astype(np.uint64)
+    new_off = (b.new_off[req].astype(np.int64) + head * d[req]).astype(np.uint64)
+    pool = None
+    if fill_pool:
+        pool = np.empty(n_pages * page_bytes // 2, dtype=np.uint16)
+        _fill_normal_bf16_parallel(pool, pool_seed)
+    out = Batch(page_bytes=page_bytes, n_pages=n_pages, services=services, service_id=sid.astype(np.uint32),
+                ctx_len=ctx.astype(np.uint32), table_off=table_off, table_cap=cap, page_table=page_table,
+                q=b.q, q_off=q_off, out_off=q_off.copy(), out_elems=b.out_elems, new_off=new_off,
+                new_elems=b.new_elems, stack=stack, pool=pool, name=b.name + "-split")
+    out.notes.update(b.notes)
+    out.notes["split_of"] = (req, head)
+    return out

@@ -60,3 +60,30 @@ def build_paged_pool(pool_u16, page_bytes, table, k_bits, v_bits, first_token=0)
                     assert page >= 0
                     byte = page * page_bytes + stream_byte % page_bytes
                     pool_u16[byte // 2] = src[t, h, j]
+
+
+def copy_logical_kv_to_split(merged, split, gather):
+    """Fill the split-layout pool with the K/V the merged-layout batch holds (test-side data movement).
+
+    gather(pool, page_bytes, table, H, d, n) -> (K[n,H,d], V[n,H,d]) reads the merged layout; every
+    (request, head) stream of the split batch is then written row by row: token t of a one-head
+    stream sits at stream byte t * 4d.
+    """
+    req, head = split.notes["split_of"]
+    cache = {}
+    P = split.page_bytes
+    for k in range(split.n_requests):
+        i, h = int(req[k]), int(head[k])
+        n = int(split.ctx_len[k])
+        if n == 0:
+            continue
+        if i not in cache:
+            sv = merged.service_of(i)
+            cache = {i: gather(merged.pool, merged.page_bytes, merged.table_of(i), sv.n_kv_heads, sv.head_dim, n)}
+        K, V = cache[i]
+        d = K.shape[2]
+        rows = np.concatenate([K[:, h, :], V[:, h, :]], axis=1)          # [n, 2d] bf16 bits
+        stream = np.arange(n, dtype=np.int64) * (4 * d)
+        page = split.table_of(k)[stream // P].astype(np.int64)
+        base = (page * P + stream % P) // 2
+        split.pool[base[:, None] + np.arange(2 * d)[None, :]] = rows

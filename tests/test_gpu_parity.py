@@ -10,7 +10,8 @@ import pytest
 
 import paper_2504_15720_amd as U
 from oracle import oracle
-from synth import SHAPES, Service, make_batch, make_config
+from synth import SHAPES, Service, make_batch, make_config, to_split_layout
+from tests.reference_math import copy_logical_kv_to_split
 from tests.ukv_harness import DeviceBatch
 
 pytestmark = pytest.mark.gpu
@@ -212,6 +213,26 @@ def test_page_renaming_gives_bit_identical_output():
         assert np.array_equal(db2.out_host(), first)
     finally:
         db2.close()
+
+
+@pytest.mark.parametrize("page_bytes", [None, 1024])
+def test_split_block_layout_matches_oracle_and_merged_layout(page_bytes):
+    """The split-block alternative of section 4.4, run through the same entry points: one request
+    per (request, kv head) of a one-kv-head service."""
+    say(f"split layout, page_bytes {page_bytes}")
+    b = make_config(5, mini=True)
+    s = to_split_layout(b, page_bytes=page_bytes)
+    copy_logical_kv_to_split(b, s, oracle.gather)
+    merged_ref = oracle.attention(b, b.pool)
+    db = DeviceBatch(s)
+    try:
+        _check_attention(db, s, "split layout")
+        got = db.out_host().astype(np.float64)
+        assert float(np.max(np.abs(got - merged_ref))) <= ATOL      # same logical K/V, other layout
+        _check_gather(db, s)
+        _decode_steps(db, s, 3, seed=17)
+    finally:
+        db.close()
 
 
 def test_many_calls_in_flight_on_a_side_stream():

@@ -12,9 +12,9 @@ import numpy as np
 import pytest
 
 from oracle import oracle
-from synth import Service, SHAPES, make_batch, make_config
-from tests.reference_math import (bits_to_f64, build_paged_pool, contiguous_attention, f32_to_bits,
-                                  torch_sdpa_attention)
+from synth import Service, SHAPES, make_batch, make_config, to_split_layout
+from tests.reference_math import (bits_to_f64, build_paged_pool, contiguous_attention, copy_logical_kv_to_split,
+                                  f32_to_bits, torch_sdpa_attention)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "address_map.txt")
 
@@ -324,3 +324,28 @@ def test_oracle_rejects_missing_pages():
     b = _OneRequest(shape, 20, np.array([0, -1, 1], np.int32), np.zeros((2, 8), np.uint16), 256)
     with pytest.raises(RuntimeError):
         oracle.attention(b, np.zeros(4 * 128, np.uint16))
+
+
+# ---------------------------------------------------------------- split-block layout
+@pytest.mark.parametrize("page_bytes", [None, 1024])
+def test_split_block_layout_gives_the_same_attention(page_bytes):
+    """Section 4.4's alternative (a block stream per kv head) changes where bytes live, not the result."""
+    b = make_config(3, mini=True)
+    s = to_split_layout(b, page_bytes=page_bytes)
+    assert s.kv_bytes() == b.kv_bytes() and s.n_requests == sum(b.service_of(i).n_kv_heads for i in range(b.n_requests))
+    copy_logical_kv_to_split(b, s, oracle.gather)
+    ref = oracle.attention(b, b.pool)
+    got = oracle.attention(s, s.pool)
+    assert np.max(np.abs(ref - got)) < 1e-13
+    # Table accounting for one layer of the 7B shape.  Equal tokens per block (2 tokens: a merged
+    # block of 32 KiB against per-head blocks of 1 KiB): the split table is n_kv_heads = 32 times
+    # larger; over 32 layers that is the 1024 x of section 4.4.  Equal block BYTES instead (the
+    # workloads here: 16 KiB either way) gives tables of practically equal size.
+    from synth import pages_for_tokens
+    sv = SHAPES["7b"]
+    n = 4096
+    merged_entries = int(pages_for_tokens(n, sv.token_bytes, 32768))
+    split_entries = sv.n_kv_heads * int(pages_for_tokens(n, sv.head_row_bytes, 1024))
+    assert split_entries == 32 * merged_entries and 32 * 32 == 1024
+    if page_bytes is None:
+        assert abs(int(s.pages_owned().sum()) / int(b.pages_owned().sum()) - 1.0) < 0.2
