@@ -139,10 +139,19 @@ size_t ukv_decode_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests);
 int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes,
                          void *stream);
 
-/* Test hook: copy tokens [0, ctx_len[i]) of every request out of the pool into contiguous
+/* Bulk load (also the tests' view of the pool): copy tokens [0, ctx_len[i]) of every request out of the pool into contiguous
  * k_out / v_out DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i] (HOST). */
 int ukv_gather(ukv_pool_t *pool, const ukv_batch_t *batch, void *k_out, void *v_out, const uint64_t *kv_off,
                void *stream);
+
+/* Bulk store: the inverse of ukv_gather.  Writes tokens [0, ctx_len[i]) of every request from
+ * contiguous k_in / v_in DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i]
+ * (HOST) into the request's pages, bit for bit.  This is how a prompt's K/V enter the cache after
+ * the prefill phase (section 2.1), and, together with ukv_gather, how an ongoing request's cache
+ * moves to another pool when the placement changes (request migration, section 5).  The table
+ * entries for ceil(ctx_len*T/page_bytes) pages must already be in page_table. */
+int ukv_scatter(ukv_pool_t *pool, const ukv_batch_t *batch, const void *k_in, const void *v_in,
+                const uint64_t *kv_off, void *stream);
 
 /* Host-only view of the split-KV plan for a batch (no device work): how the launch would be cut. */
 typedef struct {

@@ -31,7 +31,7 @@ def build(force: bool = False) -> str:
 
 def bind(cdll):
     """Declare the return types of the oracle's entry points on a loaded library."""
-    for name in ("ukv_oracle_gather", "ukv_oracle_append", "ukv_oracle_attention",
+    for name in ("ukv_oracle_gather", "ukv_oracle_scatter", "ukv_oracle_append", "ukv_oracle_attention",
                  "ukv_oracle_attention_range", "ukv_oracle_merge", "ukv_oracle_threads"):
         getattr(cdll, name).restype = C.c_int
     return cdll
@@ -74,6 +74,20 @@ def gather(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, n_kv_heads:
                                C.c_uint32(head_dim), C.c_uint64(n_tokens), _p(k, C.c_uint16), _p(v, C.c_uint16))
     _check(rc, "gather")
     return k, v
+
+
+def scatter(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, k: np.ndarray, v: np.ndarray) -> None:
+    """Write contiguous bf16 bit patterns K[n,H,d], V[n,H,d] as tokens [0, n) of one request, in place."""
+    lib = _load()
+    pool = pool_u16.view(np.uint8)
+    assert pool.flags.writeable and pool.flags.c_contiguous
+    table = _arr(table, np.int32)
+    k, v = _arr(k, np.uint16), _arr(v, np.uint16)
+    n, H, d = k.shape
+    rc = lib.ukv_oracle_scatter(_p(pool, C.c_uint8), C.c_uint64(pool.size), C.c_uint32(page_bytes),
+                                _p(table, C.c_int32), C.c_uint64(table.size), C.c_uint32(H), C.c_uint32(d),
+                                C.c_uint64(n), _p(k, C.c_uint16), _p(v, C.c_uint16))
+    _check(rc, "scatter")
 
 
 def _per_request_shapes(batch):

@@ -102,6 +102,27 @@ int ukv_oracle_gather(const uint8_t *pool, uint64_t pool_bytes, uint32_t page_by
     return ORC_OK;
 }
 
+/* The inverse of gather: write contiguous k_in[n][H][d], v_in[n][H][d] as tokens [0, n) of one
+ * request's stream (bulk store after prefill, or the receiving side of a migration). */
+int ukv_oracle_scatter(uint8_t *pool, uint64_t pool_bytes, uint32_t page_bytes, const int32_t *table,
+                       uint64_t table_len, uint32_t n_kv_heads, uint32_t head_dim, uint64_t n_tokens,
+                       const uint16_t *k_in, const uint16_t *v_in)
+{
+    if (!shape_ok(page_bytes, n_kv_heads, n_kv_heads, head_dim))
+        return ORC_EINVAL;
+    uint64_t n_pages = pool_bytes / page_bytes;
+    uint64_t row = 4ull * head_dim, tok = row * n_kv_heads;
+    for (uint64_t t = 0; t < n_tokens; ++t)
+        for (uint64_t h = 0; h < n_kv_heads; ++h) {
+            uint64_t a = head_row_address(page_bytes, n_pages, table, table_len, tok, row, t, h);
+            if (a == UINT64_MAX)
+                return ORC_ERANGE;
+            memcpy(pool + a, k_in + (t * n_kv_heads + h) * head_dim, 2ull * head_dim);
+            memcpy(pool + a + 2ull * head_dim, v_in + (t * n_kv_heads + h) * head_dim, 2ull * head_dim);
+        }
+    return ORC_OK;
+}
+
 /* Append: for request i write new_k[i][H][d], new_v[i][H][d] as token index
  * ctx_len[i]-1 of its stream (ctx_len already counts the new token). */
 int ukv_oracle_append(uint8_t *pool, uint64_t pool_bytes, uint32_t page_bytes, uint32_t n_requests,

@@ -24,6 +24,7 @@ UKV_PARAM_SLOTS, UKV_PARAM_TAPER = 7, 8
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",
     "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_gather",
+    "ukv_scatter",
     "ukv_plan_decode", "ukv_set_param", "ukv_get_param", "ukv_profile_read", "ukv_strerror", "ukv_last_error",
 ]
 
@@ -92,6 +93,7 @@ def lib():
         L.ukv_decode_workspace_bytes.restype = C.c_size_t
         L.ukv_decode_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
         L.ukv_gather.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
+        L.ukv_scatter.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_plan_decode.argtypes = [vp, C.POINTER(ukv_batch_t), C.POINTER(ukv_plan_info_t), vp, C.c_uint32]
         L.ukv_set_param.argtypes = [vp, C.c_int, C.c_int64]
         L.ukv_get_param.argtypes = [vp, C.c_int, C.POINTER(C.c_int64)]
@@ -202,6 +204,11 @@ def ukv_decode_attention(pool: int, batch: BatchDesc, workspace_ptr: int, ws_byt
 def ukv_gather(pool: int, batch: BatchDesc, k_out_ptr: int, v_out_ptr: int, kv_off, stream: int = 0) -> None:
     kv_off = np.ascontiguousarray(kv_off, np.uint64)
     _check(lib().ukv_gather(pool, C.byref(batch.c), k_out_ptr, v_out_ptr, kv_off.ctypes.data, stream), "ukv_gather")
+
+
+def ukv_scatter(pool: int, batch: BatchDesc, k_in_ptr: int, v_in_ptr: int, kv_off, stream: int = 0) -> None:
+    kv_off = np.ascontiguousarray(kv_off, np.uint64)
+    _check(lib().ukv_scatter(pool, C.byref(batch.c), k_in_ptr, v_in_ptr, kv_off.ctypes.data, stream), "ukv_scatter")
 
 
 def ukv_plan_decode(pool: int, batch: BatchDesc, want_items: bool = True):

@@ -344,20 +344,29 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
     return stage_release_after(st, s);
 }
 
-int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, const uint64_t *kv_off,
-               void *stream) {
-    if (!p || !b || !k_out || !v_out || !kv_off || !b->page_table) {
+static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, void *k_io, void *v_io,
+                       const uint64_t *kv_off, void *stream) {
+    if (!p || !b || !k_io || !v_io || !kv_off || !b->page_table) {
         set_error("null argument");
         return UKV_EINVAL;
     }
     const uint32_t n = b->n_requests;
     if (n == 0)
         return UKV_OK;
-    for (uint32_t i = 0; i < n; ++i)
+    if (!b->service_id || !b->ctx_len || !b->table_off) {
+        set_error("batch host arrays must be non-null");
+        return UKV_EINVAL;
+    }
+    for (uint32_t i = 0; i < n; ++i) {
         if (b->service_id[i] >= p->n_services || (kv_off[i] & 7)) {
             set_error("service_id out of range or kv_off not a multiple of 8");
             return UKV_EINVAL;
         }
+        if (ukv_pages_for_tokens(p, b->service_id[i], b->ctx_len[i]) > p->n_pages) {
+            set_error("ctx_len exceeds what the pool can hold");
+            return UKV_EINVAL;
+        }
+    }
     hipStream_t s = (hipStream_t)stream;
     const size_t off_recs = align_up(sizeof(ClassTable));
     const size_t total = align_up(off_recs + (size_t)n * sizeof(GatherRec));
@@ -371,10 +380,20 @@ int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, co
     for (uint32_t i = 0; i < n; ++i)
         recs[i] = GatherRec{b->table_off[i], kv_off[i], b->ctx_len[i], b->service_id[i]};
     unsigned char *d = (unsigned char *)st->mapped;
-    HIP_TRY(launch_gather(p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs), n,
-                          (const ClassRec *)d, k_out, v_out, s),
-            "launch gather kernel");
+    HIP_TRY(launch_copy_tokens(to_pool, p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs), n,
+                               (const ClassRec *)d, k_io, v_io, s),
+            "launch token copy kernel");
     return stage_release_after(st, s);
+}
+
+int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, const uint64_t *kv_off,
+               void *stream) {
+    return copy_tokens(false, p, b, k_out, v_out, kv_off, stream);
+}
+
+int ukv_scatter(ukv_pool_t *p, const ukv_batch_t *b, const void *k_in, const void *v_in, const uint64_t *kv_off,
+                void *stream) {
+    return copy_tokens(true, p, b, const_cast<void *>(k_in), const_cast<void *>(v_in), kv_off, stream);
 }
 
 int ukv_profile_read(ukv_pool_t *p, ukv_profile_t *out) {

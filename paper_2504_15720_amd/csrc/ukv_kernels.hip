@@ -5,7 +5,7 @@
 //   append_kernel : scatters each request's new K/V token into its pages (store side) and
 //                   writes the call's new page-table entries.
 //   patch_kernel  : page-table entries alone (used when a token spans more than four pages).
-//   gather_kernel : test hook, paged -> contiguous copy.
+//   copy_tokens_kernel : paged <-> contiguous copy of whole requests (gather / scatter).
 //
 // Decode is bound by HBM: every cached K/V byte is read once per step (decode phase, section
 // 2.1; merged blocks are chosen for read locality, section 4.4).  The design therefore keeps
@@ -800,10 +800,13 @@ __global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, u
     }
 }
 
-// grid (request, y): workgroups of one request stride over its tokens.
-__global__ void __launch_bounds__(256) gather_kernel(const unsigned char *pool_base, uint32_t lg,
-                                                     const int32_t *page_table, const GatherRec *recs,
-                                                     const ClassRec *classes, uint16_t *k_out, uint16_t *v_out) {
+// Paged <-> contiguous copy of whole requests.  grid (request, y): the workgroups of one request
+// stride over its tokens; each lane moves 16-byte pieces of a token row.  TO_POOL = false gathers
+// (pool -> k_io/v_io), true scatters (k_io/v_io -> pool).
+template <bool TO_POOL>
+__global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_base, uint32_t lg,
+                                                          const int32_t *page_table, const GatherRec *recs,
+                                                          const ClassRec *classes, uint16_t *k_io, uint16_t *v_io) {
     const GatherRec r = recs[blockIdx.x];
     const ClassRec c = classes[r.cls];
     const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
@@ -815,10 +818,13 @@ __global__ void __launch_bounds__(256) gather_kernel(const unsigned char *pool_b
             const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
             const uint64_t off = stream0 + (uint64_t)pc * 16;
             const int32_t pg = page_table[r.table_off + (off >> lg)];
-            const uint4 v = *reinterpret_cast<const uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) +
-                                                             (off & page_mask));
-            uint16_t *dst = (w < half ? k_out : v_out) + r.kv_off + ((uint64_t)t * c.n_kv + h) * c.d + (w % half) * 8;
-            *reinterpret_cast<uint4 *>(dst) = v;
+            uint4 *in_pool = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
+            uint4 *flat = reinterpret_cast<uint4 *>((w < half ? k_io : v_io) + r.kv_off +
+                                                    ((uint64_t)t * c.n_kv + h) * c.d + (w % half) * 8);
+            if (TO_POOL)
+                *in_pool = *flat;
+            else
+                *flat = *in_pool;
         }
     }
 }
@@ -894,13 +900,17 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
     return hipGetLastError();
 }
 
-hipError_t launch_gather(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
-                         const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_out, void *v_out,
-                         hipStream_t s) {
+hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
+                              const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
+                              hipStream_t s) {
     if (n == 0)
         return hipSuccess;
-    hipLaunchKernelGGL(gather_kernel, dim3(n, 32), dim3(256), 0, s, pool_base, log2_page, page_table, recs, classes,
-                       static_cast<uint16_t *>(k_out), static_cast<uint16_t *>(v_out));
+    if (to_pool)
+        hipLaunchKernelGGL(copy_tokens_kernel<true>, dim3(n, 64), dim3(256), 0, s, pool_base, log2_page, page_table,
+                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
+    else
+        hipLaunchKernelGGL(copy_tokens_kernel<false>, dim3(n, 64), dim3(256), 0, s, pool_base, log2_page, page_table,
+                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
     return hipGetLastError();
 }
 

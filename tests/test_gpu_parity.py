@@ -235,6 +235,38 @@ def test_split_block_layout_matches_oracle_and_merged_layout(page_bytes):
         db.close()
 
 
+def test_migration_gather_then_scatter_into_another_pool():
+    """Request migration (section 5): gather every request out of one pool and scatter it into a
+    differently fragmented pool; the new pool image is bit-exact and attention is unchanged."""
+    say("migration: gather -> scatter")
+    src = make_config(5, mini=True)
+    dst = make_config(5, mini=True, seed=991)            # same recipe, other draw: other lengths and pages
+    # the destination takes over the source's requests (service, length, q) but keeps its own placement
+    rng = np.random.default_rng(5)
+    dst = make_batch(src.services, src.service_id, src.ctx_len, src.n_pages, "permutation", rng, reserve_tokens=4,
+                     pool_seed=3)
+    dst.q = src.q.copy()
+    dst.pool[:] = 0xABCD
+    a, bdev = DeviceBatch(src), DeviceBatch(dst)
+    try:
+        k, v, kv_off, sizes = a.gather_device()
+        bdev.scatter(k, v, kv_off)
+        expect = dst.pool.copy()
+        for i in range(src.n_requests):
+            sv = src.service_of(i)
+            n = int(src.ctx_len[i])
+            gk, gv = oracle.gather(src.pool, src.page_bytes, src.table_of(i), sv.n_kv_heads, sv.head_dim, n)
+            oracle.scatter(expect, dst.page_bytes, dst.table_of(i), gk, gv)
+        assert np.array_equal(bdev.pool_host(), expect), "scattered pool image differs"
+        dst.pool = expect
+        bdev.decode()
+        ref = oracle.attention(src, src.pool)
+        assert float(np.max(np.abs(bdev.out_host().astype(np.float64) - ref))) <= ATOL
+    finally:
+        a.close()
+        bdev.close()
+
+
 def test_many_calls_in_flight_on_a_side_stream():
     """More calls than staging slots are enqueued without synchronising, on a non-default stream;
     every call's output must still be that call's (plans and records are not overwritten early)."""

@@ -37,6 +37,9 @@ MUTATIONS = {
         "            memcpy(pool + a + 2ull * d, new_k + new_off[i] + h * d, 2ull * d);"),
     "append one token late": ("t = (uint64_t)ctx_len[i] - 1;", "t = (uint64_t)ctx_len[i];"),
     "merge weights inverted": ("double w = exp(m[c] - M);", "double w = exp(M - m[c]);"),
+    "scatter writes head rows token-minor": (
+        "memcpy(pool + a, k_in + (t * n_kv_heads + h) * head_dim, 2ull * head_dim);",
+        "memcpy(pool + a, k_in + (h * n_tokens + t) * head_dim, 2ull * head_dim);"),
     "gather reads V at the K offset": (
         "memcpy(v_out + (t * n_kv_heads + h) * head_dim, pool + a + 2ull * head_dim, 2ull * head_dim);",
         "memcpy(v_out + (t * n_kv_heads + h) * head_dim, pool + a, 2ull * head_dim);"),
@@ -56,6 +59,7 @@ def _run_pins():
     pins.test_two_token_logistic_closed_form()
     pins.test_split_and_merge_equals_whole()
     pins.test_append_touches_exactly_the_new_token(5)
+    pins.test_scatter_places_every_element_and_inverts_gather("13b")
 
 
 def test_unmutated_copy_passes(tmp_path, monkeypatch):

@@ -319,6 +319,24 @@ def test_append_touches_exactly_the_new_token(cfg):
     assert np.array_equal(ref, b.pool)
 
 
+@pytest.mark.parametrize("name", ["h12", "13b", "8b"])
+def test_scatter_places_every_element_and_inverts_gather(name):
+    shape = SHAPES[name]
+    rng = np.random.default_rng(77)
+    n, P = 11, 16384
+    need = -(-n * shape.token_bytes // P)
+    table = rng.permutation(need + 4)[:need].astype(np.int32)
+    k = f32_to_bits(rng.standard_normal((n, shape.n_kv_heads, shape.head_dim)).astype(np.float32))
+    v = f32_to_bits(rng.standard_normal((n, shape.n_kv_heads, shape.head_dim)).astype(np.float32))
+    pool = np.full((need + 4) * P // 2, 0xABCD, np.uint16)
+    ref = pool.copy()
+    oracle.scatter(pool, P, table, k, v)
+    build_paged_pool(ref, P, table, k, v)                 # element-by-element placement, test-side
+    assert np.array_equal(pool, ref)
+    gk, gv = oracle.gather(pool, P, table, shape.n_kv_heads, shape.head_dim, n)
+    assert np.array_equal(gk, k) and np.array_equal(gv, v)
+
+
 def test_oracle_rejects_missing_pages():
     shape = Service(2, 2, 8)
     b = _OneRequest(shape, 20, np.array([0, -1, 1], np.int32), np.zeros((2, 8), np.uint16), 256)

@@ -81,6 +81,24 @@ class DeviceBatch:
     def pool_host(self) -> np.ndarray:
         return self.pool_t.cpu().numpy().view(np.uint16)
 
+    def kv_layout(self):
+        """Element offsets / sizes of every request in the contiguous K (or V) array of gather/scatter."""
+        b = self.b
+        tok_elems = np.array([b.services[s].n_kv_heads * b.services[s].head_dim for s in b.service_id], np.int64)
+        sizes = b.ctx_len.astype(np.int64) * tok_elems
+        return (np.cumsum(sizes) - sizes).astype(np.uint64), sizes
+
+    def scatter(self, k_t, v_t, kv_off):
+        U.ukv_scatter(self.pool, self.desc(), k_t.data_ptr(), v_t.data_ptr(), kv_off, self.stream())
+
+    def gather_device(self):
+        kv_off, sizes = self.kv_layout()
+        total = int(sizes.sum())
+        k = self.torch.zeros(max(total, 8), dtype=self.torch.int16, device=self.dev)
+        v = self.torch.zeros(max(total, 8), dtype=self.torch.int16, device=self.dev)
+        U.ukv_gather(self.pool, self.desc(), k.data_ptr(), v.data_ptr(), kv_off, self.stream())
+        return k, v, kv_off, sizes
+
     def gather(self):
         b = self.b
         tok_elems = np.array([b.services[s].n_kv_heads * b.services[s].head_dim for s in b.service_id], np.int64)
