@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstring>
 #include <unordered_map>
+#include <vector>
 
 #include "ukv_internal.h"
 
@@ -368,20 +369,29 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, void *
         }
     }
     hipStream_t s = (hipStream_t)stream;
+    // one record (= one workgroup) per chunk of about 1 MiB of a request's stream
+    std::vector<GatherRec> chunks;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t T = p->classes.c[b->service_id[i]].token_bytes;
+        const uint32_t step = std::max<uint32_t>(1, (1u << 20) / T);
+        for (uint32_t t0 = 0; t0 < b->ctx_len[i]; t0 += step)
+            chunks.push_back(GatherRec{b->table_off[i], kv_off[i], t0, std::min(b->ctx_len[i], t0 + step),
+                                       b->service_id[i], 0});
+    }
+    if (chunks.empty())
+        return UKV_OK;
     const size_t off_recs = align_up(sizeof(ClassTable));
-    const size_t total = align_up(off_recs + (size_t)n * sizeof(GatherRec));
+    const size_t total = align_up(off_recs + chunks.size() * sizeof(GatherRec));
     int rc;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
     unsigned char *h = (unsigned char *)st->host;
     std::memcpy(h, &p->classes, sizeof(ClassTable));
-    GatherRec *recs = (GatherRec *)(h + off_recs);
-    for (uint32_t i = 0; i < n; ++i)
-        recs[i] = GatherRec{b->table_off[i], kv_off[i], b->ctx_len[i], b->service_id[i]};
+    std::memcpy(h + off_recs, chunks.data(), chunks.size() * sizeof(GatherRec));
     unsigned char *d = (unsigned char *)st->mapped;
-    HIP_TRY(launch_copy_tokens(to_pool, p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs), n,
-                               (const ClassRec *)d, k_io, v_io, s),
+    HIP_TRY(launch_copy_tokens(to_pool, p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs),
+                               (uint32_t)chunks.size(), (const ClassRec *)d, k_io, v_io, s),
             "launch token copy kernel");
     return stage_release_after(st, s);
 }

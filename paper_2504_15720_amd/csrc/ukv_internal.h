@@ -81,11 +81,12 @@ struct AppendRec {
                      // patches those table entries; -1 = read the table
 };
 
-struct GatherRec {
+struct GatherRec { // tokens [t0, t1) of one request
     uint64_t table_off;
     uint64_t kv_off;
-    uint32_t ctx_len;
+    uint32_t t0, t1;
     uint32_t cls;
+    uint32_t pad_;
 };
 
 // ---- kernel launchers (ukv_kernels.hip) ----

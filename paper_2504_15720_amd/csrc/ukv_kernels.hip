@@ -800,9 +800,10 @@ __global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, u
     }
 }
 
-// Paged <-> contiguous copy of whole requests.  grid (request, y): the workgroups of one request
-// stride over its tokens; each lane moves 16-byte pieces of a token row.  TO_POOL = false gathers
-// (pool -> k_io/v_io), true scatters (k_io/v_io -> pool).
+// Paged <-> contiguous copy.  One workgroup per record = tokens [t0, t1) of one request (the
+// host cuts requests into chunks of about 1 MiB); the (token, 16-byte piece) pairs of the chunk
+// are spread over the lanes, four in flight per lane.  TO_POOL = false gathers (pool ->
+// k_io/v_io), true scatters (k_io/v_io -> pool).
 template <bool TO_POOL>
 __global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_base, uint32_t lg,
                                                           const int32_t *page_table, const GatherRec *recs,
@@ -812,20 +813,36 @@ __global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_ba
     const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
     const uint32_t n_pieces = c.token_bytes / 16;
     const uint64_t page_mask = (1ull << lg) - 1;
-    for (uint32_t t = blockIdx.y; t < r.ctx_len; t += gridDim.y) {
-        const uint64_t stream0 = (uint64_t)t * c.token_bytes;
-        for (uint32_t pc = threadIdx.x; pc < n_pieces; pc += blockDim.x) {
-            const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
-            const uint64_t off = stream0 + (uint64_t)pc * 16;
-            const int32_t pg = page_table[r.table_off + (off >> lg)];
-            uint4 *in_pool = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
-            uint4 *flat = reinterpret_cast<uint4 *>((w < half ? k_io : v_io) + r.kv_off +
-                                                    ((uint64_t)t * c.n_kv + h) * c.d + (w % half) * 8);
-            if (TO_POOL)
-                *in_pool = *flat;
-            else
-                *flat = *in_pool;
-        }
+    const uint64_t total = (uint64_t)(r.t1 - r.t0) * n_pieces;
+    auto addrs = [&](uint64_t idx, uint4 *&in_pool, uint4 *&flat) {
+        const uint32_t t = r.t0 + (uint32_t)(idx / n_pieces), pc = (uint32_t)(idx % n_pieces);
+        const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
+        const uint64_t off = (uint64_t)t * c.token_bytes + (uint64_t)pc * 16;
+        const int32_t pg = page_table[r.table_off + (off >> lg)];
+        in_pool = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
+        flat = reinterpret_cast<uint4 *>((w < half ? k_io : v_io) + r.kv_off + ((uint64_t)t * c.n_kv + h) * c.d +
+                                         (w % half) * 8);
+    };
+    uint64_t idx = threadIdx.x;
+    for (; idx + 3 * 256 < total; idx += 4 * 256) {
+        uint4 *pp[4], *ff[4], x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            addrs(idx + u * 256, pp[u], ff[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            x[u] = TO_POOL ? *ff[u] : *pp[u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *(TO_POOL ? pp[u] : ff[u]) = x[u];
+    }
+    for (; idx < total; idx += 256) {
+        uint4 *p1, *f1;
+        addrs(idx, p1, f1);
+        if (TO_POOL)
+            *p1 = *f1;
+        else
+            *f1 = *p1;
     }
 }
 
@@ -906,10 +923,10 @@ hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t l
     if (n == 0)
         return hipSuccess;
     if (to_pool)
-        hipLaunchKernelGGL(copy_tokens_kernel<true>, dim3(n, 64), dim3(256), 0, s, pool_base, log2_page, page_table,
+        hipLaunchKernelGGL(copy_tokens_kernel<true>, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table,
                            recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
     else
-        hipLaunchKernelGGL(copy_tokens_kernel<false>, dim3(n, 64), dim3(256), 0, s, pool_base, log2_page, page_table,
+        hipLaunchKernelGGL(copy_tokens_kernel<false>, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table,
                            recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
     return hipGetLastError();
 }
