@@ -66,13 +66,16 @@ struct ProfPair {
     int get() {
         if (!p->tun.profile)
             return UKV_OK;
-        if (!p->ev_free.empty()) {
-            ev = p->ev_free.back();
-            p->ev_free.pop_back();
-        } else {
-            HIP_TRY(hipEventCreate(&ev.a), "hipEventCreate");
-            HIP_TRY(hipEventCreate(&ev.b), "hipEventCreate");
+        if (p->ev_free.empty()) { // create a batch at once, so the timed loop rarely creates events
+            for (int k = 0; k < 64; ++k) {
+                ukv_pool::EvPair e{nullptr, nullptr, 0};
+                HIP_TRY(hipEventCreate(&e.a), "hipEventCreate");
+                HIP_TRY(hipEventCreate(&e.b), "hipEventCreate");
+                p->ev_free.push_back(e);
+            }
         }
+        ev = p->ev_free.back();
+        p->ev_free.pop_back();
         ev.which = which;
         return UKV_OK;
     }
@@ -184,7 +187,7 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
             p->tun.slots = r;
         p->tun.slots_auto = false;
     }
-    Plan plan;
+    Plan &plan = p->plan_scratch; // storage reused from call to call
     int rc = build_plan(p, b, plan);
     if (rc != UKV_OK)
         return rc;

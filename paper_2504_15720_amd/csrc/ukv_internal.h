@@ -161,6 +161,8 @@ struct ukv_pool {
     Stage stage[kStages];
     int next_stage = 0;
 
+    ukv::Plan plan_scratch;
+
     // profiling
     struct EvPair {
         hipEvent_t a, b;

@@ -34,7 +34,15 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         set_error("batch host arrays must be non-null");
         return UKV_EINVAL;
     }
-    plan = Plan();
+    plan.seqs.clear();
+    plan.items.clear();
+    plan.span_first.clear();
+    plan.reduce.clear();
+    plan.item_span.clear();
+    plan.seq_req.clear();
+    plan.partial_floats = 0;
+    plan.kv_bytes = 0;
+    plan.max_reduce_heads = 0;
     uint64_t total_cost = 0;
     for (uint32_t i = 0; i < n; ++i) {
         const uint32_t cls = b->service_id[i];
@@ -83,8 +91,10 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             return (uint64_t)plan.seqs[k].ctx_len * c.hs * c.row_bytes;
         };
         std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return cost_of(x) > cost_of(y); });
-        std::vector<SeqRec> seqs(order.size());
-        std::vector<uint32_t> req(order.size());
+        static thread_local std::vector<SeqRec> seqs;
+        static thread_local std::vector<uint32_t> req;
+        seqs.resize(order.size());
+        req.resize(order.size());
         for (uint32_t k = 0; k < order.size(); ++k) {
             seqs[k] = plan.seqs[order[k]];
             req[k] = plan.seq_req[order[k]];
