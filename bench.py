@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--heads-per-slice", type=int, default=0)
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
+    ap.add_argument("--taper", type=int, default=0)
+    ap.add_argument("--gqa-cost-pct", type=int, default=0)
     ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")
     ap.add_argument("--layout", choices=["merged", "split"], default="merged",
                     help="split = one block stream and table per (request, kv head), the alternative of section 4.4")
@@ -125,6 +127,10 @@ def main():
         U.ukv_set_param(db.pool, U.UKV_PARAM_HEADS_PER_SLICE, args.heads_per_slice)
     if args.slots:
         U.ukv_set_param(db.pool, U.UKV_PARAM_SLOTS, args.slots)
+    if args.taper:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_TAPER, args.taper)
+    if args.gqa_cost_pct:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_GQA_COST_PCT, args.gqa_cost_pct)
     if args.no_taper:
         U.ukv_set_param(db.pool, U.UKV_PARAM_TAPER, 0)
     if args.unfused_merge:

@@ -169,13 +169,16 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 
 /* Tunables (integers).  Setting one never changes results beyond fp32 summation order. */
 #define UKV_PARAM_MAX_SPANS 1        /* upper limit of decode workgroups per launch */
-#define UKV_PARAM_MIN_SPAN_BYTES 2   /* do not cut spans smaller than this many KV bytes */
-#define UKV_PARAM_BLOCK_THREADS 3    /* 256 or 512 */
+#define UKV_PARAM_MIN_SPAN_BYTES 2   /* do not cut spans smaller than this many KV bytes (default 512 KiB) */
+#define UKV_PARAM_BLOCK_THREADS 3    /* 256 or 512 (default 512; 256 where every service has d = 128 and g > 1) */
 #define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
 #define UKV_PARAM_PROFILE 5          /* 1 = time kernels with HIP events (see ukv_profile_read) */
 #define UKV_PARAM_FUSED_MERGE 6      /* 1 (default) = merge partials inside the decode launch; 0 = second launch */
 #define UKV_PARAM_SLOTS 7            /* decode workgroups resident at once; 0 (default) = ask the device */
-#define UKV_PARAM_TAPER 8            /* 1 (default) = spans shrink batch by batch; 0 = equal spans */
+#define UKV_PARAM_GQA_COST_PCT 9     /* planner cost of a KV byte of a matrix-core service (d = 128, g > 1), in percent of
+                                        a byte of the other kinds (default 150, measured on mixed batches) */
+#define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
+                                        workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
 int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("UKV_LIB") or os.path.join(_HERE, "libukv.so")
 UKV_OK, UKV_EINVAL, UKV_ENOMEM, UKV_ENOSPC, UKV_EHIP = 0, -1, -2, -3, -4
 UKV_PARAM_MAX_SPANS, UKV_PARAM_MIN_SPAN_BYTES, UKV_PARAM_BLOCK_THREADS = 1, 2, 3
 UKV_PARAM_HEADS_PER_SLICE, UKV_PARAM_PROFILE, UKV_PARAM_FUSED_MERGE = 4, 5, 6
-UKV_PARAM_SLOTS, UKV_PARAM_TAPER = 7, 8
+UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT = 7, 8, 9
 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",

@@ -128,6 +128,7 @@ struct Tunables {
     int64_t fused_merge = 1;
     int64_t slots = 512; // workgroups resident at once (refreshed from the device at the first launch)
     int64_t taper = 1;
+    int64_t gqa_cost_pct = 150; // planner weight of a matrix-core (grouped-query) KV byte, percent
     bool slots_auto = true;
 };
 

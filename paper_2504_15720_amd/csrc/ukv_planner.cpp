@@ -10,6 +10,7 @@ namespace ukv {
 
 static constexpr uint64_t kItemOverheadBytes = 16 * 1024; // q load, merge and output, as KV bytes
 static constexpr uint64_t kMinItemTokens = 16;
+static constexpr uint64_t kDefaultTaperPct = 88;
 
 // partials of different items never share a 128-byte line
 static uint32_t part_stride_of(const ClassRec &c) { return (c.hs * c.g * (c.d + 2) + 31u) & ~31u; }
@@ -43,6 +44,11 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
     plan.partial_floats = 0;
     plan.kv_bytes = 0;
     plan.max_reduce_heads = 0;
+    // planner cost of one token of one head-slice: its KV bytes, weighted by the kernel kind
+    auto token_cost = [&](const ClassRec &c) {
+        const uint64_t bytes = (uint64_t)c.hs * c.row_bytes;
+        return c.kind == kD128GQA ? bytes * (uint64_t)p->tun.gqa_cost_pct / 100 : bytes;
+    };
     uint64_t total_cost = 0;
     for (uint32_t i = 0; i < n; ++i) {
         const uint32_t cls = b->service_id[i];
@@ -72,7 +78,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             s.part_stride = part_stride_of(c);
             plan.seqs.push_back(s);
             plan.seq_req.push_back(i);
-            total_cost += kItemOverheadBytes + ctx * c.hs * c.row_bytes;
+            total_cost += kItemOverheadBytes + ctx * token_cost(c);
         }
     }
     if (plan.seqs.empty()) {
@@ -88,7 +94,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             order[k] = k;
         auto cost_of = [&](uint32_t k) {
             const ClassRec &c = p->classes.c[plan.seqs[k].cls];
-            return (uint64_t)plan.seqs[k].ctx_len * c.hs * c.row_bytes;
+            return (uint64_t)plan.seqs[k].ctx_len * token_cost(c);
         };
         std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return cost_of(x) > cost_of(y); });
         static thread_local std::vector<SeqRec> seqs;
@@ -105,8 +111,10 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
 
     // Span sizes.  Workgroups are dispatched in order onto `slots` resident positions, so equal
     // spans would leave the last round partly empty.  With tapering, each batch of `slots` spans
-    // takes half of the remaining cost (factoring self-scheduling): rounds shrink geometrically
-    // down to min_span_bytes and the tail of the launch is one small round.
+    // takes a fixed share of the remaining cost (factoring self-scheduling): rounds shrink
+    // geometrically down to min_span_bytes and the tail of the launch is one small round.  A large
+    // share keeps the number of cuts (each costs an item start and a partial to merge) low; what
+    // the first round's uneven finish leaves is evened out by the small rounds after it.
     std::vector<uint64_t> targets;
     {
         const uint64_t min_span = (uint64_t)p->tun.min_span_bytes, max_spans = (uint64_t)p->tun.max_spans;
@@ -116,8 +124,9 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             targets.assign(1, (total_cost + n - 1) / n);
         } else {
             uint64_t R = total_cost;
+            const uint64_t pct = p->tun.taper == 1 ? kDefaultTaperPct : (uint64_t)p->tun.taper;
             while (R > 0 && targets.size() < max_spans) {
-                const uint64_t c = std::max<uint64_t>(min_span, R / (2 * slots));
+                const uint64_t c = std::max<uint64_t>(min_span, R * pct / (100 * slots));
                 uint64_t batch = std::min<uint64_t>(slots, (R + c - 1) / c);
                 batch = std::min<uint64_t>(batch, max_spans - targets.size());
                 targets.insert(targets.end(), batch, c);
@@ -144,7 +153,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
     for (uint32_t k = 0; k < plan.seqs.size(); ++k) {
         const SeqRec &s = plan.seqs[k];
         const ClassRec &c = p->classes.c[s.cls];
-        const uint64_t cost = (uint64_t)c.hs * c.row_bytes;
+        const uint64_t cost = token_cost(c);
         seq_first_item[k] = (uint32_t)plan.items.size();
         uint64_t t = 0, rem = s.ctx_len;
         if (rem == 0) {

@@ -127,6 +127,17 @@ int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out) {
     std::memcpy(p->services, desc->services, sizeof(ukv_service_t) * desc->n_services);
     std::memset(&p->classes, 0, sizeof p->classes);
     int rc = derive_classes(p);
+    if (rc == UKV_OK) {
+        // A pool whose services all run on the matrix-core path does better with four waves (four
+        // kv heads) per workgroup: smaller partials and twice the workgroups in flight.
+        bool all_gqa = true;
+        for (uint32_t s = 0; s < p->n_services; ++s)
+            all_gqa = all_gqa && p->classes.c[s].kind == kD128GQA;
+        if (all_gqa) {
+            p->tun.block_threads = 256;
+            rc = derive_classes(p);
+        }
+    }
     if (rc != UKV_OK) {
         delete p;
         return rc;
@@ -263,8 +274,15 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
         if (value > 0)
             p->tun.slots = value;
         return UKV_OK;
+    case UKV_PARAM_GQA_COST_PCT:
+        if (value < 50 || value > 400)
+            return fail(UKV_EINVAL, "gqa_cost_pct must lie in 50..400");
+        p->tun.gqa_cost_pct = value;
+        return UKV_OK;
     case UKV_PARAM_TAPER:
-        p->tun.taper = value ? 1 : 0;
+        if (value < 0 || value > 95 || (value > 1 && value < 5))
+            return fail(UKV_EINVAL, "taper must be 0, 1 or a percentage in 5..95");
+        p->tun.taper = value;
         return UKV_OK;
     default:
         return fail(UKV_EINVAL, "unknown parameter");
@@ -283,6 +301,7 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_FUSED_MERGE: *value = p->tun.fused_merge; return UKV_OK;
     case UKV_PARAM_SLOTS: *value = p->tun.slots; return UKV_OK;
     case UKV_PARAM_TAPER: *value = p->tun.taper; return UKV_OK;
+    case UKV_PARAM_GQA_COST_PCT: *value = p->tun.gqa_cost_pct; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

@@ -147,14 +147,43 @@ def test_plan_full_size_configs_balance_and_fit_workspace():
         U.ukv_set_param(p, U.UKV_PARAM_TAPER, 0)          # equal spans
         per_span = per_span_cost()
         assert per_span.max() < 1.25 * per_span.mean()
-        U.ukv_set_param(p, U.UKV_PARAM_TAPER, 1)          # batches of `slots` spans, each half the rest
+        U.ukv_set_param(p, U.UKV_PARAM_TAPER, 50)         # batches of `slots` spans, each half the rest
         U.ukv_set_param(p, U.UKV_PARAM_SLOTS, 512)
+        U.ukv_set_param(p, U.UKV_PARAM_GQA_COST_PCT, 100)
         per_span = per_span_cost()
         first, second = per_span[:512], per_span[512:1024]
         assert 0.4 < second.mean() / first.mean() < 0.6
         assert per_span[-256:].mean() < 0.5 * first.mean()
         assert abs(first.sum() / per_span.sum() - 0.5) < 0.05
+        U.ukv_set_param(p, U.UKV_PARAM_TAPER, 1)          # default share of the first batch
+        per_span = per_span_cost()
+        assert abs(per_span[:512].sum() / per_span.sum() - 0.88) < 0.03
+        for bad in (-1, 3, 96):
+            with pytest.raises(U.UkvError):
+                U.ukv_set_param(p, U.UKV_PARAM_TAPER, bad)
         U.ukv_pool_destroy(p)
+
+
+def test_plan_cost_weight_of_matrix_core_services():
+    """A grouped-query (d = 128) byte counts gqa_cost_pct percent of another byte.  With equal spans of
+    a fixed minimum size, doubling the weight doubles the span count of an all-grouped-query batch
+    and leaves an all-multi-head batch alone."""
+    counts = {}
+    for cfg in (3, 4):
+        b = make_config(cfg, fill_pool=False)
+        p = _pool(b.services, n_pages=b.n_pages)
+        assert U.ukv_get_param(p, U.UKV_PARAM_GQA_COST_PCT) == 150
+        U.ukv_set_param(p, U.UKV_PARAM_TAPER, 0)
+        U.ukv_set_param(p, U.UKV_PARAM_MIN_SPAN_BYTES, 8 << 20)
+        for w in (100, 200):
+            U.ukv_set_param(p, U.UKV_PARAM_GQA_COST_PCT, w)
+            info, _ = _check_plan(b, p)
+            counts[cfg, w] = info.n_spans
+        with pytest.raises(U.UkvError):
+            U.ukv_set_param(p, U.UKV_PARAM_GQA_COST_PCT, 10)
+        U.ukv_pool_destroy(p)
+    assert counts[3, 100] == counts[3, 200]
+    assert abs(counts[4, 200] / counts[4, 100] - 2.0) < 0.05
 
 
 def test_plan_handles_empty_contexts_and_bad_batches():
@@ -185,4 +214,12 @@ def test_params_roundtrip_and_validation():
         U.ukv_set_param(p, U.UKV_PARAM_BLOCK_THREADS, 128)
     with pytest.raises(U.UkvError):
         U.ukv_set_param(p, 99, 1)
+    U.ukv_pool_destroy(p)
+    # pools of grouped-query (d = 128) services only start with four-wave workgroups
+    p = _pool([SHAPES["8b"], SHAPES["70b"]])
+    assert U.ukv_get_param(p, U.UKV_PARAM_BLOCK_THREADS) == 256
+    assert U.ukv_pool_info(p, 1).heads_per_slice == 4
+    U.ukv_pool_destroy(p)
+    p = _pool([SHAPES["8b"], SHAPES["7b"]])
+    assert U.ukv_get_param(p, U.UKV_PARAM_BLOCK_THREADS) == 512
     U.ukv_pool_destroy(p)
