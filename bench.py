@@ -2,9 +2,11 @@
 """Benchmark of the unified-KV decode hot path on one MI355X.
 
 A step is one pass of the whole path over one mixed-service batch: grow every request by one
-token (host: page allocation from the library's free list), `ukv_append` (page-table patches +
-K/V scatter) and `ukv_decode_attention` (split-KV decode launch + merge launch).  Inputs are
-resident in HBM before the timed region.  Prints ONE JSON line.
+token (host: page allocation from the library's free list), then `ukv_decode_step`: the new
+page-table entries, the store of every request's new K/V token into its pages and split-KV
+decode attention with the merge of cut requests, as one plan upload and one decode launch.
+`--separate-append` runs the same step as `ukv_append` + `ukv_decode_attention` (two launches).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
   value      whole-step KV throughput: sum over steps of ctx_len*token_bytes / wall time
   roofline   the decode kernel alone: algorithmic KV bytes per launch / its mean duration,
@@ -88,6 +90,7 @@ def main():
     ap.add_argument("--heads-per-slice", type=int, default=0)
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
+    ap.add_argument("--separate-append", action="store_true")
     ap.add_argument("--taper", type=int, default=0)
     ap.add_argument("--gqa-cost-pct", type=int, default=0)
     ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")
@@ -151,7 +154,12 @@ def main():
                 lib_ids = U.ukv_pages_alloc(db.pool, ids.size)
                 assert np.array_equal(lib_ids, ids)
             desc = db.desc(entry, ids)
-            db.append(desc)
+            if args.separate_append:
+                db.append(desc)
+            else:
+                db.step(desc)
+                kv_bytes.append(b.kv_bytes())
+                return
         db.decode(desc)
         kv_bytes.append(b.kv_bytes())
 
@@ -184,7 +192,9 @@ def main():
         "config": {"workload": WORKLOAD_NAMES[args.config], "n_requests": b.n_requests,
                    "kv_bytes_per_step": int(kv_per_step), "pool_pages": b.n_pages,
                    "stated_pool_pages": b.notes.get("stated_pages"), "page_bytes": b.page_bytes,
-                   "step": "attention only" if args.attention_only else "grow + append + attention",
+                   "step": "attention only" if args.attention_only else
+                           "grow + append + attention (two launches)" if args.separate_append else
+                           "grow + append + attention (one launch)",
                    "layout": args.layout, "block_table_entries": int(b.pages_owned().sum()),
                    "pages_in_use": int(b.stack.used_pages),
                    "kv_storage": "bf16", "decode_workgroups": info.n_spans, "work_items": info.n_items,

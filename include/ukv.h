@@ -139,6 +139,15 @@ size_t ukv_decode_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests);
 int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes,
                          void *stream);
 
+/* One decode iteration in one launch (section 2.1: each iteration stores the new token's KV pair and
+ * attends over the whole cache; section 4.4: both go through the block table): the same results as
+ * ukv_append followed by ukv_decode_attention on this batch -- pool bytes and page-table entries bit
+ * for bit, out up to fp32 summation order.  The new page-table entries are written with the plan
+ * upload; the workgroup that attends to a request's last token takes that token's K/V from
+ * new_k/new_v, stores it into the request's pages and uses it from registers, so the store side
+ * costs no launch of its own.  Arguments, workspace and errors as for those two calls together. */
+int ukv_decode_step(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes, void *stream);
+
 /* Bulk load (also the tests' view of the pool): copy tokens [0, ctx_len[i]) of every request out of the pool into contiguous
  * k_out / v_out DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i] (HOST). */
 int ukv_gather(ukv_pool_t *pool, const ukv_batch_t *batch, void *k_out, void *v_out, const uint64_t *kv_off,

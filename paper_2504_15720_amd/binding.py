@@ -23,7 +23,8 @@ UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT = 7, 8, 9
 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",
-    "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_gather",
+    "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_decode_step",
+    "ukv_gather",
     "ukv_scatter",
     "ukv_plan_decode", "ukv_set_param", "ukv_get_param", "ukv_profile_read", "ukv_strerror", "ukv_last_error",
 ]
@@ -92,6 +93,7 @@ def lib():
         L.ukv_decode_workspace_bytes.argtypes = [vp, C.c_uint32]
         L.ukv_decode_workspace_bytes.restype = C.c_size_t
         L.ukv_decode_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
+        L.ukv_decode_step.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
         L.ukv_gather.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_scatter.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_plan_decode.argtypes = [vp, C.POINTER(ukv_batch_t), C.POINTER(ukv_plan_info_t), vp, C.c_uint32]
@@ -199,6 +201,10 @@ def ukv_decode_workspace_bytes(pool: int, n_requests: int) -> int:
 def ukv_decode_attention(pool: int, batch: BatchDesc, workspace_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().ukv_decode_attention(pool, C.byref(batch.c), workspace_ptr, ws_bytes, stream),
            "ukv_decode_attention")
+
+
+def ukv_decode_step(pool: int, batch: BatchDesc, workspace_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().ukv_decode_step(pool, C.byref(batch.c), workspace_ptr, ws_bytes, stream), "ukv_decode_step")
 
 
 def ukv_gather(pool: int, batch: BatchDesc, k_out_ptr: int, v_out_ptr: int, kv_off, stream: int = 0) -> None:

@@ -165,16 +165,40 @@ int ukv_plan_decode(const ukv_pool_t *p, const ukv_batch_t *b, ukv_plan_info_t *
     return UKV_OK;
 }
 
-int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream) {
+// Attention alone, or (with_append) the whole step: the new page-table entries ride with the plan
+// upload and the new tokens are stored by the decode workgroups that attend to them.
+static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream,
+                       bool with_append) {
     if (!p || !b) {
         set_error("null pool or batch");
         return UKV_EINVAL;
     }
-    if (b->n_requests == 0)
+    const uint32_t n_patches = with_append ? b->n_patches : 0;
+    if (b->n_requests == 0 && n_patches == 0)
         return UKV_OK;
-    if (!b->page_table || !b->q || !b->out) {
+    if (!b->page_table || (b->n_requests && (!b->q || !b->out))) {
         set_error("page_table, q and out must be non-null device pointers");
         return UKV_EINVAL;
+    }
+    if (with_append) {
+        if (b->n_requests && (!b->new_k || !b->new_v || !b->new_off)) {
+            set_error("a decode step needs new_k, new_v and new_off");
+            return UKV_EINVAL;
+        }
+        if (n_patches && (!b->patch_entry || !b->patch_page)) {
+            set_error("patch arrays missing");
+            return UKV_EINVAL;
+        }
+        for (uint32_t i = 0; i < n_patches; ++i)
+            if (b->patch_page[i] < 0 || (uint64_t)b->patch_page[i] >= p->n_pages) {
+                set_error("patch page id out of range");
+                return UKV_EINVAL;
+            }
+        for (uint32_t i = 0; i < b->n_requests; ++i)
+            if (b->new_off[i] & 7) {
+                set_error("new_off must be a multiple of 8 elements");
+                return UKV_EINVAL;
+            }
     }
     if (!workspace || ((uintptr_t)workspace & 255)) {
         set_error("workspace must be non-null and 256-byte aligned");
@@ -191,6 +215,9 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
     int rc = build_plan(p, b, plan);
     if (rc != UKV_OK)
         return rc;
+    if (with_append)
+        for (size_t k = 0; k < plan.seqs.size(); ++k)
+            plan.seqs[k].new_off = b->new_off[plan.seq_req[k]];
     const uint32_t n_spans = (uint32_t)plan.span_first.size() - 1;
     const BlobLayout L = blob_layout(plan.seqs.size(), plan.items.size(), n_spans, plan.reduce.size());
     const size_t part_off = align_up(L.total);
@@ -198,8 +225,12 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
         set_error("workspace too small for this batch");
         return UKV_ENOSPC;
     }
+    // the patch arrays are only read by the upload kernel, from the staging slot itself
+    const size_t off_pe = align_up(L.total);
+    const size_t off_pp = align_up(off_pe + (size_t)n_patches * sizeof(uint64_t));
+    const size_t stage_bytes = align_up(off_pp + (size_t)n_patches * sizeof(int32_t));
     ukv_pool::Stage *st = nullptr;
-    rc = stage_acquire(p, L.total, &st);
+    rc = stage_acquire(p, stage_bytes, &st);
     if (rc != UKV_OK)
         return rc;
     unsigned char *h = (unsigned char *)st->host;
@@ -210,7 +241,14 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
     if (!plan.reduce.empty())
         std::memcpy(h + L.reduce, plan.reduce.data(), plan.reduce.size() * sizeof(ReduceRec));
     std::memset(h + L.counters, 0, L.total - L.counters);
-    HIP_TRY(launch_stage_copy(workspace, st->mapped, L.total, s), "launch plan upload");
+    if (n_patches) {
+        std::memcpy(h + off_pe, b->patch_entry, (size_t)n_patches * sizeof(uint64_t));
+        std::memcpy(h + off_pp, b->patch_page, (size_t)n_patches * sizeof(int32_t));
+    }
+    const unsigned char *hm = (const unsigned char *)st->mapped;
+    HIP_TRY(launch_stage_copy(workspace, st->mapped, L.total, b->page_table, (const uint64_t *)(hm + off_pe),
+                              (const int32_t *)(hm + off_pp), n_patches, s),
+            "launch plan upload");
     if ((rc = stage_release_after(st, s)) != UKV_OK)
         return rc;
 
@@ -228,6 +266,8 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
     a.partials = (float *)(w + part_off);
     const bool fused = p->tun.fused_merge != 0;
     a.counters = fused ? (uint32_t *)(w + L.counters) : nullptr;
+    a.new_k = with_append ? (const uint16_t *)b->new_k : nullptr;
+    a.new_v = with_append ? (const uint16_t *)b->new_v : nullptr;
 
     {
         ProfPair pp{p, 0};
@@ -247,6 +287,14 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
         pp.done();
     }
     return UKV_OK;
+}
+
+int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream) {
+    return decode_impl(p, b, workspace, ws_bytes, stream, false);
+}
+
+int ukv_decode_step(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream) {
+    return decode_impl(p, b, workspace, ws_bytes, stream, true);
 }
 
 int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {

@@ -19,12 +19,13 @@ struct SeqRec {
     uint64_t q_off;       // element offset of the request's q (head 0)
     uint64_t out_off;     // element offset of the request's out (head 0)
     uint64_t part_off;    // float offset of this sequence's first partial (n_parts > 1)
+    uint64_t new_off;     // element offset of the request's new K/V token (fused append only)
     uint32_t ctx_len;
     uint32_t cls;         // service index
     uint32_t head0;       // first kv head of the slice
     uint32_t n_parts;     // work items this sequence was cut into
     uint32_t part_stride; // floats per partial: n_heads_q * (head_dim + 2), rounded up to 32 (one line)
-    uint32_t pad_[3];
+    uint32_t pad_[1];
 };
 static_assert(sizeof(SeqRec) == 64, "SeqRec layout");
 
@@ -62,6 +63,10 @@ struct DecodeArgs {
     const uint32_t *span_first; // [n_spans + 1]
     float *partials;
     uint32_t *counters; // per sequence: finished items (fused merge); null = merge in a second launch
+    // Fused append (null = attention only): the item that holds a request's last token takes that
+    // token's K/V from here and stores it into the request's pages.
+    const uint16_t *new_k;
+    const uint16_t *new_v;
 };
 
 struct ReduceRec {
@@ -91,7 +96,9 @@ struct GatherRec { // tokens [t0, t1) of one request
 
 // ---- kernel launchers (ukv_kernels.hip) ----
 int decode_resident_workgroups(uint32_t block_threads); // occupancy x compute units; 0 on failure
-hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, hipStream_t s);
+hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, int32_t *page_table,
+                             const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
+                             hipStream_t s);
 hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,

@@ -80,6 +80,12 @@ __device__ __forceinline__ uint4 ld_g16(const void *p) {
 __device__ __forceinline__ void st_g16(float *p, float x, float y, float z, float w) {
     *as_global(reinterpret_cast<f32x4g *>(p)) = (f32x4g){x, y, z, w};
 }
+__device__ __forceinline__ u32x4 ld_g16v(const void *p) { return *as_global(reinterpret_cast<const u32x4 *>(p)); }
+// 128-bit streaming store (the new token's pieces: written once, read by later launches only)
+__device__ __forceinline__ void st_g16v(void *p, const u32x4 &v) {
+    __builtin_nontemporal_store(v, as_global(reinterpret_cast<u32x4 *>(p)));
+}
+__device__ __forceinline__ void st_g16v(void *p, const uint4 &v) { st_g16v(p, (u32x4){v.x, v.y, v.z, v.w}); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -90,9 +96,9 @@ __device__ __forceinline__ uint64_t uni(uint64_t x) {
 }
 __device__ __forceinline__ float uni(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
 
-// Workgroup state in LDS.  The kernel body only picks items; the per-kind item functions are
-// separate (non-inlined) functions so that the register allocation of one kind does not inflate
-// the others; they take their (workgroup-uniform) inputs from s_ctx and move them to SGPRs.
+// Workgroup state in LDS.  The kernel body only picks items and publishes them in s_ctx; the
+// per-kind item functions take their (workgroup-uniform) inputs from there and move them to
+// SGPRs, so that nothing of one item stays live in registers across the next.
 static constexpr int kMaxBlock = 512;
 struct ItemCtx {
     DecodeArgs a;
@@ -103,6 +109,20 @@ struct ItemCtx {
 __shared__ int32_t s_tab[kTabWindow];                                  // page-table window
 __shared__ __align__(16) float s_mbuf[kMaxBlock * 8 + (kMaxBlock / 8) * 2]; // merge buffer
 __shared__ __align__(16) ItemCtx s_ctx;
+
+// Fused append: an item appends when the launch carries new tokens and it ends at the request's
+// last token.  That token is then not read from the pool: lanes take its row from new_k/new_v,
+// store it into the request's page and use it from registers, so the store side of the step
+// costs no launch and no wait.  Workgroup-uniform.
+__device__ __forceinline__ bool item_appends(const SeqRec &s, const Item &it) {
+    return uni(reinterpret_cast<uint64_t>(s_ctx.a.new_k)) != 0 && s.ctx_len > 0 && it.t1 == s.ctx_len;
+}
+// new_k / new_v rows of kv head kvh of the item's request (element pointers)
+__device__ __forceinline__ void new_token_rows(uint32_t kvh, uint32_t D, const uint16_t *&nk, const uint16_t *&nv) {
+    const uint64_t e0 = uni(s_ctx.s.new_off) + (uint64_t)kvh * D;
+    nk = reinterpret_cast<const uint16_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.new_k))) + e0;
+    nv = reinterpret_cast<const uint16_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.new_v))) + e0;
+}
 
 __device__ __forceinline__ DecodeArgs ctx_args() {
     DecodeArgs a;
@@ -117,6 +137,8 @@ __device__ __forceinline__ DecodeArgs ctx_args() {
     a.span_first = nullptr;
     a.partials = reinterpret_cast<float *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.partials)));
     a.counters = reinterpret_cast<uint32_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.counters)));
+    a.new_k = nullptr; // the fused-append inputs are fetched where they are used (new_token_rows)
+    a.new_v = nullptr;
     return a;
 }
 __device__ __forceinline__ SeqRec ctx_seq() {
@@ -125,6 +147,7 @@ __device__ __forceinline__ SeqRec ctx_seq() {
     s.q_off = uni(s_ctx.s.q_off);
     s.out_off = uni(s_ctx.s.out_off);
     s.part_off = uni(s_ctx.s.part_off);
+    s.new_off = 0;
     s.ctx_len = uni(s_ctx.s.ctx_len);
     s.cls = uni(s_ctx.s.cls);
     s.head0 = uni(s_ctx.s.head0);
@@ -345,7 +368,7 @@ __device__ __forceinline__ void finish_item(const DecodeArgs &a, const SeqRec &s
 }
 
 template <int D, int G, int NT>
-__device__ __attribute__((noinline)) void process_item() {
+__device__ __forceinline__ void process_item() {
     const DecodeArgs a = ctx_args();
     const SeqRec s = ctx_seq();
     const ClassRec c = ctx_class();
@@ -364,18 +387,16 @@ __device__ __attribute__((noinline)) void process_item() {
     const uint32_t lg = a.log2_page;
     const uint64_t page_mask = (1ull << lg) - 1;
 
+    // q is only unpacked after the first page-table window is in LDS: its loads, the window's and
+    // (fused append) the new token's are then in flight together, one round trip for all three.
     float qf[G][8];
+    uint4 qraw[G];
     {
         const uint4 *qp = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.q) + s.q_off +
                                                           (uint64_t)(kvh * G) * D + lir * 8);
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const uint4 w = ld_g16(qp + g * LPR);
-            unpack8(w, qf[g]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                qf[g][e] *= c.scale_log2e;
-        }
+        for (int g = 0; g < G; ++g)
+            qraw[g] = ld_g16(qp + g * LPR);
     }
     float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -392,6 +413,10 @@ __device__ __attribute__((noinline)) void process_item() {
     const uint64_t slice_lo = (uint64_t)s.head0 * c.row_bytes;
     const uint64_t slice_hi = (uint64_t)(s.head0 + HS) * c.row_bytes;
 
+    const bool appends = item_appends(s, it);
+    const uint32_t t_pool = appends ? it.t1 - 1 : it.t1; // tokens below this are read from the pool
+    uint4 nkr[1], nvr[1]; // the new token's K and V pieces of this lane (fused append)
+    uint4 *new_dst = nullptr;
     uint32_t w0 = it.t0;
     while (w0 < it.t1) { // workgroup-uniform: one pass per page-table window
         const uint64_t s_lo = ((uint64_t)w0 * T + slice_lo) >> lg;
@@ -399,10 +424,31 @@ __device__ __attribute__((noinline)) void process_item() {
         const uint64_t tmax = (lim - slice_hi) / T; // last token whose slice ends inside the window
         const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)it.t1 ? tmax + 1 : (uint64_t)it.t1);
         const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + slice_hi - 1) >> lg) - s_lo) + 1;
-        __syncthreads();
+        const uint32_t r1 = w1 < t_pool ? w1 : t_pool;
+        // The new token is handled in the window that holds it, ahead of that window's pool tokens:
+        // its loads are issued here, so that they are in flight together with the table window's.
+        const bool new_here = appends && w1 == it.t1 && live && tl == 0;
+        if (new_here) {
+            const uint16_t *nk, *nv;
+            new_token_rows(kvh, D, nk, nv);
+            nkr[0] = ld_g16(nk + lir * 8);
+            nvr[0] = ld_g16(nv + lir * 8);
+        }
+        if (w0 != it.t0)
+            __syncthreads(); // later windows: every wave is done with the previous one (the first
+                             // follows the workgroup barrier that published the item)
         for (uint32_t e = tid; e < n_ent; e += NT)
             tab[e] = as_global(a.page_table)[s.table_off + s_lo + e];
         __syncthreads();
+        if (w0 == it.t0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                unpack8(qraw[g], qf[g]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    qf[g][e] *= c.scale_log2e;
+            }
+        }
 
         if (live) {
             auto row_ptr = [&](uint32_t t) -> const uint4 * {
@@ -411,8 +457,12 @@ __device__ __attribute__((noinline)) void process_item() {
                 return reinterpret_cast<const uint4 *>(a.pool_base + ((uint64_t)(uint32_t)pg << lg) +
                                                        (off & page_mask));
             };
+            if (new_here) { // into the softmax from registers; into the pool once the item's loads are done
+                new_dst = const_cast<uint4 *>(row_ptr(it.t1 - 1));
+                update<G, 1, LPR>(qf, nkr, nvr, m, l, acc);
+            }
             uint32_t t = w0 + tl;
-            for (; (uint64_t)t + (uint64_t)(U - 1) * TI < w1; t += U * TI) {
+            for (; (uint64_t)t + (uint64_t)(U - 1) * TI < r1; t += U * TI) {
                 uint4 kr[U], vr[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -422,7 +472,7 @@ __device__ __attribute__((noinline)) void process_item() {
                 }
                 update<G, U, LPR>(qf, kr, vr, m, l, acc);
             }
-            for (; t < w1; t += TI) {
+            for (; t < r1; t += TI) {
                 uint4 kr[1], vr[1];
                 const uint4 *p = row_ptr(t);
                 kr[0] = ld_kv(p);
@@ -493,6 +543,12 @@ __device__ __attribute__((noinline)) void process_item() {
         }
     }
 
+    // The store of the new token waits until here: loads (and barriers) issued after a store have
+    // to wait for its acknowledgement too, and nothing in this item reads it back.
+    if (new_dst != nullptr) {
+        st_g16v(new_dst, nkr[0]);
+        st_g16v(new_dst + LPR, nvr[0]);
+    }
     finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, 0, tab, mbuf);
 }
 
@@ -525,7 +581,7 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float x) { // x finite, >= 0
 }
 
 template <int NT>
-__device__ __attribute__((noinline)) void process_item_gqa() {
+__device__ __forceinline__ void process_item_gqa() {
     const DecodeArgs a = ctx_args();
     const SeqRec s = ctx_seq();
     const ClassRec c = ctx_class();
@@ -565,6 +621,10 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
     const uint64_t slice_lo = (uint64_t)s.head0 * c.row_bytes;
     const uint64_t slice_hi = (uint64_t)(s.head0 + HS) * c.row_bytes;
 
+    const bool appends = item_appends(s, it);
+    const uint32_t t_pool = appends ? it.t1 - 1 : it.t1; // tokens below this are read from the pool
+    u32x4 nK[4], nV; // the new token's K and V pieces of this lane (fused append)
+    unsigned char *new_dst = nullptr;
     uint32_t w0 = it.t0;
     while (w0 < it.t1) { // workgroup-uniform: one pass per page-table window
         const uint64_t s_lo = ((uint64_t)w0 * T + slice_lo) >> lg;
@@ -572,13 +632,27 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
         const uint64_t tmax = (lim - slice_hi) / T;
         const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)it.t1 ? tmax + 1 : (uint64_t)it.t1);
         const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + slice_hi - 1) >> lg) - s_lo) + 1;
-        __syncthreads();
+        const uint32_t r1 = w1 < t_pool ? w1 : t_pool;
+        // The new token is handled in the window that holds it, ahead of that window's pool tokens:
+        // its loads are issued here, so that they are in flight together with the table window's.
+        const bool new_here = appends && w1 == it.t1 && live;
+        if (new_here) {
+            const uint16_t *nk16, *nv16;
+            new_token_rows(kvh, D, nk16, nv16);
+            const unsigned char *nk = reinterpret_cast<const unsigned char *>(nk16) + q * 16;
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+                nK[st] = ld_g16v(nk + st * 64);
+            nV = ld_g16v(reinterpret_cast<const unsigned char *>(nv16) + j * 16);
+        }
+        if (w0 != it.t0)
+            __syncthreads(); // later windows only: see process_item
         for (uint32_t e = tid; e < n_ent; e += NT)
             tab[e] = as_global(a.page_table)[s.table_off + s_lo + e];
         __syncthreads();
 
         if (live) {
-            const uint32_t last = w1 - 1;
+            const uint32_t last = r1 - 1; // only used when the window holds a pool token
             // K rows: tokens tb+j and tb+16+j, chunk (step*4 + q) -> kA[half*4 + step]; V: chunk j of the
             // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token and
             // masked in the scores.  All ten page lookups are issued before the first is used.
@@ -603,7 +677,7 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
                 for (int e = 0; e < 8; ++e)
                     vr[e] = ld_kv4(row_ptr(min(tau(tb, e), last)) + 2 * D + j * 16);
             };
-            auto compute_tile = [&](uint32_t tb, const u32x4 (&kA)[8], const u32x4 (&vr)[8]) {
+            auto compute_tile = [&](uint32_t tb, uint32_t t_lim, const u32x4 (&kA)[8], const u32x4 (&vr)[8]) {
                 f32x4_t s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f}, s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
@@ -613,8 +687,8 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
                 float sc[8];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    sc[r] = (tb + 4 * q + r < w1) ? s0[r] * c.scale_log2e : -INFINITY;
-                    sc[4 + r] = (tb + 16 + 4 * q + r < w1) ? s1[r] * c.scale_log2e : -INFINITY;
+                    sc[r] = (tb + 4 * q + r < t_lim) ? s0[r] * c.scale_log2e : -INFINITY;
+                    sc[4 + r] = (tb + 16 + 4 * q + r < t_lim) ? s1[r] * c.scale_log2e : -INFINITY;
                 }
                 float mt = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
                                  fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
@@ -656,10 +730,25 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
                     oacc[mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Pl, oacc[mm], 0, 0, 0);
                 }
             };
-            for (uint32_t tb = w0; tb < w1; tb += 32) {
+            if (new_here) {
+                // The new token as a tile of its own: every row of the tile is that token (all but
+                // the first masked).  It goes into the pool once the item's loads are done.
+                new_dst = const_cast<unsigned char *>(row_ptr(it.t1 - 1));
+                u32x4 kA[8], vr[8];
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    kA[st] = nK[st];
+                    kA[4 + st] = nK[st];
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    vr[e] = nV;
+                compute_tile(it.t1 - 1, it.t1, kA, vr);
+            }
+            for (uint32_t tb = w0; tb < r1; tb += 32) {
                 u32x4 kA[8], vr[8];
                 load_tile(tb, kA, vr);
-                compute_tile(tb, kA, vr);
+                compute_tile(tb, r1, kA, vr);
             }
         }
         w0 = w1;
@@ -690,6 +779,15 @@ __device__ __attribute__((noinline)) void process_item_gqa() {
             if (q == 0)
                 st_part2(pbase + (uint64_t)HS * G * D + hq * 2, m, l);
         }
+    }
+    if (new_dst != nullptr) { // K: 16 pieces over lanes (j = 0, q) x 4; V: 16 pieces over lanes (j, q = 0)
+        if (j == 0) {
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+                st_g16v(new_dst + q * 16 + st * 64, nK[st]);
+        }
+        if (q == 0)
+            st_g16v(new_dst + 2 * D + j * 16, nV);
     }
     finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, G, tab, mbuf);
 }
@@ -847,7 +945,18 @@ __global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_ba
 }
 
 // Plan upload: copies 16-byte pieces from pinned, device-mapped host memory into the workspace.
-__global__ void __launch_bounds__(256) stage_copy_kernel(uint4 *dst, const uint4 *src, uint32_t n16) {
+// Workgroups past the copy write the step's new page-table entries (fused append), so that the
+// decode launch that follows finds them in place.
+__global__ void __launch_bounds__(256) stage_copy_kernel(uint4 *dst, const uint4 *src, uint32_t n16,
+                                                         int32_t *page_table, const uint64_t *patch_entry,
+                                                         const int32_t *patch_page, uint32_t n_patches) {
+    const uint32_t copy_blocks = (n16 + 255) / 256;
+    if (blockIdx.x >= copy_blocks) {
+        const uint32_t i = (blockIdx.x - copy_blocks) * blockDim.x + threadIdx.x;
+        if (i < n_patches)
+            page_table[patch_entry[i]] = patch_page[i];
+        return;
+    }
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n16)
         dst[i] = src[i];
@@ -868,12 +977,15 @@ int decode_resident_workgroups(uint32_t block_threads) {
 }
 
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps.
-hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, hipStream_t s) {
+hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, int32_t *page_table,
+                             const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
+                             hipStream_t s) {
     const uint32_t n16 = (uint32_t)((bytes + 15) / 16);
-    if (n16 == 0)
+    const uint32_t blocks = (n16 + 255) / 256 + (n_patches + 255) / 256;
+    if (blocks == 0)
         return hipSuccess;
-    hipLaunchKernelGGL(stage_copy_kernel, dim3((n16 + 255) / 256), dim3(256), 0, s, static_cast<uint4 *>(dst),
-                       static_cast<const uint4 *>(src_mapped), n16);
+    hipLaunchKernelGGL(stage_copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4 *>(dst),
+                       static_cast<const uint4 *>(src_mapped), n16, page_table, patch_entry, patch_page, n_patches);
     return hipGetLastError();
 }
 

@@ -23,8 +23,8 @@ def say(msg):
     sys.stdout.flush()
 
 
-def _check_attention(db, b, tag):
-    db.decode()
+def _check_attention(db, b, tag, run=None):
+    (run or db.decode)()
     got = db.out_host().astype(np.float64)
     ref = oracle.attention(b, b.pool)
     assert np.all(np.isfinite(got)), f"{tag}: non-finite output"
@@ -47,10 +47,13 @@ def _check_gather(db, b):
         assert np.array_equal(v[o:o + int(sizes[i])], rv.reshape(-1)), f"gather V mismatch, request {i}"
 
 
-def _decode_steps(db, b, steps, seed, check_every=1):
-    """steps x (grow, append, attention) with the oracle mirroring the pool image on the host."""
+def _decode_steps(db, b, steps, seed, check_every=1, fused="no"):
+    """steps x (grow, append, attention) with the oracle mirroring the pool image on the host.
+    fused: "no" = ukv_append then ukv_decode_attention; "yes" = ukv_decode_step (one launch);
+    "alternate" = odd steps fused."""
     rng = np.random.default_rng(seed)
     for step in range(steps):
+        one_launch = fused == "yes" or (fused == "alternate" and step % 2 == 1)
         entry, ids = b.grow_one_token()
         lib_ids = U.ukv_pages_alloc(db.pool, ids.size) if ids.size else np.zeros(0, np.int32)
         assert np.array_equal(lib_ids, ids), "library free list diverged from the synthetic stack"
@@ -59,6 +62,13 @@ def _decode_steps(db, b, steps, seed, check_every=1):
         db.set_q(q)
         db.set_new(nk, nv)
         oracle.append(b, b.pool, nk, nv)
+        if one_launch:
+            desc = db.desc(entry, ids)
+            if step % check_every == 0 or step == steps - 1:
+                _check_attention(db, b, f"step {step} (one launch)", run=lambda: db.step(desc))
+            else:
+                db.step(desc)
+            continue
         db.append(db.desc(entry, ids))
         if step % check_every == 0 or step == steps - 1:
             _check_attention(db, b, f"step {step}")
@@ -70,7 +80,7 @@ def _decode_steps(db, b, steps, seed, check_every=1):
 @pytest.mark.parametrize("block", [256, 512])
 def test_mini_configs_match_oracle(cfg, block):
     say(f"mini cfg {cfg} block {block}")
-    b = make_config(cfg, mini=True)
+    b = make_config(cfg, mini=True, reserve_tokens=12)
     db = DeviceBatch(b)
     try:
         U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, block)
@@ -84,6 +94,12 @@ def test_mini_configs_match_oracle(cfg, block):
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)
         steps = max(1, int(b.notes["steps"]))
         _decode_steps(db, b, min(steps, 4), seed=cfg)
+        _decode_steps(db, b, 2, seed=50 + cfg, fused="yes")                    # last items are cut parts
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 512 * 1024)
+        _decode_steps(db, b, 2, seed=60 + cfg, fused="yes")                    # mostly whole requests
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 48 * 1024)
+        _decode_steps(db, b, 1, seed=70 + cfg, fused="yes")
     finally:
         db.close()
 
@@ -111,6 +127,12 @@ def test_edge_cases_empty_single_and_ragged():
         _decode_steps(db, b, 2, seed=3)       # 0 -> 1 -> 2 tokens, including first-page allocation
     finally:
         db.close()
+    b = make_batch(services, sid, ctx, 2048, "permutation", np.random.default_rng(99), reserve_tokens=2, pool_seed=5)
+    db = DeviceBatch(b)
+    try:
+        _decode_steps(db, b, 2, seed=3, fused="yes")   # the same, store and attention in one launch
+    finally:
+        db.close()
 
 
 def test_small_pages_and_group_sizes_outside_the_workloads():
@@ -122,7 +144,7 @@ def test_small_pages_and_group_sizes_outside_the_workloads():
     sid = np.array([0, 1, 2, 3, 4, 5, 0, 1, 2, 3, 4, 5])
     ctx = np.array([37, 1200, 515, 64, 3, 700, 1, 33, 16, 17, 300, 31])
     rng = np.random.default_rng(123)
-    b = make_batch(services, sid, ctx, 64 * 1024, "permutation", rng, page_bytes=1024, reserve_tokens=3,
+    b = make_batch(services, sid, ctx, 64 * 1024, "permutation", rng, page_bytes=1024, reserve_tokens=9,
                    pool_seed=9)
     db = DeviceBatch(b)
     try:
@@ -135,6 +157,9 @@ def test_small_pages_and_group_sizes_outside_the_workloads():
             U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 512 * 1024)
         _check_gather(db, b)
         _decode_steps(db, b, 3, seed=11)
+        _decode_steps(db, b, 3, seed=12, fused="yes")     # several new pages per token and request
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 16 * 1024)
+        _decode_steps(db, b, 2, seed=13, fused="alternate")
     finally:
         db.close()
 
@@ -176,9 +201,16 @@ def test_append_changes_only_the_new_token_bytes():
         _decode_steps_no_attention(db, b, 3)
     finally:
         db.close()
+    b = make_config(5, mini=True)
+    b.pool[:] = 0xABCD
+    db = DeviceBatch(b)
+    try:
+        _decode_steps_no_attention(db, b, 3, fused=True)      # the store fused into the decode launch
+    finally:
+        db.close()
 
 
-def _decode_steps_no_attention(db, b, steps):
+def _decode_steps_no_attention(db, b, steps, fused=False):
     rng = np.random.default_rng(8)
     for _ in range(steps):
         entry, ids = b.grow_one_token()
@@ -186,7 +218,10 @@ def _decode_steps_no_attention(db, b, steps):
         _, nk, nv = b.draw_step_inputs(rng)
         db.set_new(nk, nv)
         oracle.append(b, b.pool, nk, nv)
-        db.append(db.desc(entry, ids))
+        if fused:
+            db.step(db.desc(entry, ids))
+        else:
+            db.append(db.desc(entry, ids))
     got = db.pool_host()
     assert np.array_equal(got, b.pool)
     untouched = got == 0xABCD
@@ -310,6 +345,12 @@ def test_errors_from_the_compute_calls():
         with pytest.raises(U.UkvError) as e:
             db.append(db.desc([0], [b.n_pages + 5]))
         assert e.value.code == U.UKV_EINVAL
+        with pytest.raises(U.UkvError) as e:
+            db.step(db.desc([0], [b.n_pages + 5]))
+        assert e.value.code == U.UKV_EINVAL
+        with pytest.raises(U.UkvError) as e:
+            U.ukv_decode_step(db.pool, db.desc(), db.ws_t.data_ptr(), 1024, db.stream())
+        assert e.value.code == U.UKV_ENOSPC
     finally:
         db.close()
 
@@ -323,7 +364,7 @@ def test_full_size_configs_match_oracle(cfg):
     try:
         steps = int(b.notes["steps"])
         if steps:
-            _decode_steps(db, b, steps, seed=100 + cfg)
+            _decode_steps(db, b, steps, seed=100 + cfg, fused="alternate")
         else:
             _check_attention(db, b, "attention")
     finally:
@@ -336,6 +377,6 @@ def test_full_size_config5_sixteen_steps():
     say(f"  generated: {b.n_requests} requests, {b.kv_bytes() / 1e9:.2f} GB of KV, pool {b.n_pages} pages")
     db = DeviceBatch(b)
     try:
-        _decode_steps(db, b, 16, seed=105, check_every=5)
+        _decode_steps(db, b, 16, seed=105, check_every=5, fused="alternate")
     finally:
         db.close()

@@ -75,6 +75,10 @@ class DeviceBatch:
     def append(self, desc):
         U.ukv_append(self.pool, desc, self.stream())
 
+    def step(self, desc):
+        """append + attention as one launch"""
+        U.ukv_decode_step(self.pool, desc, self.ws_t.data_ptr(), self.ws_bytes, self.stream())
+
     def out_host(self) -> np.ndarray:
         return self.out_t.cpu().numpy()
 
