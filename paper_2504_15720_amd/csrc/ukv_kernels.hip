@@ -178,10 +178,11 @@ __device__ __forceinline__ Item ctx_item() {
     return it;
 }
 
-// Online-softmax update of one kv head's G query heads with U tokens.
-template <int G, int U, int LPR>
+// Online-softmax update of one kv head's G query heads with U tokens.  MASKED: token u only
+// counts if bit u of `valid` is set (bit 0 always is: the running maximum stays finite).
+template <int G, int U, int LPR, bool MASKED = false>
 __device__ __forceinline__ void update(const float (&qf)[G][8], const uint4 (&kr)[U], const uint4 (&vr)[U],
-                                       float (&m)[G], float (&l)[G], float (&acc)[G][8]) {
+                                       float (&m)[G], float (&l)[G], float (&acc)[G][8], uint32_t valid = ~0u) {
     float kf[U][8], vf[U][8];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -199,6 +200,8 @@ __device__ __forceinline__ void update(const float (&qf)[G][8], const uint4 (&kr
             for (int e = 0; e < 8; ++e)
                 d = fmaf(qf[g][e], kf[u][e], d);
             sc[u] = row_sum<LPR>(d);
+            if (MASKED && !((valid >> u) & 1u))
+                sc[u] = -INFINITY;
             mx = fmaxf(mx, sc[u]);
         }
         const float alpha = fast_exp2(m[g] - mx); // m = -inf on the first batch gives 0
@@ -472,12 +475,18 @@ __device__ __forceinline__ void process_item() {
                 }
                 update<G, U, LPR>(qf, kr, vr, m, l, acc);
             }
-            for (; t < r1; t += TI) {
-                uint4 kr[1], vr[1];
-                const uint4 *p = row_ptr(t);
-                kr[0] = ld_kv(p);
-                vr[0] = ld_kv(p + LPR);
-                update<G, 1, LPR>(qf, kr, vr, m, l, acc);
+            if (t < r1) { // the last, partly filled batch in one round trip: missing tokens are masked
+                uint4 kr[U], vr[U];
+                uint32_t valid = 0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool ok = t + u * TI < r1;
+                    valid |= (uint32_t)ok << u;
+                    const uint4 *p = row_ptr(ok ? t + u * TI : t);
+                    kr[u] = ld_kv(p);
+                    vr[u] = ld_kv(p + LPR);
+                }
+                update<G, U, LPR, true>(qf, kr, vr, m, l, acc, valid);
             }
         }
         w0 = w1;
