@@ -32,7 +32,7 @@ def build(force: bool = False) -> str:
 def bind(cdll):
     """Declare the return types of the oracle's entry points on a loaded library."""
     for name in ("ukv_oracle_gather", "ukv_oracle_scatter", "ukv_oracle_append", "ukv_oracle_attention",
-                 "ukv_oracle_attention_range", "ukv_oracle_merge", "ukv_oracle_threads"):
+                 "ukv_oracle_attention_range", "ukv_oracle_merge", "ukv_oracle_prefill", "ukv_oracle_threads"):
         getattr(cdll, name).restype = C.c_int
     return cdll
 
@@ -166,6 +166,25 @@ def attention_range(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, n_
                                         _p(l, C.c_double), _p(acc, C.c_double))
     _check(rc, "attention_range")
     return m, l, acc
+
+
+def prefill(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, n_q_heads: int, n_kv_heads: int,
+            head_dim: int, scale: float, ctx_len: int, positions, q_rows: np.ndarray, n_threads: int = 0):
+    """Causal prefill attention of one request at the listed positions: q_rows[k] ([Q, d] bf16 bits) is the
+    query of position positions[k] and attends to tokens 0..positions[k].  Returns fp64 [n_pos, Q, d]."""
+    lib = _load()
+    pool = pool_u16.view(np.uint8)
+    table = _arr(table, np.int32)
+    pos = _arr(positions, np.uint32)
+    qq = _arr(q_rows, np.uint16).reshape(pos.size, n_q_heads, head_dim)
+    out = np.empty((pos.size, n_q_heads, head_dim), np.float64)
+    rc = lib.ukv_oracle_prefill(_p(pool, C.c_uint8), C.c_uint64(pool.size), C.c_uint32(page_bytes),
+                                _p(table, C.c_int32), C.c_uint64(table.size), C.c_uint32(n_q_heads),
+                                C.c_uint32(n_kv_heads), C.c_uint32(head_dim), C.c_double(scale),
+                                C.c_uint32(ctx_len), C.c_uint32(pos.size), _p(pos, C.c_uint32), _p(qq, C.c_uint16),
+                                _p(out, C.c_double), C.c_int(n_threads))
+    _check(rc, "prefill")
+    return out
 
 
 def merge(m: np.ndarray, l: np.ndarray, acc: np.ndarray) -> np.ndarray:

@@ -25,12 +25,22 @@
  *     section 2.3, is 8192 tokens * 32 layers of exactly this).  Head-rows never
  *     straddle pages (page_bytes % head_row_bytes == 0 is required); token rows may.
  *   - Query head a reads kv head a / (n_q_heads / n_kv_heads).
+ *   - Prefill phase (section 2.1): all tokens of the prompt (or of a chunk of
+ *     it) are processed in one pass that also leaves their key/value pairs in
+ *     the cache.  Reading taken here (the paper serves decoder-only models and
+ *     does not restate the mask): the pass is causal, i.e. the query of the
+ *     token at position p attends to the cached pairs of positions 0..p, so
+ *     that its result is what a decode step at that position would compute.
+ *     ukv_oracle_prefill writes that definition out position by position.
  *
  * Pins (tests/, -m "not gpu"): brute force on contiguous arrays, torch's fp64
  * scaled_dot_product_attention, closed forms (constant V, one token, equal
  * keys, two-token logistic, zero query), invariances (page renaming, token
  * order, score shift, batch composition), hand-worked address fixtures, the
- * 4 GiB closed form, and sentinel checks for append.
+ * 4 GiB closed form, and sentinel checks for append.  Prefill: the masked-matrix
+ * formulation in numpy, torch's fp64 SDPA with is_causal, position 0 = value 0,
+ * last position = the decode entry point, zero queries = running means, and
+ * causality (rewriting later tokens leaves earlier positions bit-identical).
  *
  * Parallelism: OpenMP over requests only.  fp64 throughout; bf16 inputs are
  * widened exactly.
@@ -277,6 +287,50 @@ int ukv_oracle_attention_range(const uint8_t *pool, uint64_t pool_bytes, uint32_
         return ORC_EINVAL;
     return attend_range(pool, pool_bytes / page_bytes, page_bytes, table, table_len, n_q_heads, n_kv_heads,
                         head_dim, scale, t0, t1, q, m_out, l_out, acc_out);
+}
+
+/* Prefill phase of one request (section 2.1), causal: for each listed position pos[k] (< ctx_len),
+ * the query row q_rows[k] ([Q][d] bf16) attends to tokens 0..pos[k] of the request's cache, exactly
+ * as the decode definition above with a context of pos[k]+1 tokens.  out: fp64 [n_pos][Q][d]. */
+int ukv_oracle_prefill(const uint8_t *pool, uint64_t pool_bytes, uint32_t page_bytes, const int32_t *table,
+                       uint64_t table_len, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
+                       double scale, uint32_t ctx_len, uint32_t n_pos, const uint32_t *pos,
+                       const uint16_t *q_rows, double *out, int n_threads)
+{
+    if (!shape_ok(page_bytes, n_q_heads, n_kv_heads, head_dim))
+        return ORC_EINVAL;
+    for (uint32_t k = 0; k < n_pos; ++k)
+        if (pos[k] >= ctx_len)
+            return ORC_EINVAL;
+    uint64_t n_pages = pool_bytes / page_bytes, row = (uint64_t)n_q_heads * head_dim;
+    int rc_all = ORC_OK;
+#ifdef _OPENMP
+    if (n_threads > 0)
+        omp_set_num_threads(n_threads);
+#else
+    (void)n_threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < (int64_t)n_pos; ++k) {
+        double *o = out + (uint64_t)k * row;
+        double *m = (double *)malloc(sizeof(double) * n_q_heads);
+        double *l = (double *)malloc(sizeof(double) * n_q_heads);
+        int rc = (m && l) ? attend_range(pool, n_pages, page_bytes, table, table_len, n_q_heads, n_kv_heads,
+                                         head_dim, scale, 0, (uint64_t)pos[k] + 1, q_rows + (uint64_t)k * row, m,
+                                         l, o)
+                          : ORC_ENOMEM;
+        if (rc == ORC_OK) {
+            for (uint32_t a = 0; a < n_q_heads; ++a)
+                for (uint32_t j = 0; j < head_dim; ++j)
+                    o[(uint64_t)a * head_dim + j] /= l[a];
+        } else {
+#pragma omp critical
+            rc_all = rc;
+        }
+        free(m);
+        free(l);
+    }
+    return rc_all;
 }
 
 /* Combine n_parts range statistics of one query head: with M = max_c m_c,

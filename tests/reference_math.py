@@ -48,6 +48,38 @@ def torch_sdpa_attention(q_bits, k_bits, v_bits, scale):
     return o[0, :, 0, :].numpy()
 
 
+def contiguous_causal_attention(q_bits, k_bits, v_bits, scale, first_pos=0):
+    """Prefill by the masked-matrix formulation: q [m,Q,d] are the queries of positions first_pos..first_pos+m-1,
+    k/v [n,H,d]; scores of tokens beyond a query's own position are set to -inf.  Returns fp64 [m,Q,d]."""
+    q, k, v = bits_to_f64(q_bits), bits_to_f64(k_bits), bits_to_f64(v_bits)
+    m, Q, d = q.shape
+    n, H, _ = k.shape
+    G = Q // H
+    allowed = np.arange(n)[None, :] <= (first_pos + np.arange(m))[:, None]      # [m, n]
+    out = np.zeros((m, Q, d))
+    for a in range(Q):
+        h = a // G
+        s = (q[:, a, :] @ k[:, h, :].T) * scale                                  # [m, n]
+        s = np.where(allowed, s, -np.inf)
+        w = np.exp(s - s.max(axis=1, keepdims=True))
+        w /= w.sum(axis=1, keepdims=True)
+        out[:, a, :] = w @ v[:, h, :]
+    return out
+
+
+def torch_sdpa_causal(q_bits, k_bits, v_bits, scale):
+    """torch's fp64 SDPA with is_causal=True (square case: as many queries as tokens)."""
+    import torch
+    q = torch.from_numpy(bits_to_f64(q_bits)).permute(1, 0, 2)      # [Q,n,d]
+    k = torch.from_numpy(bits_to_f64(k_bits)).permute(1, 0, 2)      # [H,n,d]
+    v = torch.from_numpy(bits_to_f64(v_bits)).permute(1, 0, 2)
+    G = q.shape[0] // k.shape[0]
+    k = k.repeat_interleave(G, dim=0)
+    v = v.repeat_interleave(G, dim=0)
+    o = torch.nn.functional.scaled_dot_product_attention(q[None], k[None], v[None], is_causal=True, scale=scale)
+    return o[0].permute(1, 0, 2).numpy()                             # [n,Q,d]
+
+
 def build_paged_pool(pool_u16, page_bytes, table, k_bits, v_bits, first_token=0):
     """Place K/V [n,H,d] into the pool image element by element."""
     n, H, d = k_bits.shape

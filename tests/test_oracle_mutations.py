@@ -40,6 +40,15 @@ MUTATIONS = {
     "scatter writes head rows token-minor": (
         "memcpy(pool + a, k_in + (t * n_kv_heads + h) * head_dim, 2ull * head_dim);",
         "memcpy(pool + a, k_in + (h * n_tokens + t) * head_dim, 2ull * head_dim);"),
+    "prefill mask off by one (own token excluded)": (
+        "head_dim, scale, 0, (uint64_t)pos[k] + 1, q_rows + (uint64_t)k * row, m,",
+        "head_dim, scale, 0, (uint64_t)pos[k] + (pos[k] == 0), q_rows + (uint64_t)k * row, m,"),
+    "prefill not causal (every position sees the whole context)": (
+        "head_dim, scale, 0, (uint64_t)pos[k] + 1, q_rows + (uint64_t)k * row, m,",
+        "head_dim, scale, 0, (uint64_t)ctx_len, q_rows + (uint64_t)k * row, m,"),
+    "prefill uses the first query row for every position": (
+        "head_dim, scale, 0, (uint64_t)pos[k] + 1, q_rows + (uint64_t)k * row, m,",
+        "head_dim, scale, 0, (uint64_t)pos[k] + 1, q_rows, m,"),
     "gather reads V at the K offset": (
         "memcpy(v_out + (t * n_kv_heads + h) * head_dim, pool + a + 2ull * head_dim, 2ull * head_dim);",
         "memcpy(v_out + (t * n_kv_heads + h) * head_dim, pool + a, 2ull * head_dim);"),
@@ -60,6 +69,8 @@ def _run_pins():
     pins.test_split_and_merge_equals_whole()
     pins.test_append_touches_exactly_the_new_token(5)
     pins.test_scatter_places_every_element_and_inverts_gather("13b")
+    pins.test_prefill_equals_masked_matrix_and_torch_causal(1, 19)
+    pins.test_prefill_closed_forms_and_causality()
 
 
 def test_unmutated_copy_passes(tmp_path, monkeypatch):

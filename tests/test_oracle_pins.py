@@ -13,7 +13,7 @@ import pytest
 
 from oracle import oracle
 from synth import Service, SHAPES, make_batch, make_config, to_split_layout
-from tests.reference_math import (bits_to_f64, build_paged_pool, contiguous_attention, copy_logical_kv_to_split,
+from tests.reference_math import (contiguous_causal_attention, torch_sdpa_causal, bits_to_f64, build_paged_pool, contiguous_attention, copy_logical_kv_to_split,
                                   f32_to_bits, torch_sdpa_attention)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "address_map.txt")
@@ -367,3 +367,73 @@ def test_split_block_layout_gives_the_same_attention(page_bytes):
     assert split_entries == 32 * merged_entries and 32 * 32 == 1024
     if page_bytes is None:
         assert abs(int(s.pages_owned().sum()) / int(b.pages_owned().sum()) - 1.0) < 0.2
+
+
+# ---------------------------------------------------------------- prefill phase (section 2.1), causal
+
+
+def _prefill_case(rng, shape, n, page_bytes):
+    n_pages = 2 * (-(-n * shape.token_bytes // page_bytes)) + 3
+    _, k, v, table, pool = _random_case(rng, shape, n, page_bytes, n_pages)
+    q = f32_to_bits(rng.standard_normal((n, shape.n_q_heads, shape.head_dim)).astype(np.float32))
+    return q, k, v, table, pool
+
+
+@pytest.mark.parametrize("si", range(len(SMALL_SHAPES)))
+@pytest.mark.parametrize("n", [1, 2, 19])
+def test_prefill_equals_masked_matrix_and_torch_causal(si, n):
+    shape = SMALL_SHAPES[si]
+    rng = np.random.default_rng(7000 + 10 * si + n)
+    P = 4 * shape.head_dim * 3
+    q, k, v, table, pool = _prefill_case(rng, shape, n, P)
+    got = oracle.prefill(pool, P, table, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.softmax_scale,
+                         n, np.arange(n), q)
+    assert np.max(np.abs(got - contiguous_causal_attention(q, k, v, shape.softmax_scale))) < 1e-12
+    assert np.max(np.abs(got - torch_sdpa_causal(q, k, v, shape.softmax_scale))) < 1e-12
+
+
+def test_prefill_chunk_of_the_last_positions_and_service_shapes():
+    """A chunk: only the last m positions are queried (chunked prefill); real head shapes and 16 KiB pages."""
+    for name, n, m in (("8b", 11, 4), ("13b", 6, 6), ("h12", 13, 5)):
+        shape = SHAPES[name]
+        rng = np.random.default_rng(len(name) * 100 + n)
+        q, k, v, table, pool = _prefill_case(rng, shape, n, 16384)
+        pos = np.arange(n - m, n)
+        got = oracle.prefill(pool, 16384, table, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                             shape.softmax_scale, n, pos, q[pos])
+        ref = contiguous_causal_attention(q[pos], k, v, shape.softmax_scale, first_pos=n - m)
+        assert np.max(np.abs(got - ref)) < 1e-12
+
+
+def test_prefill_closed_forms_and_causality():
+    shape = Service(8, 2, 16)
+    rng = np.random.default_rng(77)
+    n, P = 12, 4 * 16 * 3
+    q, k, v, table, pool = _prefill_case(rng, shape, n, P)
+    args = (P, table, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.softmax_scale, n)
+    got = oracle.prefill(pool, *args, np.arange(n), q)
+    # position 0 sees one token: its value, exactly, for every query head of the group
+    v0 = bits_to_f64(v[0])                                                       # [H, d]
+    assert np.array_equal(got[0], np.repeat(v0, shape.group, axis=0))
+    # the last position is a decode step over the whole context (a different entry point)
+    dec = oracle.attention(_OneRequest(shape, n, table, q[n - 1], P), pool).reshape(shape.n_q_heads, -1)
+    assert np.max(np.abs(got[n - 1] - dec)) < 1e-15
+    # zero queries: position p returns the mean of values 0..p
+    zq = np.zeros_like(q)
+    gz = oracle.prefill(pool, *args, np.arange(n), zq)
+    vf = bits_to_f64(v)
+    for p_ in (0, 3, n - 1):
+        assert np.max(np.abs(gz[p_] - np.repeat(vf[:p_ + 1].mean(axis=0), shape.group, axis=0))) < 1e-12
+    # causality: rewriting the cache of tokens after p does not change position p
+    pool2 = pool.copy()
+    k2, v2 = k.copy(), v.copy()
+    k2[7:], v2[7:] = k2[7:] ^ 0x8000, v2[7:] ^ 0x8000                            # flip signs of tokens 7..
+    build_paged_pool(pool2, P, table, k2, v2)
+    g2 = oracle.prefill(pool2, *args, np.arange(n), q)
+    assert np.array_equal(g2[:7], got[:7]) and not np.allclose(g2[7:], got[7:])
+    # positions are looked up, not assumed consecutive; rows follow the order of the list
+    pick = np.array([9, 2, 2, 11])
+    gp = oracle.prefill(pool, *args, pick, q[pick])
+    assert np.array_equal(gp, got[pick])
+    with pytest.raises(RuntimeError):
+        oracle.prefill(pool, *args, np.array([n]), q[:1])                        # position outside the context
