@@ -148,6 +148,21 @@ int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *works
  * costs no launch of its own.  Arguments, workspace and errors as for those two calls together. */
 int ukv_decode_step(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes, void *stream);
 
+/* Prefill phase (section 2.1: the tokens of a prompt, or of a chunk of it, are processed in one pass
+ * that leaves their KV pairs in the cache), attention part, causal:
+ *   out[i][r][a][:] = sum_t softmax_t(scale * q[i][r][a] . K[t][a/G]) * V[t][a/G],  t <= ctx_len[i] - q_len[i] + r,
+ * for the q_len[i] last tokens of request i (row r is the token at position ctx_len[i] - q_len[i] + r).
+ * All ctx_len[i] tokens, the chunk's own included, must already be in the pool (ukv_scatter or
+ * ukv_append) and hold finite values; bytes past ctx_len are never read.  q: DEVICE bf16 [q_len][n_q_heads][head_dim] per request at element offset q_off[i];
+ * out: DEVICE fp32, same shape, at out_off[i]; q_len: HOST [n], 0 <= q_len[i] <= ctx_len[i].
+ * fp32 accumulation as in ukv_decode_attention.  Services with head_dim 128 (g = 1, 2, 4, 8) only:
+ * others give UKV_EINVAL.  workspace: DEVICE, 256-byte aligned, at least
+ * ukv_prefill_workspace_bytes(pool, n_requests, sum of q_len) bytes; else UKV_ENOSPC.
+ * Uses service_id, ctx_len, table_off, page_table, q, q_off, out, out_off. */
+size_t ukv_prefill_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests, uint64_t total_q_rows);
+int ukv_prefill_attention(ukv_pool_t *pool, const ukv_batch_t *batch, const uint32_t *q_len, void *workspace,
+                          size_t ws_bytes, void *stream);
+
 /* Bulk load (also the tests' view of the pool): copy tokens [0, ctx_len[i]) of every request out of the pool into contiguous
  * k_out / v_out DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i] (HOST). */
 int ukv_gather(ukv_pool_t *pool, const ukv_batch_t *batch, void *k_out, void *v_out, const uint64_t *kv_off,
@@ -186,6 +201,7 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_SLOTS 7            /* decode workgroups resident at once; 0 (default) = ask the device */
 #define UKV_PARAM_GQA_COST_PCT 9     /* planner cost of a KV byte of a matrix-core service (d = 128, g > 1), in percent of
                                         a byte of the other kinds (default 150, measured on mixed batches) */
+#define UKV_PARAM_PREFILL_XCD 10     /* 1 (default) = prefill workgroups of one (request, kv head) share an XCD (one L2) */
 #define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
                                         workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
@@ -194,8 +210,8 @@ int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 /* Kernel times collected while UKV_PARAM_PROFILE is 1 (HIP events on the caller's stream).
  * Reading waits for the recorded events and resets the accumulators. */
 typedef struct {
-    uint32_t n_decode, n_reduce, n_append;
-    double decode_ms, reduce_ms, append_ms; /* sums over the launches */
+    uint32_t n_decode, n_reduce, n_append, n_prefill;
+    double decode_ms, reduce_ms, append_ms, prefill_ms; /* sums over the launches */
 } ukv_profile_t;
 int ukv_profile_read(ukv_pool_t *pool, ukv_profile_t *out);
 

@@ -19,11 +19,12 @@ LIB_PATH = os.environ.get("UKV_LIB") or os.path.join(_HERE, "libukv.so")
 UKV_OK, UKV_EINVAL, UKV_ENOMEM, UKV_ENOSPC, UKV_EHIP = 0, -1, -2, -3, -4
 UKV_PARAM_MAX_SPANS, UKV_PARAM_MIN_SPAN_BYTES, UKV_PARAM_BLOCK_THREADS = 1, 2, 3
 UKV_PARAM_HEADS_PER_SLICE, UKV_PARAM_PROFILE, UKV_PARAM_FUSED_MERGE = 4, 5, 6
-UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT = 7, 8, 9
+UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT, UKV_PARAM_PREFILL_XCD = 7, 8, 9, 10
 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",
     "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_decode_step",
+    "ukv_prefill_workspace_bytes", "ukv_prefill_attention",
     "ukv_gather",
     "ukv_scatter",
     "ukv_plan_decode", "ukv_set_param", "ukv_get_param", "ukv_profile_read", "ukv_strerror", "ukv_last_error",
@@ -62,7 +63,9 @@ class ukv_plan_info_t(C.Structure):
 
 class ukv_profile_t(C.Structure):
     _fields_ = [("n_decode", C.c_uint32), ("n_reduce", C.c_uint32), ("n_append", C.c_uint32),
-                ("decode_ms", C.c_double), ("reduce_ms", C.c_double), ("append_ms", C.c_double)]
+                ("n_prefill", C.c_uint32),
+                ("decode_ms", C.c_double), ("reduce_ms", C.c_double), ("append_ms", C.c_double),
+                ("prefill_ms", C.c_double)]
 
 
 class UkvError(RuntimeError):
@@ -94,6 +97,9 @@ def lib():
         L.ukv_decode_workspace_bytes.restype = C.c_size_t
         L.ukv_decode_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
         L.ukv_decode_step.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
+        L.ukv_prefill_workspace_bytes.argtypes = [vp, C.c_uint32, C.c_uint64]
+        L.ukv_prefill_workspace_bytes.restype = C.c_size_t
+        L.ukv_prefill_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, C.c_size_t, vp]
         L.ukv_gather.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_scatter.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_plan_decode.argtypes = [vp, C.POINTER(ukv_batch_t), C.POINTER(ukv_plan_info_t), vp, C.c_uint32]
@@ -205,6 +211,17 @@ def ukv_decode_attention(pool: int, batch: BatchDesc, workspace_ptr: int, ws_byt
 
 def ukv_decode_step(pool: int, batch: BatchDesc, workspace_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().ukv_decode_step(pool, C.byref(batch.c), workspace_ptr, ws_bytes, stream), "ukv_decode_step")
+
+
+def ukv_prefill_workspace_bytes(pool: int, n_requests: int, total_q_rows: int) -> int:
+    return int(lib().ukv_prefill_workspace_bytes(pool, n_requests, total_q_rows))
+
+
+def ukv_prefill_attention(pool: int, batch: BatchDesc, q_len, workspace_ptr: int, ws_bytes: int,
+                          stream: int = 0) -> None:
+    q_len = np.ascontiguousarray(q_len, np.uint32)
+    _check(lib().ukv_prefill_attention(pool, C.byref(batch.c), q_len.ctypes.data, workspace_ptr, ws_bytes, stream),
+           "ukv_prefill_attention")
 
 
 def ukv_gather(pool: int, batch: BatchDesc, k_out_ptr: int, v_out_ptr: int, kv_off, stream: int = 0) -> None:

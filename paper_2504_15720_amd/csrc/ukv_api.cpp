@@ -457,6 +457,156 @@ int ukv_scatter(ukv_pool_t *p, const ukv_batch_t *b, const void *k_in, const voi
     return copy_tokens(true, p, b, const_cast<void *>(k_in), const_cast<void *>(v_in), kv_off, stream);
 }
 
+// Prefill work list: one record per (request, kv head, tile of query rows), heaviest first.  Each XCD
+// has its own L2 and consecutive workgroups go to consecutive XCDs, so the tiles of one (request, kv
+// head) -- which read the same K/V -- are placed at launch positions of one residue modulo 8.
+static constexpr uint32_t kXcds = 8;
+
+static size_t prefill_rec_bound(const ukv_pool *p, uint32_t n_requests, uint64_t total_q_rows) {
+    uint64_t max_kv = 1, max_g = 1;
+    for (uint32_t s = 0; s < p->n_services; ++s) {
+        max_kv = std::max<uint64_t>(max_kv, p->classes.c[s].n_kv);
+        max_g = std::max<uint64_t>(max_g, p->classes.c[s].g);
+    }
+    const uint64_t min_rows = std::max<uint64_t>(1, kPrefillCols / max_g);
+    const uint64_t tiles = max_kv * (total_q_rows / min_rows + n_requests);
+    return (size_t)(kXcds * (tiles + 1)); // the interleave pads every XCD's queue to the longest one
+}
+
+size_t ukv_prefill_workspace_bytes(const ukv_pool_t *p, uint32_t n_requests, uint64_t total_q_rows) {
+    if (!p)
+        return 0;
+    return align_up(sizeof(ClassTable)) + align_up(prefill_rec_bound(p, n_requests, total_q_rows) * sizeof(PrefillRec));
+}
+
+int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q_len, void *workspace,
+                          size_t ws_bytes, void *stream) {
+    if (!p || !b) {
+        set_error("null pool or batch");
+        return UKV_EINVAL;
+    }
+    const uint32_t n = b->n_requests;
+    if (n == 0)
+        return UKV_OK;
+    if (!q_len || !b->service_id || !b->ctx_len || !b->table_off || !b->q_off || !b->out_off) {
+        set_error("batch host arrays and q_len must be non-null");
+        return UKV_EINVAL;
+    }
+    if (!b->page_table || !b->q || !b->out) {
+        set_error("page_table, q and out must be non-null device pointers");
+        return UKV_EINVAL;
+    }
+    if (!workspace || ((uintptr_t)workspace & 255)) {
+        set_error("workspace must be non-null and 256-byte aligned");
+        return UKV_EINVAL;
+    }
+    struct Group {
+        uint64_t cost;
+        uint32_t req, kvh;
+    };
+    std::vector<Group> groups;
+    uint64_t total_rows = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (b->service_id[i] >= p->n_services) {
+            set_error("service_id out of range");
+            return UKV_EINVAL;
+        }
+        const ClassRec &c = p->classes.c[b->service_id[i]];
+        if (q_len[i] > b->ctx_len[i]) {
+            set_error("q_len exceeds ctx_len");
+            return UKV_EINVAL;
+        }
+        if ((b->q_off[i] & 7) || (b->out_off[i] & 3)) {
+            set_error("q_off must be a multiple of 8 elements and out_off of 4");
+            return UKV_EINVAL;
+        }
+        if (ukv_pages_for_tokens(p, b->service_id[i], b->ctx_len[i]) > p->n_pages) {
+            set_error("ctx_len exceeds what the pool can hold");
+            return UKV_EINVAL;
+        }
+        if (q_len[i] == 0)
+            continue;
+        if (c.d != 128 || 16 % c.g != 0) {
+            set_error("prefill attention supports head_dim 128 with group 1, 2, 4 or 8");
+            return UKV_EINVAL;
+        }
+        total_rows += q_len[i];
+        // causal: row r looks at ctx_len - q_len + r + 1 tokens
+        const uint64_t first = (uint64_t)b->ctx_len[i] - q_len[i] + 1, last = b->ctx_len[i];
+        const uint64_t cost = (first + last) * q_len[i] / 2 * c.g;
+        for (uint32_t h = 0; h < c.n_kv; ++h)
+            groups.push_back(Group{cost, i, h});
+    }
+    if (groups.empty())
+        return UKV_OK;
+    std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
+    // heaviest group first onto the least loaded of the XCD queues
+    const uint32_t n_queues = p->tun.prefill_xcd ? kXcds : 1;
+    std::vector<std::vector<PrefillRec>> queue(n_queues);
+    std::vector<uint64_t> load(n_queues, 0);
+    for (const Group &g : groups) {
+        const uint32_t k = (uint32_t)(std::min_element(load.begin(), load.end()) - load.begin());
+        load[k] += g.cost;
+        const uint32_t i = g.req;
+        const ClassRec &c = p->classes.c[b->service_id[i]];
+        const uint32_t rows = kPrefillCols / c.g;
+        const uint32_t n_tiles = (q_len[i] + rows - 1) / rows;
+        for (uint32_t t = n_tiles; t-- > 0;) { // the last rows look at the most tokens: they go first
+            PrefillRec r{};
+            r.table_off = b->table_off[i];
+            r.q_off = b->q_off[i];
+            r.out_off = b->out_off[i];
+            r.ctx_len = b->ctx_len[i];
+            r.q_len = q_len[i];
+            r.cls = b->service_id[i];
+            r.kvh = g.kvh;
+            r.r0 = t * rows;
+            queue[k].push_back(r);
+        }
+    }
+    size_t longest = 0;
+    for (auto &qv : queue)
+        longest = std::max(longest, qv.size());
+    const size_t n_recs = longest * n_queues;
+    const size_t off_recs = align_up(sizeof(ClassTable));
+    const size_t total = align_up(off_recs + n_recs * sizeof(PrefillRec));
+    if (total > ws_bytes) {
+        set_error("workspace too small for this batch");
+        return UKV_ENOSPC;
+    }
+    int rc;
+    ukv_pool::Stage *st = nullptr;
+    if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
+        return rc;
+    unsigned char *h = (unsigned char *)st->host;
+    std::memcpy(h, &p->classes, sizeof(ClassTable));
+    PrefillRec *recs = (PrefillRec *)(h + off_recs);
+    std::memset(recs, 0, n_recs * sizeof(PrefillRec)); // q_len == 0: filler
+    for (uint32_t k = 0; k < n_queues; ++k)
+        for (size_t e = 0; e < queue[k].size(); ++e)
+            recs[e * n_queues + k] = queue[k][e];
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(launch_stage_copy(workspace, st->mapped, total, nullptr, nullptr, nullptr, 0, s), "launch plan upload");
+    if ((rc = stage_release_after(st, s)) != UKV_OK)
+        return rc;
+    unsigned char *w = (unsigned char *)workspace;
+    PrefillArgs a{};
+    a.pool_base = p->base;
+    a.log2_page = p->log2_page;
+    a.page_table = b->page_table;
+    a.q = (const uint16_t *)b->q;
+    a.out = (float *)b->out;
+    a.classes = (const ClassRec *)w;
+    a.recs = (const PrefillRec *)(w + off_recs);
+    ProfPair pp{p, 3};
+    if ((rc = pp.get()) != UKV_OK)
+        return rc;
+    HIP_TRY(launch_prefill(a, (uint32_t)n_recs, s, pp.ev.a, pp.ev.b), "launch prefill kernel");
+    pp.done();
+    (void)total_rows;
+    return UKV_OK;
+}
+
 int ukv_profile_read(ukv_pool_t *p, ukv_profile_t *out) {
     if (!p || !out) {
         set_error("null argument");
@@ -473,9 +623,12 @@ int ukv_profile_read(ukv_pool_t *p, ukv_profile_t *out) {
         } else if (e.which == 1) {
             out->n_reduce++;
             out->reduce_ms += ms;
-        } else {
+        } else if (e.which == 2) {
             out->n_append++;
             out->append_ms += ms;
+        } else {
+            out->n_prefill++;
+            out->prefill_ms += ms;
         }
         p->ev_free.push_back(e);
     }

@@ -86,6 +86,31 @@ struct AppendRec {
                      // patches those table entries; -1 = read the table
 };
 
+// Prefill: one workgroup = a tile of query rows of one (request, kv head).
+struct PrefillRec {
+    uint64_t table_off;
+    uint64_t q_off;   // element offset of the request's first query row
+    uint64_t out_off; // element offset of the request's first output row
+    uint32_t ctx_len; // tokens in the cache, the chunk's own included
+    uint32_t q_len;   // query rows of the request; row r is the token at position ctx_len - q_len + r
+    uint32_t cls;
+    uint32_t kvh;
+    uint32_t r0;      // first query row of the tile
+    uint32_t pad_[5]; // q_len == 0: filler workgroup (keeps the XCD interleave regular)
+};
+static_assert(sizeof(PrefillRec) == 64, "PrefillRec layout");
+
+struct PrefillArgs {
+    const unsigned char *pool_base;
+    uint32_t log2_page;
+    const int32_t *page_table;
+    const uint16_t *q; // bf16
+    float *out;
+    const ClassRec *classes;
+    const PrefillRec *recs;
+};
+static constexpr uint32_t kPrefillCols = 128; // (query row, query head of the group) pairs per workgroup
+
 struct GatherRec { // tokens [t0, t1) of one request
     uint64_t table_off;
     uint64_t kv_off;
@@ -109,6 +134,7 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
                          uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
                          const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                               const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
                               hipStream_t s);
@@ -136,6 +162,7 @@ struct Tunables {
     int64_t slots = 512; // workgroups resident at once (refreshed from the device at the first launch)
     int64_t taper = 1;
     int64_t gqa_cost_pct = 150; // planner weight of a matrix-core (grouped-query) KV byte, percent
+    int64_t prefill_xcd = 1;
     bool slots_auto = true;
 };
 

@@ -576,18 +576,13 @@ __device__ __forceinline__ void process_item() {
 // V is loaded row-major (lane (i, q): 16-byte chunk i of the 8 tokens tau(q, .), i.e. whole
 // 256-byte rows per 16 lanes) and transposed inside the lane with byte permutes; output row
 // (MFMA m, lane i) is d = 8i + m.  P is split into bf16 high and low parts (two products), so the
-// weights keep ~16 mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
+// weights keep 16 mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
 __device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
-
-__device__ __forceinline__ uint32_t bf16_rne_bits(float x) { // x finite, >= 0
-    const uint32_t u = __float_as_uint(x);
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
 
 template <int NT>
 __device__ __forceinline__ void process_item_gqa() {
@@ -706,17 +701,19 @@ __device__ __forceinline__ void process_item_gqa() {
                 const float mn = fmaxf(m, mt);
                 const float alpha = fast_exp2(m - mn);
                 m = mn;
+                // P as two bf16 parts by truncation: hi = upper 16 bits of p, lo = upper 16 bits of the
+                // exact remainder p - hi; hi + lo carries 16 mantissa bits.  One byte permute packs a pair.
                 uint32_t ph[4], pl[4];
                 float psum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; e += 2) {
                     const float p0 = fast_exp2(sc[e] - mn), p1 = fast_exp2(sc[e + 1] - mn);
                     psum += p0 + p1;
-                    const uint32_t h0 = bf16_rne_bits(p0), h1 = bf16_rne_bits(p1);
-                    const uint32_t l0 = bf16_rne_bits(p0 - __uint_as_float(h0 << 16));
-                    const uint32_t l1 = bf16_rne_bits(p1 - __uint_as_float(h1 << 16));
-                    ph[e / 2] = h0 | (h1 << 16);
-                    pl[e / 2] = l0 | (l1 << 16);
+                    const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+                    const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);
+                    const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+                    ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+                    pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
                 }
                 l = fmaf(l, alpha, psum);
                 if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
@@ -822,6 +819,215 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
         case kD128G1: process_item<128, 1, NT>(); break;
         case kD128GQA: process_item_gqa<NT>(); break;
         default: break;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Prefill phase (section 2.1): the queries of a chunk of prompt tokens attend, causally, to the
+// request's cache (their own K/V included; the caller has stored them with the bulk store).
+//
+// Same matrix-core formulation as the grouped-query decode path, with the 16 columns of a product
+// now (query row, query head of the group) pairs: a workgroup of four waves owns kPrefillCols = 128
+// such columns of one (request, kv head), each wave NB = 2 blocks of 16.  A wave walks the tokens
+// 0 .. (last position of its columns) in tiles of 32; the K rows and the transposed V of a tile are
+// loaded once and used for both blocks.  Column j of a block is row r0 + blk*(16/G) + j/G, head
+// j%G; the score of (token t, column) counts if t <= position(column) -- only the last tiles of a
+// block are partly masked, tiles wholly behind a block's rows are skipped.  The running maximum
+// starts at a large finite negative number, so that a column none of whose tokens has been seen yet
+// stays at weight 0 without inf - inf.
+static constexpr float kMinusBig = -1.0e30f;
+
+template <int NB>
+__global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
+    constexpr int D = 128, NT = 256;
+    __shared__ PrefillRec s_rec;
+    __shared__ ClassRec s_cls;
+    if (threadIdx.x == 0) {
+        s_rec = a.recs[blockIdx.x];
+        s_cls = a.classes[s_rec.cls];
+    }
+    __syncthreads();
+    const uint32_t q_len = uni(s_rec.q_len);
+    if (q_len == 0)
+        return; // filler
+    const uint64_t table_off = uni(s_rec.table_off), q_off = uni(s_rec.q_off), out_off = uni(s_rec.out_off);
+    const uint32_t ctx_len = uni(s_rec.ctx_len), kvh = uni(s_rec.kvh), r0 = uni(s_rec.r0);
+    const uint32_t G = uni(s_cls.g), n_q = uni(s_cls.n_q);
+    const uint64_t T = uni(s_cls.token_bytes);
+    const float scale_log2e = uni(s_cls.scale_log2e);
+    int32_t *tab = s_tab;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = uni((uint32_t)(tid >> 6));
+    const uint32_t j = lane & 15, q = lane >> 4;
+    const uint32_t lg = a.log2_page;
+    const uint64_t page_mask = (1ull << lg) - 1;
+    const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
+    const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
+    const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
+
+    // per block: this lane's column (row, head), its position, and the q operand
+    uint32_t col_pos[NB];
+    bool col_ok[NB];
+    bf16x8_t qB[NB][4];
+    f32x4_t oacc[NB][8];
+    float m[NB], l[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const uint32_t row = row_w + b * rpb + j / G;
+        col_ok[b] = row < q_len;
+        col_pos[b] = pos0 + row;
+        const uint4 *qp = reinterpret_cast<const uint4 *>(a.q + q_off + ((uint64_t)(col_ok[b] ? row : 0) * n_q + kvh * G +
+                                                                         j % G) * D) + q;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            uint4 w = ld_g16(qp + st * 4);
+            if (!col_ok[b])
+                w = make_uint4(0, 0, 0, 0);
+            qB[b][st] = as_bf16x8(w);
+        }
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm)
+            oacc[b][mm] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        m[b] = kMinusBig;
+        l[b] = 0.f;
+    }
+    // tokens this wave / this workgroup has to look at: up to the position of the last valid row
+    auto hi_of = [&](uint32_t first_row, uint32_t n_rows) -> uint32_t {
+        if (first_row >= q_len)
+            return 0;
+        const uint32_t last_row = min(first_row + n_rows, q_len) - 1;
+        return pos0 + last_row + 1;
+    };
+    const uint32_t wave_hi = hi_of(row_w, NB * rpb);
+    const uint32_t wg_hi = hi_of(r0, 4 * NB * rpb);
+    uint32_t blk_hi[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+        blk_hi[b] = hi_of(row_w + b * rpb, rpb);
+
+    const uint64_t row_off = (uint64_t)kvh * (4 * D);
+    uint32_t w0 = 0;
+    while (w0 < wg_hi) { // workgroup-uniform: one pass per page-table window
+        const uint64_t s_lo = ((uint64_t)w0 * T + row_off) >> lg;
+        const uint64_t lim = (s_lo + kTabWindow) << lg;
+        const uint64_t tmax = (lim - (row_off + 4 * D)) / T; // last token whose head-row ends inside the window
+        const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)wg_hi ? tmax + 1 : (uint64_t)wg_hi);
+        const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + row_off + 4 * D - 1) >> lg) - s_lo) + 1;
+        if (w0 != 0)
+            __syncthreads();
+        for (uint32_t e = tid; e < n_ent; e += NT)
+            tab[e] = as_global(a.page_table)[table_off + s_lo + e];
+        __syncthreads();
+
+        const uint32_t r1 = min(w1, wave_hi);
+        if (w0 < r1) {
+            const uint32_t last = r1 - 1;
+            auto row_ptr = [&](uint32_t t) -> const unsigned char * {
+                const uint64_t off = (uint64_t)t * T + row_off;
+                const int32_t pg = tab[(uint32_t)((off >> lg) - s_lo)];
+                return a.pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask);
+            };
+            auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
+            for (uint32_t tb = w0; tb < r1; tb += 32) {
+                u32x4 kA[8], vr[8];
+                {
+                    const unsigned char *p0 = row_ptr(min(tb + j, last)) + q * 16;
+                    const unsigned char *p1 = row_ptr(min(tb + 16 + j, last)) + q * 16;
+#pragma unroll
+                    for (int st = 0; st < 4; ++st) {
+                        kA[st] = ld_g16v(p0 + st * 64);
+                        kA[4 + st] = ld_g16v(p1 + st * 64);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        vr[e] = ld_g16v(row_ptr(min(tau(tb, e), last)) + 2 * D + j * 16);
+                }
+                // V^T operands of the tile, shared by the blocks: element mm of each token's chunk
+                bf16x8_t Vt[8];
+#pragma unroll
+                for (int mm = 0; mm < 8; ++mm) {
+                    const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
+                    uint32_t vt[4];
+#pragma unroll
+                    for (int pr = 0; pr < 4; ++pr)
+                        vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][mm / 2], vr[2 * pr][mm / 2], sel);
+                    Vt[mm] = as_bf16x8(make_uint4(vt[0], vt[1], vt[2], vt[3]));
+                }
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    if (tb >= blk_hi[b]) // wave-uniform: the tile lies behind every row of the block
+                        continue;
+                    f32x4_t s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f}, s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int st = 0; st < 4; ++st) {
+                        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[b][st], s0, 0, 0, 0);
+                        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[4 + st]), qB[b][st], s1, 0, 0, 0);
+                    }
+                    // causal mask: token t counts for this column if t <= its position (and lies in
+                    // this window: tokens past it were loaded as copies of the window's last token)
+                    const uint32_t t_lim = col_ok[b] ? min(col_pos[b] + 1, r1) : 0;
+                    float sc[8];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        sc[r] = (tb + 4 * q + r < t_lim) ? s0[r] * scale_log2e : -INFINITY;
+                        sc[4 + r] = (tb + 16 + 4 * q + r < t_lim) ? s1[r] * scale_log2e : -INFINITY;
+                    }
+                    float mt = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
+                                     fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+                    mt = fmaxf(mt, __shfl_xor(mt, 16));
+                    mt = fmaxf(mt, __shfl_xor(mt, 32));
+                    const float mn = fmaxf(m[b], mt); // finite: m starts at kMinusBig
+                    const float alpha = fast_exp2(m[b] - mn);
+                    m[b] = mn;
+                    uint32_t ph[4], pl[4];
+                    float psum = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2) {
+                        const float p0 = fast_exp2(sc[e] - mn), p1 = fast_exp2(sc[e + 1] - mn);
+                        psum += p0 + p1;
+                        const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+                        const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
+                        const float x1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+                        ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+                        pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
+                    }
+                    l[b] = fmaf(l[b], alpha, psum);
+                    if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+                        for (int mm = 0; mm < 8; ++mm)
+                            oacc[b][mm] *= alpha;
+                    }
+                    const bf16x8_t Ph = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                    const bf16x8_t Pl = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
+#pragma unroll
+                    for (int mm = 0; mm < 8; ++mm) {
+                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Ph, oacc[b][mm], 0, 0, 0);
+                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Pl, oacc[b][mm], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        w0 = w1;
+    }
+
+    // lane (j, q) holds O[column j][d = 32q + 8r + mm] in oacc[b][mm][r]; l is a per-lane partial sum
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float lb = l[b];
+        lb += __shfl_xor(lb, 16);
+        lb += __shfl_xor(lb, 32);
+        if (!col_ok[b])
+            continue;
+        const float inv = lb > 0.f ? 1.f / lb : 0.f;
+        const uint32_t row = col_pos[b] - pos0;
+        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 32 * q;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            st_g16(dst + 8 * r, oacc[b][0][r] * inv, oacc[b][1][r] * inv, oacc[b][2][r] * inv, oacc[b][3][r] * inv);
+            st_g16(dst + 8 * r + 4, oacc[b][4][r] * inv, oacc[b][5][r] * inv, oacc[b][6][r] * inv,
+                   oacc[b][7][r] * inv);
         }
     }
 }
@@ -1035,6 +1241,14 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
     hipExtLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, s, ev0, ev1, 0, pool_base, log2_page, page_table,
                           recs, n, classes, static_cast<const uint16_t *>(new_k),
                           static_cast<const uint16_t *>(new_v), patch_entry, patch_page, n_patches);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+    if (n_recs == 0)
+        return hipSuccess;
+    static_assert(kPrefillCols == 4 * 2 * 16, "four waves x two blocks of 16 columns");
+    hipExtLaunchKernelGGL(prefill_kernel<2>, dim3(n_recs), dim3(256), 0, s, ev0, ev1, 0, a);
     return hipGetLastError();
 }
 

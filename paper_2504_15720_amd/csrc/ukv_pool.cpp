@@ -279,6 +279,9 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
             return fail(UKV_EINVAL, "gqa_cost_pct must lie in 50..400");
         p->tun.gqa_cost_pct = value;
         return UKV_OK;
+    case UKV_PARAM_PREFILL_XCD:
+        p->tun.prefill_xcd = value ? 1 : 0;
+        return UKV_OK;
     case UKV_PARAM_TAPER:
         if (value < 0 || value > 95 || (value > 1 && value < 5))
             return fail(UKV_EINVAL, "taper must be 0, 1 or a percentage in 5..95");
@@ -302,6 +305,7 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_SLOTS: *value = p->tun.slots; return UKV_OK;
     case UKV_PARAM_TAPER: *value = p->tun.taper; return UKV_OK;
     case UKV_PARAM_GQA_COST_PCT: *value = p->tun.gqa_cost_pct; return UKV_OK;
+    case UKV_PARAM_PREFILL_XCD: *value = p->tun.prefill_xcd; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

@@ -19,4 +19,5 @@ from .workloads import (  # noqa: F401
     lockstep_order,
     pages_for_tokens,
     to_split_layout,
+    draw_prefill_inputs,
 )

@@ -266,6 +266,19 @@ class Batch:
         return entry, ids
 
 
+def draw_prefill_inputs(b: "Batch", q_len: np.ndarray, rng: np.random.Generator):
+    """Query rows for the prefill phase: request i gets q_len[i] rows of [n_q_heads, head_dim] bf16 bits.
+
+    Returns (q_bits flat, q_off, out_off, n_elems): element offsets of each request's first row in the flat
+    q array and in the (same-shaped) output array.  The requests' K/V are whatever the pool image holds."""
+    q_len = np.asarray(q_len, np.int64)
+    row = np.array([b.services[s].n_q_heads * b.services[s].head_dim for s in b.service_id], np.int64)
+    sizes = q_len * row
+    off = (np.cumsum(sizes) - sizes).astype(np.uint64)
+    n_elems = int(sizes.sum())
+    return normal_bf16(max(n_elems, 8), rng), off, off.copy(), max(n_elems, 8)
+
+
 def draw_lengths(law: dict, n: int, rng: np.random.Generator) -> np.ndarray:
     if law["kind"] == "uniform":
         return rng.integers(law["lo"], law["hi"] + 1, size=n).astype(np.int64)

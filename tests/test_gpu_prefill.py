@@ -1,0 +1,184 @@
+"""GPU parity of the prefill attention (causal, paged K/V) against the CPU oracle, row by row."""
+import sys
+
+import numpy as np
+import pytest
+
+import paper_2504_15720_amd as U
+from oracle import oracle
+from synth import SHAPES, Service, draw_prefill_inputs, make_batch
+from tests.ukv_harness import DeviceBatch
+
+pytestmark = pytest.mark.gpu
+ATOL = 2e-3
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _check_rows(b, out, q_bits, q_len, q_off, out_off, rows_of=None, tag=""):
+    """Compare the listed rows (default: all) of every request with the oracle."""
+    worst = 0.0
+    for i in range(b.n_requests):
+        s = b.service_of(i)
+        n, m = int(b.ctx_len[i]), int(q_len[i])
+        if m == 0:
+            continue
+        rows = np.arange(m) if rows_of is None else np.asarray(rows_of(m))
+        row_elems = s.n_q_heads * s.head_dim
+        qr = q_bits[int(q_off[i]):int(q_off[i]) + m * row_elems].reshape(m, s.n_q_heads, s.head_dim)
+        ref = oracle.prefill(b.pool, b.page_bytes, b.table_of(i), s.n_q_heads, s.n_kv_heads, s.head_dim,
+                             s.softmax_scale, n, n - m + rows, qr[rows])
+        got = out[int(out_off[i]):int(out_off[i]) + m * row_elems].reshape(m, s.n_q_heads, s.head_dim)[rows]
+        assert np.all(np.isfinite(got)), f"{tag}: non-finite output, request {i}"
+        err = float(np.max(np.abs(got.astype(np.float64) - ref)))
+        worst = max(worst, err)
+        assert err <= ATOL, f"{tag}: request {i} (ctx {n}, rows {m}): max |err| {err}"
+    say(f"  {tag}: max|err| = {worst:.3e}")
+    return worst
+
+
+SERVICES = [SHAPES["7b"], SHAPES["13b"], SHAPES["8b"], SHAPES["70b"], Service(16, 8, 128)]
+
+
+def test_whole_prompts_every_row():
+    say("prefill: whole prompts")
+    sid = np.array([0, 1, 2, 3, 4, 0, 2, 3, 4, 1, 0])
+    ctx = np.array([1, 5, 33, 130, 257, 384, 64, 17, 96, 128, 300])
+    rng = np.random.default_rng(31)
+    b = make_batch(SERVICES, sid, ctx, 4096, "permutation", rng, pool_seed=3)
+    db = DeviceBatch(b)
+    try:
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, ctx, rng)
+        for xcd in (1, 0):
+            U.ukv_set_param(db.pool, U.UKV_PARAM_PREFILL_XCD, xcd)
+            out_t, _ = db.prefill(ctx, q_bits, q_off, out_off, n_el)
+            _check_rows(b, out_t.cpu().numpy(), q_bits, ctx, q_off, out_off, tag=f"whole prompts, xcd interleave {xcd}")
+    finally:
+        db.close()
+
+
+def test_chunks_and_edge_cases():
+    """Chunked prefill (the last rows only), q_len 0 and 1, contexts on tile edges, rows that are not a
+    multiple of the workgroup's tile."""
+    say("prefill: chunks")
+    sid = np.array([0, 1, 2, 3, 4, 0, 1, 2, 3])
+    ctx = np.array([700, 512, 1000, 333, 640, 32, 0, 129, 2048])
+    q_len = np.array([100, 512, 1, 45, 128, 0, 0, 129, 31])
+    rng = np.random.default_rng(32)
+    b = make_batch(SERVICES, sid, ctx, 8192, "permutation", rng, pool_seed=4)
+    db = DeviceBatch(b)
+    try:
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        out = out_t.cpu().numpy()
+        _check_rows(b, out, q_bits, q_len, q_off, out_off, tag="chunks")
+        # a chunk of one row is a decode step: the same numbers as ukv_decode_attention gives
+        i = 2
+        s = b.service_of(i)
+        row = s.n_q_heads * s.head_dim
+        b.q = b.q.copy()
+        b.q[int(b.q_off[i]):int(b.q_off[i]) + row] = q_bits[int(q_off[i]):int(q_off[i]) + row]
+        db.set_q(b.q)
+        db.decode()
+        dec = db.out_host()[int(b.out_off[i]):int(b.out_off[i]) + row]
+        assert np.max(np.abs(dec - out[int(out_off[i]):int(out_off[i]) + row])) < 1e-5
+    finally:
+        db.close()
+
+
+def test_small_pages_long_table_windows():
+    """1 KiB pages: a 13B-shaped token spans 20 pages, so a few hundred tokens need several page-table
+    windows; the kv heads of a request sit at different places of the window."""
+    say("prefill: small pages")
+    sid = np.array([1, 3, 0])
+    ctx = np.array([450, 700, 130])
+    rng = np.random.default_rng(33)
+    b = make_batch(SERVICES, sid, ctx, 64 * 1024, "permutation", rng, page_bytes=1024, pool_seed=5)
+    db = DeviceBatch(b)
+    try:
+        q_len = np.array([450, 64, 130])
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        _check_rows(b, out_t.cpu().numpy(), q_bits, q_len, q_off, out_off,
+                    rows_of=lambda m: np.unique(np.r_[0, 1, m // 3, m // 2, m - 2, m - 1].clip(0, m - 1)),
+                    tag="1 KiB pages")
+    finally:
+        db.close()
+
+
+def test_future_tokens_do_not_leak():
+    """Overwrite the cache of the later tokens with huge finite values of both signs: earlier rows stay
+    bit-identical (masked weights are exactly zero; the contract asks for finite K/V within ctx_len)."""
+    say("prefill: causality on the device")
+    sid = np.array([2])
+    ctx = np.array([200])
+    rng = np.random.default_rng(34)
+    b = make_batch(SERVICES, sid, ctx, 1024, "permutation", rng, pool_seed=6)
+    q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, ctx, rng)
+    db = DeviceBatch(b)
+    try:
+        out_t, _ = db.prefill(ctx, q_bits, q_off, out_off, n_el)
+        base = out_t.cpu().numpy().copy()
+    finally:
+        db.close()
+    s = b.service_of(0)
+    cut = 77                                    # tokens >= cut become +-3.4e38
+    tab = b.table_of(0)
+    for t in range(cut, 200):
+        for byte in range(t * s.token_bytes, (t + 1) * s.token_bytes, 2):
+            b.pool[(int(tab[byte // b.page_bytes]) * b.page_bytes + byte % b.page_bytes) // 2] = \
+                0x7F7F if (byte // 2) % 3 else 0xFF7F
+    db = DeviceBatch(b)
+    try:
+        out_t, _ = db.prefill(ctx, q_bits, q_off, out_off, n_el)
+        got = out_t.cpu().numpy()
+    finally:
+        db.close()
+    row = s.n_q_heads * s.head_dim
+    assert np.array_equal(got[:cut * row], base[:cut * row])
+    assert not np.array_equal(got[cut * row:(cut + 1) * row], base[cut * row:(cut + 1) * row])
+
+
+def test_prefill_errors():
+    services = [SHAPES["7b"], SHAPES["h12"]]
+    rng = np.random.default_rng(35)
+    b = make_batch(services, np.array([0, 1]), np.array([40, 40]), 512, "permutation", rng, pool_seed=7)
+    db = DeviceBatch(b)
+    try:
+        q_len = np.array([40, 0])
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        db.prefill(q_len, q_bits, q_off, out_off, n_el)                      # a d = 64 request with no rows is fine
+        with pytest.raises(U.UkvError) as e:
+            db.prefill(np.array([40, 8]), *draw_prefill_inputs(b, np.array([40, 8]), rng))
+        assert e.value.code == U.UKV_EINVAL                                  # head_dim 64 is not supported
+        with pytest.raises(U.UkvError) as e:
+            db.prefill(np.array([41, 0]), *draw_prefill_inputs(b, np.array([41, 0]), rng))
+        assert e.value.code == U.UKV_EINVAL                                  # more rows than tokens
+        _, _, desc = db._pf_keep
+        with pytest.raises(U.UkvError) as e:
+            U.ukv_prefill_attention(db.pool, desc, q_len, db.pf_ws_t.data_ptr(), 256, db.stream())
+        assert e.value.code == U.UKV_ENOSPC
+    finally:
+        db.close()
+
+
+def test_long_prompts_sampled_rows():
+    """Prompts of the size the paper's summarization inputs have (about 13 k tokens, section 2.3) and a
+    GQA prompt of 8 k: rows at the start, around tile edges and at the end against the oracle."""
+    say("prefill: long prompts")
+    sid = np.array([0, 3, 2])
+    ctx = np.array([13000, 8192, 3000])
+    rng = np.random.default_rng(36)
+    b = make_batch(SERVICES, sid, ctx, 32768, "permutation", rng, pool_seed=8)
+    db = DeviceBatch(b)
+    try:
+        q_len = np.array([13000, 8192, 1000])
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        pick = lambda m: np.unique(np.r_[0, 1, 15, 16, 31, 32, 127, 128, m // 2, m - 129, m - 128, m - 2, m - 1].clip(0, m - 1))
+        _check_rows(b, out_t.cpu().numpy(), q_bits, q_len, q_off, out_off, rows_of=pick, tag="long prompts")
+    finally:
+        db.close()

@@ -79,6 +79,26 @@ class DeviceBatch:
         """append + attention as one launch"""
         U.ukv_decode_step(self.pool, desc, self.ws_t.data_ptr(), self.ws_bytes, self.stream())
 
+    def prefill(self, q_len, q_bits: np.ndarray, q_off, out_off, n_elems: int):
+        """Causal attention of the last q_len[i] tokens of every request; returns (fp32 output tensor, desc)."""
+        torch = self.torch
+        b = self.b
+        q_len = np.ascontiguousarray(q_len, np.uint32)
+        q_t = torch.from_numpy(q_bits.view(np.int16).copy()).to(self.dev)
+        out_t = torch.full((n_elems,), float("nan"), dtype=torch.float32, device=self.dev)
+        ws = U.ukv_prefill_workspace_bytes(self.pool, b.n_requests, int(q_len.sum()))
+        if getattr(self, "pf_ws_t", None) is None or self.pf_ws_t.numel() < ws:
+            self.pf_ws_t = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+        desc = U.BatchDesc(b.service_id, b.ctx_len, b.table_off, self.table_t.data_ptr(), q_t.data_ptr(), q_off,
+                           out_t.data_ptr(), out_off, self.newk_t.data_ptr(), self.newv_t.data_ptr(), b.new_off,
+                           None, None)
+        self._pf_keep = (q_t, out_t, desc)
+
+        def run():
+            U.ukv_prefill_attention(self.pool, desc, q_len, self.pf_ws_t.data_ptr(), ws, self.stream())
+        run()
+        return out_t, run
+
     def out_host(self) -> np.ndarray:
         return self.out_t.cpu().numpy()
 
