@@ -78,6 +78,68 @@ def cpu_baseline(batch, kv_bytes_total: int, target_s: float = 15.0):
     }
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+
+PREFILL_WORKLOADS = {
+    # name: (service shapes, request mix, prompt-length law, n prompts, pool pages)
+    "chat": (("7b", "8b"), (0.5, 0.5), dict(kind="lognormal", median=1024, sigma=0.8, max=8192), 32, 1 << 17),
+    "summarize": (("7b", "70b"), (0.5, 0.5), dict(kind="lognormal", median=13000, sigma=0.25, max=20000), 6,
+                  1 << 17),
+}
+
+
+def main_prefill(args):
+    """Prefill attention (next row after the decode path): whole prompts, causal; one JSON line."""
+    import numpy as np
+    import torch
+    import paper_2504_15720_amd as U
+    from synth import SHAPES, draw_prefill_inputs, make_batch
+    from synth.workloads import draw_lengths
+    from tests.ukv_harness import DeviceBatch
+
+    names, mix, law, n, pages = PREFILL_WORKLOADS[args.prefill_workload]
+    rng = np.random.default_rng(20250415 + 77)
+    services = [SHAPES[x] for x in names]
+    sid = rng.choice(len(services), size=n, p=mix)
+    ctx = np.maximum(draw_lengths(law, n, rng), 64)
+    b = make_batch(services, sid, ctx, pages, "permutation", rng, pool_seed=11)
+    db = DeviceBatch(b, profile=True)
+    if args.prefill_no_xcd:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_PREFILL_XCD, 0)
+    q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, ctx, rng)
+    _, run = db.prefill(ctx, q_bits, q_off, out_off, n_el)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    U.ukv_profile_read(db.pool)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = U.ukv_profile_read(db.pool)
+    k_ms = prof.prefill_ms / max(prof.n_prefill, 1)
+    # causal attention: row p of a prompt meets p + 1 tokens; 2 products x 2 flop x d per (row, token, query head)
+    flops = float(sum(4.0 * s.head_dim * s.n_q_heads * (int(c) * (int(c) + 1) / 2)
+                      for s, c in ((b.service_of(i), b.ctx_len[i]) for i in range(b.n_requests))))
+    tokens = int(ctx.sum())
+    line = {
+        "metric": "prefill-attention TFLOP/s (causal, paged KV), 1 GPU", "value": round(flops * args.steps / wall / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"prefill/{args.prefill_workload}: {n} whole prompts, services {names}, lengths {law}",
+                   "prompt_tokens": tokens, "flops_per_step": flops, "page_bytes": b.page_bytes},
+        "prompt_tokens_per_s": round(tokens * args.steps / wall, 1),
+        "kernel_ms": {"prefill": round(k_ms, 4)},
+        "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(flops / (k_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+    }
+    db.close()
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +153,9 @@ def main():
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
     ap.add_argument("--separate-append", action="store_true")
+    ap.add_argument("--phase", choices=["decode", "prefill"], default="decode")
+    ap.add_argument("--prefill-workload", choices=list(PREFILL_WORKLOADS), default="chat")
+    ap.add_argument("--prefill-no-xcd", action="store_true")
     ap.add_argument("--taper", type=int, default=0)
     ap.add_argument("--gqa-cost-pct", type=int, default=0)
     ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")
@@ -104,6 +169,9 @@ def main():
         print("bench.py: this build runs on ONE GPU; every GPU box here has one and the path uses no "
               "collectives. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+
+    if args.phase == "prefill":
+        return main_prefill(args)
 
     import numpy as np
     import torch

@@ -109,7 +109,8 @@ struct PrefillArgs {
     const ClassRec *classes;
     const PrefillRec *recs;
 };
-static constexpr uint32_t kPrefillCols = 128; // (query row, query head of the group) pairs per workgroup
+static constexpr uint32_t kPrefillBlocks = 2;                    // 16-column blocks per wave
+static constexpr uint32_t kPrefillCols = 64 * kPrefillBlocks;   // (query row, query head of the group) pairs per workgroup
 
 struct GatherRec { // tokens [t0, t1) of one request
     uint64_t table_off;

@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "ukv_internal.h"
 
 namespace ukv {
@@ -837,12 +839,27 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
 // starts at a large finite negative number, so that a column none of whose tokens has been seen yet
 // stays at weight 0 without inf - inf.
 static constexpr float kMinusBig = -1.0e30f;
+static constexpr float kLazy = 6.0f; // log2 of the largest weight tolerated before the reference moves
+// A staged tile in LDS: 32 K rows, then 32 V rows, 256 B each, written by global-to-LDS loads (no
+// registers in between; lane L of a wave instruction fills bytes [16 L, 16 L + 16) of a 1 KiB stretch,
+// from any global address).  A K row keeps its sixteen 16-byte pieces at positions piece ^ (token % 16),
+// so that the operand reads of eight adjacent lanes (one piece of eight rows) fall on different banks;
+// the V reads of eight adjacent lanes are 128 contiguous bytes of one row.  Two tiles: one is read
+// while the next is written.
+static constexpr int kPfTabWindow = 1024;
+static constexpr uint32_t kPfVOff = 32 * 256, kPfTileBytes = 2 * kPfVOff;
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef const __attribute__((address_space(1))) void *global_ptr_t;
 
 template <int NB>
-__global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
+__global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillArgs a) {
     constexpr int D = 128, NT = 256;
     __shared__ PrefillRec s_rec;
     __shared__ ClassRec s_cls;
+    __shared__ __align__(16) unsigned char s_kv[2 * kPfTileBytes];
+    __shared__ __align__(16) uint4 s_q[NB * 4 * 256]; // each lane's own q operands (parked here, not in 16 NB registers)
+    __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
+                                             // a workgroup sets how many of them fit a CU)
     if (threadIdx.x == 0) {
         s_rec = a.recs[blockIdx.x];
         s_cls = a.classes[s_rec.cls];
@@ -856,13 +873,15 @@ __global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
     const uint32_t G = uni(s_cls.g), n_q = uni(s_cls.n_q);
     const uint64_t T = uni(s_cls.token_bytes);
     const float scale_log2e = uni(s_cls.scale_log2e);
-    int32_t *tab = s_tab;
+    int32_t *tab = s_ptab;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t wave = uni((uint32_t)(tid >> 6));
     const uint32_t j = lane & 15, q = lane >> 4;
     const uint32_t lg = a.log2_page;
     const uint64_t page_mask = (1ull << lg) - 1;
+    // this lane's share of a staged tile: piece position (lane % 16) of tokens 8 wave + 4 x + lane / 16, x = 0, 1
+    const uint32_t ld_tok = 8 * wave + (lane >> 4), ld_pos = lane & 15;
     const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
     const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
     const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
@@ -870,7 +889,6 @@ __global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
     // per block: this lane's column (row, head), its position, and the q operand
     uint32_t col_pos[NB];
     bool col_ok[NB];
-    bf16x8_t qB[NB][4];
     f32x4_t oacc[NB][8];
     float m[NB], l[NB];
 #pragma unroll
@@ -885,7 +903,7 @@ __global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
             uint4 w = ld_g16(qp + st * 4);
             if (!col_ok[b])
                 w = make_uint4(0, 0, 0, 0);
-            qB[b][st] = as_bf16x8(w);
+            s_q[(b * 4 + st) * 256 + tid] = w; // read back by this lane only
         }
 #pragma unroll
         for (int mm = 0; mm < 8; ++mm)
@@ -902,16 +920,14 @@ __global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
     };
     const uint32_t wave_hi = hi_of(row_w, NB * rpb);
     const uint32_t wg_hi = hi_of(r0, 4 * NB * rpb);
-    uint32_t blk_hi[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-        blk_hi[b] = hi_of(row_w + b * rpb, rpb);
+    const uint32_t wave_lo = pos0 + row_w;                     // position of the wave's first row
+    const bool wave_full = row_w + NB * rpb <= q_len;          // all the wave's columns are valid rows
 
     const uint64_t row_off = (uint64_t)kvh * (4 * D);
     uint32_t w0 = 0;
     while (w0 < wg_hi) { // workgroup-uniform: one pass per page-table window
         const uint64_t s_lo = ((uint64_t)w0 * T + row_off) >> lg;
-        const uint64_t lim = (s_lo + kTabWindow) << lg;
+        const uint64_t lim = (s_lo + kPfTabWindow) << lg;
         const uint64_t tmax = (lim - (row_off + 4 * D)) / T; // last token whose head-row ends inside the window
         const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)wg_hi ? tmax + 1 : (uint64_t)wg_hi);
         const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + row_off + 4 * D - 1) >> lg) - s_lo) + 1;
@@ -921,71 +937,106 @@ __global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
             tab[e] = as_global(a.page_table)[table_off + s_lo + e];
         __syncthreads();
 
-        const uint32_t r1 = min(w1, wave_hi);
-        if (w0 < r1) {
-            const uint32_t last = r1 - 1;
+        const uint32_t r1 = min(w1, wave_hi); // this wave's tokens of the window end here
+        {
+            const uint32_t last = w1 - 1;
+            // Window-relative byte offsets fit 32 bits (a window spans at most kPfTabWindow pages).
+            const uint32_t c0 = (uint32_t)(((uint64_t)w0 * T + row_off) - (s_lo << lg));
+            const uint32_t T32 = (uint32_t)T, mask32 = (uint32_t)page_mask;
             auto row_ptr = [&](uint32_t t) -> const unsigned char * {
-                const uint64_t off = (uint64_t)t * T + row_off;
-                const int32_t pg = tab[(uint32_t)((off >> lg) - s_lo)];
-                return a.pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask);
+                const uint32_t off = (t - w0) * T32 + c0;
+                const int32_t pg = tab[off >> lg];
+                return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
+            };
+            // Tile staging: each wave fetches 8 of the tile's 32 head-rows (K | V, 512 B each) with four
+            // global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in
+            // the scores).
+            auto issue = [&](uint32_t tb, uint32_t buf) {
+#pragma unroll
+                for (uint32_t x = 0; x < 2; ++x) {
+                    const uint32_t tok = ld_tok + 4 * x;
+                    const unsigned char *rp = row_ptr(min(tb + tok, last));
+                    unsigned char *dst = s_kv + buf * kPfTileBytes + (2 * wave + x) * 1024;
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + ((ld_pos ^ (tok & 15)) * 16)), (lds_ptr_t)dst, 16,
+                                                     0, 0);
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + 2 * D + ld_pos * 16), (lds_ptr_t)(dst + kPfVOff),
+                                                     16, 0, 0);
+                }
             };
             auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
-            for (uint32_t tb = w0; tb < r1; tb += 32) {
-                u32x4 kA[8], vr[8];
-                {
-                    const unsigned char *p0 = row_ptr(min(tb + j, last)) + q * 16;
-                    const unsigned char *p1 = row_ptr(min(tb + 16 + j, last)) + q * 16;
-#pragma unroll
-                    for (int st = 0; st < 4; ++st) {
-                        kA[st] = ld_g16v(p0 + st * 64);
-                        kA[4 + st] = ld_g16v(p1 + st * 64);
-                    }
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        vr[e] = ld_g16v(row_ptr(min(tau(tb, e), last)) + 2 * D + j * 16);
-                }
-                // V^T operands of the tile, shared by the blocks: element mm of each token's chunk
-                bf16x8_t Vt[8];
-#pragma unroll
-                for (int mm = 0; mm < 8; ++mm) {
-                    const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
-                    uint32_t vt[4];
-#pragma unroll
-                    for (int pr = 0; pr < 4; ++pr)
-                        vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][mm / 2], vr[2 * pr][mm / 2], sel);
-                    Vt[mm] = as_bf16x8(make_uint4(vt[0], vt[1], vt[2], vt[3]));
-                }
+            // One tile against all NB blocks of the wave, stage by stage over the blocks, so that the
+            // blocks' independent instruction chains can overlap.  MASKED: the tile reaches past some
+            // column's position (or past the window); otherwise every score counts and the compares are
+            // skipped.  A block that lies wholly before the tile just sees every score masked.
+            auto tile_step = [&](uint32_t tb, const unsigned char *kv, auto masked) {
+                constexpr bool MASKED = decltype(masked)::value;
+                uint32_t tq = tid; // opaque per tile: keeps the q reads below inside the loop (out of registers)
+                asm volatile("" : "+v"(tq));
+                f32x4_t s0[NB], s1[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    if (tb >= blk_hi[b]) // wave-uniform: the tile lies behind every row of the block
-                        continue;
-                    f32x4_t s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f}, s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                    s0[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                    s1[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                }
 #pragma unroll
-                    for (int st = 0; st < 4; ++st) {
-                        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[b][st], s0, 0, 0, 0);
-                        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[4 + st]), qB[b][st], s1, 0, 0, 0);
-                    }
-                    // causal mask: token t counts for this column if t <= its position (and lies in
-                    // this window: tokens past it were loaded as copies of the window's last token)
-                    const uint32_t t_lim = col_ok[b] ? min(col_pos[b] + 1, r1) : 0;
-                    float sc[8];
+                for (int st = 0; st < 4; ++st) { // K rows of tokens j and 16+j, pieces st*4+q
+                    const uint32_t pc = ((st * 4 + q) ^ j) * 16; // (16 + j) % 16 == j
+                    const u32x4 k0 = *reinterpret_cast<const u32x4 *>(kv + j * 256 + pc);
+                    const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kv + (16 + j) * 256 + pc);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        sc[r] = (tb + 4 * q + r < t_lim) ? s0[r] * scale_log2e : -INFINITY;
-                        sc[4 + r] = (tb + 16 + 4 * q + r < t_lim) ? s1[r] * scale_log2e : -INFINITY;
+                    for (int b = 0; b < NB; ++b) {
+                        const bf16x8_t qb = as_bf16x8(s_q[(b * 4 + st) * 256 + tq]);
+                        s0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0), qb, s0[b], 0, 0, 0);
+                        s1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1), qb, s1[b], 0, 0, 0);
                     }
-                    float mt = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
-                                     fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-                    mt = fmaxf(mt, __shfl_xor(mt, 16));
-                    mt = fmaxf(mt, __shfl_xor(mt, 32));
-                    const float mn = fmaxf(m[b], mt); // finite: m starts at kMinusBig
-                    const float alpha = fast_exp2(m[b] - mn);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                float sc[NB][8], mt[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    if (MASKED) {
+                        // causal mask: token t counts for this column if t <= its position (and lies in
+                        // this window: tokens past it were loaded as copies of the window's last token)
+                        const uint32_t t_lim = col_ok[b] ? min(col_pos[b] + 1, r1) : 0;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            sc[b][r] = (tb + 4 * q + r < t_lim) ? s0[b][r] * scale_log2e : -INFINITY;
+                            sc[b][4 + r] = (tb + 16 + 4 * q + r < t_lim) ? s1[b][r] * scale_log2e : -INFINITY;
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            sc[b][r] = s0[b][r] * scale_log2e;
+                            sc[b][4 + r] = s1[b][r] * scale_log2e;
+                        }
+                    }
+                    mt[b] = fmaxf(fmaxf(fmaxf(sc[b][0], sc[b][1]), fmaxf(sc[b][2], sc[b][3])),
+                                  fmaxf(fmaxf(sc[b][4], sc[b][5]), fmaxf(sc[b][6], sc[b][7])));
+                }
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    mt[b] = fmaxf(mt[b], __shfl_xor(mt[b], 16));
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    mt[b] = fmaxf(mt[b], __shfl_xor(mt[b], 32));
+                float alpha[NB];
+                bf16x8_t Ph[NB], Pl[NB];
+                bool rescale = false;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    // The reference point of the exponentials only moves when the maximum has grown by
+                    // more than 2^kLazy: weights then stay below 2^kLazy, and the accumulators are rescaled
+                    // rarely.
+                    const float mn = mt[b] > m[b] + kLazy ? mt[b] : m[b]; // finite: m starts at kMinusBig
+                    alpha[b] = fast_exp2(m[b] - mn);
+                    rescale |= alpha[b] != 1.f;
                     m[b] = mn;
+                    // P as two bf16 parts by truncation (see process_item_gqa)
                     uint32_t ph[4], pl[4];
                     float psum = 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
-                        const float p0 = fast_exp2(sc[e] - mn), p1 = fast_exp2(sc[e + 1] - mn);
+                        const float p0 = fast_exp2(sc[b][e] - mn), p1 = fast_exp2(sc[b][e + 1] - mn);
                         psum += p0 + p1;
                         const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
                         const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
@@ -993,20 +1044,60 @@ __global__ void __launch_bounds__(256) prefill_kernel(PrefillArgs a) {
                         ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
                         pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
                     }
-                    l[b] = fmaf(l[b], alpha, psum);
-                    if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+                    l[b] = fmaf(l[b], alpha[b], psum);
+                    Ph[b] = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                    Pl[b] = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
+                }
+                if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
 #pragma unroll
                         for (int mm = 0; mm < 8; ++mm)
-                            oacc[b][mm] *= alpha;
-                    }
-                    const bf16x8_t Ph = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
-                    const bf16x8_t Pl = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
+                            oacc[b][mm] *= alpha[b];
+                }
+                // V from LDS (rows of the 8 tokens tau(q, .), piece j), transposed one output row group at
+                // a time and multiplied into every block.  The scheduling barrier keeps these 32 registers
+                // from being loaded before the scores are done with theirs.
+                __builtin_amdgcn_sched_barrier(0);
+                u32x4 vr[8];
 #pragma unroll
-                    for (int mm = 0; mm < 8; ++mm) {
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Ph, oacc[b][mm], 0, 0, 0);
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Pl, oacc[b][mm], 0, 0, 0);
+                for (int e = 0; e < 8; ++e)
+                    vr[e] = *reinterpret_cast<const u32x4 *>(kv + kPfVOff + tau(0, e) * 256 + j * 16);
+#pragma unroll
+                for (int mm = 0; mm < 8; ++mm) {
+                    const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
+                    uint32_t vt[4];
+#pragma unroll
+                    for (int pr = 0; pr < 4; ++pr)
+                        vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][mm / 2], vr[2 * pr][mm / 2], sel);
+                    const bf16x8_t Vt = as_bf16x8(make_uint4(vt[0], vt[1], vt[2], vt[3]));
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Ph[b], oacc[b][mm], 0, 0, 0);
+                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Pl[b], oacc[b][mm], 0, 0, 0);
                     }
                 }
+            };
+            issue(w0, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tile is in LDS
+            __syncthreads();
+            uint32_t cur = 0;
+            for (uint32_t tb = w0; tb < w1; tb += 32) { // workgroup-uniform
+                const bool more = tb + 32 < w1;
+                if (more)
+                    issue(tb + 32, cur ^ 1); // lands in the other tile while this one is computed
+                if (tb < r1) {
+                    const unsigned char *kv = s_kv + cur * kPfTileBytes;
+                    // wave-uniform: all 32 tokens lie in the window and at or before the wave's first row,
+                    // and every column of the wave is a valid row
+                    if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full)
+                        tile_step(tb, kv, std::false_type{});
+                    else
+                        tile_step(tb, kv, std::true_type{});
+                }
+                __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the next tile is in LDS
+                __syncthreads(); // the next tile is complete; the one just read may be overwritten
+                cur ^= 1;
             }
         }
         w0 = w1;
@@ -1247,8 +1338,8 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
 hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
-    static_assert(kPrefillCols == 4 * 2 * 16, "four waves x two blocks of 16 columns");
-    hipExtLaunchKernelGGL(prefill_kernel<2>, dim3(n_recs), dim3(256), 0, s, ev0, ev1, 0, a);
+    static_assert(kPrefillCols == 4 * kPrefillBlocks * 16, "four waves x NB blocks of 16 columns");
+    hipExtLaunchKernelGGL(prefill_kernel<kPrefillBlocks>, dim3(n_recs), dim3(256), 0, s, ev0, ev1, 0, a);
     return hipGetLastError();
 }
 
