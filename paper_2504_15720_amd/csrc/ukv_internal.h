@@ -109,8 +109,9 @@ struct PrefillArgs {
     const ClassRec *classes;
     const PrefillRec *recs;
 };
-static constexpr uint32_t kPrefillBlocks = 2;                    // 16-column blocks per wave
-static constexpr uint32_t kPrefillCols = 64 * kPrefillBlocks;   // (query row, query head of the group) pairs per workgroup
+static constexpr uint32_t kPrefillBlocks = 2; // 16-column blocks per wave
+static constexpr uint32_t kPrefillWaves = 4;  // waves per workgroup (8 was measured: slower, one workgroup per CU)
+static constexpr uint32_t kPrefillCols = 16 * kPrefillBlocks * kPrefillWaves; // (query row, query head) pairs per workgroup
 
 struct GatherRec { // tokens [t0, t1) of one request
     uint64_t table_off;

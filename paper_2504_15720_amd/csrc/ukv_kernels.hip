@@ -851,13 +851,14 @@ static constexpr uint32_t kPfVOff = 32 * 256, kPfTileBytes = 2 * kPfVOff;
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef const __attribute__((address_space(1))) void *global_ptr_t;
 
-template <int NB>
-__global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillArgs a) {
-    constexpr int D = 128, NT = 256;
+template <int NB, int NW>
+__global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
+    constexpr int D = 128, NT = 64 * NW; // NW = 4 or 8 waves
+    constexpr uint32_t TPW = 32 / NW;    // tokens of a tile each wave stages
     __shared__ PrefillRec s_rec;
     __shared__ ClassRec s_cls;
     __shared__ __align__(16) unsigned char s_kv[2 * kPfTileBytes];
-    __shared__ __align__(16) uint4 s_q[NB * 4 * 256]; // each lane's own q operands (parked here, not in 16 NB registers)
+    __shared__ __align__(16) uint4 s_q[NB * 4 * NT]; // each lane's own q operands (parked here, not in 16 NB registers)
     __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
                                              // a workgroup sets how many of them fit a CU)
     if (threadIdx.x == 0) {
@@ -880,8 +881,8 @@ __global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillAr
     const uint32_t j = lane & 15, q = lane >> 4;
     const uint32_t lg = a.log2_page;
     const uint64_t page_mask = (1ull << lg) - 1;
-    // this lane's share of a staged tile: piece position (lane % 16) of tokens 8 wave + 4 x + lane / 16, x = 0, 1
-    const uint32_t ld_tok = 8 * wave + (lane >> 4), ld_pos = lane & 15;
+    // this lane's share of a staged tile: piece position (lane % 16) of tokens TPW wave + 4 x + lane / 16
+    const uint32_t ld_tok = TPW * wave + (lane >> 4), ld_pos = lane & 15;
     const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
     const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
     const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
@@ -903,7 +904,7 @@ __global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillAr
             uint4 w = ld_g16(qp + st * 4);
             if (!col_ok[b])
                 w = make_uint4(0, 0, 0, 0);
-            s_q[(b * 4 + st) * 256 + tid] = w; // read back by this lane only
+            s_q[(b * 4 + st) * NT + tid] = w; // read back by this lane only
         }
 #pragma unroll
         for (int mm = 0; mm < 8; ++mm)
@@ -919,7 +920,7 @@ __global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillAr
         return pos0 + last_row + 1;
     };
     const uint32_t wave_hi = hi_of(row_w, NB * rpb);
-    const uint32_t wg_hi = hi_of(r0, 4 * NB * rpb);
+    const uint32_t wg_hi = hi_of(r0, NW * NB * rpb);
     const uint32_t wave_lo = pos0 + row_w;                     // position of the wave's first row
     const bool wave_full = row_w + NB * rpb <= q_len;          // all the wave's columns are valid rows
 
@@ -948,15 +949,15 @@ __global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillAr
                 const int32_t pg = tab[off >> lg];
                 return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
             };
-            // Tile staging: each wave fetches 8 of the tile's 32 head-rows (K | V, 512 B each) with four
-            // global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in
+            // Tile staging: each wave fetches TPW of the tile's 32 head-rows (K | V, 512 B each), four rows
+            // per pair of global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in
             // the scores).
             auto issue = [&](uint32_t tb, uint32_t buf) {
 #pragma unroll
-                for (uint32_t x = 0; x < 2; ++x) {
+                for (uint32_t x = 0; x < TPW / 4; ++x) {
                     const uint32_t tok = ld_tok + 4 * x;
                     const unsigned char *rp = row_ptr(min(tb + tok, last));
-                    unsigned char *dst = s_kv + buf * kPfTileBytes + (2 * wave + x) * 1024;
+                    unsigned char *dst = s_kv + buf * kPfTileBytes + ((TPW / 4) * wave + x) * 1024;
                     __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + ((ld_pos ^ (tok & 15)) * 16)), (lds_ptr_t)dst, 16,
                                                      0, 0);
                     __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + 2 * D + ld_pos * 16), (lds_ptr_t)(dst + kPfVOff),
@@ -985,7 +986,7 @@ __global__ void __launch_bounds__(256, NB == 1 ? 3 : 2) prefill_kernel(PrefillAr
                     const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kv + (16 + j) * 256 + pc);
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        const bf16x8_t qb = as_bf16x8(s_q[(b * 4 + st) * 256 + tq]);
+                        const bf16x8_t qb = as_bf16x8(s_q[(b * 4 + st) * NT + tq]);
                         s0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0), qb, s0[b], 0, 0, 0);
                         s1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1), qb, s1[b], 0, 0, 0);
                     }
@@ -1338,8 +1339,9 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
 hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
-    static_assert(kPrefillCols == 4 * kPrefillBlocks * 16, "four waves x NB blocks of 16 columns");
-    hipExtLaunchKernelGGL(prefill_kernel<kPrefillBlocks>, dim3(n_recs), dim3(256), 0, s, ev0, ev1, 0, a);
+    static_assert(kPrefillCols == kPrefillWaves * kPrefillBlocks * 16, "NW waves x NB blocks of 16 columns");
+    hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves>), dim3(n_recs), dim3(64 * kPrefillWaves), 0, s, ev0,
+                          ev1, 0, a);
     return hipGetLastError();
 }
 
