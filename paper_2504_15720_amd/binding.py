@@ -28,6 +28,8 @@ EXPORTS = [
     "ukv_gather",
     "ukv_scatter",
     "ukv_plan_decode", "ukv_set_param", "ukv_get_param", "ukv_profile_read", "ukv_strerror", "ukv_last_error",
+    "ukv_sched_create", "ukv_sched_destroy", "ukv_sched_add_request", "ukv_sched_next_batch", "ukv_sched_complete",
+    "ukv_sched_pages_needed", "ukv_sched_request_info", "ukv_sched_pending",
 ]
 
 
@@ -68,6 +70,18 @@ class ukv_profile_t(C.Structure):
                 ("prefill_ms", C.c_double)]
 
 
+class ukv_sched_service_t(C.Structure):
+    _fields_ = [("mean_time", C.c_double), ("std_time", C.c_double), ("starvation_threshold", C.c_double)]
+
+
+class ukv_sched_request_t(C.Structure):
+    _fields_ = [("service", C.c_uint32), ("queue", C.c_uint32), ("prompt_len", C.c_uint32), ("ctx_len", C.c_uint32),
+                ("doublings", C.c_uint32), ("arrival", C.c_double), ("budget", C.c_double), ("priority", C.c_double)]
+
+
+UKV_SCHED_WAIT, UKV_SCHED_DECODING = 0, 1
+
+
 class UkvError(RuntimeError):
     def __init__(self, code: int, what: str):
         self.code = code
@@ -106,6 +120,16 @@ def lib():
         L.ukv_set_param.argtypes = [vp, C.c_int, C.c_int64]
         L.ukv_get_param.argtypes = [vp, C.c_int, C.POINTER(C.c_int64)]
         L.ukv_profile_read.argtypes = [vp, C.POINTER(ukv_profile_t)]
+        L.ukv_sched_create.argtypes = [vp, C.POINTER(ukv_sched_service_t), C.c_uint32, C.c_uint32, C.POINTER(vp)]
+        L.ukv_sched_destroy.argtypes = [vp]
+        L.ukv_sched_add_request.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_double]
+        L.ukv_sched_next_batch.argtypes = [vp, C.c_double, C.c_uint64, vp, C.c_uint32, C.POINTER(C.c_uint32),
+                                           C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        L.ukv_sched_complete.argtypes = [vp, vp, vp, C.c_uint32, C.c_double, C.c_double]
+        L.ukv_sched_pages_needed.argtypes = [vp, C.c_uint64, C.POINTER(C.c_uint64)]
+        L.ukv_sched_request_info.argtypes = [vp, C.c_uint64, C.POINTER(ukv_sched_request_t)]
+        L.ukv_sched_pending.argtypes = [vp]
+        L.ukv_sched_pending.restype = C.c_uint32
         L.ukv_strerror.argtypes = [C.c_int]
         L.ukv_strerror.restype = C.c_char_p
         L.ukv_last_error.restype = C.c_char_p
@@ -244,6 +268,54 @@ def ukv_plan_decode(pool: int, batch: BatchDesc, want_items: bool = True):
         _check(lib().ukv_plan_decode(pool, C.byref(batch.c), C.byref(info), items.ctypes.data, info.n_items),
                "ukv_plan_decode")
     return info, items
+
+
+def ukv_sched_create(pool: int, profiles, max_batch: int) -> int:
+    """profiles: (mean_time, std_time, starvation_threshold) per service of the pool."""
+    arr = (ukv_sched_service_t * len(profiles))(*[ukv_sched_service_t(*map(float, p)) for p in profiles])
+    out = C.c_void_p()
+    _check(lib().ukv_sched_create(pool, arr, len(profiles), max_batch, C.byref(out)), "ukv_sched_create")
+    return out.value
+
+
+def ukv_sched_destroy(sched: int) -> None:
+    _check(lib().ukv_sched_destroy(sched), "ukv_sched_destroy")
+
+
+def ukv_sched_add_request(sched: int, rid: int, service: int, prompt_len: int, now: float) -> None:
+    _check(lib().ukv_sched_add_request(sched, rid, service, prompt_len, now), "ukv_sched_add_request")
+
+
+def ukv_sched_next_batch(sched: int, now: float, free_pages: int, cap: int = 4096):
+    """Returns (ids, service, queue)."""
+    ids = np.zeros(cap, np.uint64)
+    n, svc, queue = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    _check(lib().ukv_sched_next_batch(sched, now, free_pages, ids.ctypes.data, cap, C.byref(n), C.byref(svc),
+                                      C.byref(queue)), "ukv_sched_next_batch")
+    return [int(x) for x in ids[:n.value]], int(svc.value), int(queue.value)
+
+
+def ukv_sched_complete(sched: int, ids, finished, elapsed: float, now: float) -> None:
+    ids = np.ascontiguousarray(ids, np.uint64)
+    fin = np.ascontiguousarray(finished, np.uint8)
+    _check(lib().ukv_sched_complete(sched, ids.ctypes.data, fin.ctypes.data, ids.size, elapsed, now),
+           "ukv_sched_complete")
+
+
+def ukv_sched_pages_needed(sched: int, rid: int) -> int:
+    out = C.c_uint64()
+    _check(lib().ukv_sched_pages_needed(sched, rid, C.byref(out)), "ukv_sched_pages_needed")
+    return int(out.value)
+
+
+def ukv_sched_request_info(sched: int, rid: int) -> ukv_sched_request_t:
+    out = ukv_sched_request_t()
+    _check(lib().ukv_sched_request_info(sched, rid, C.byref(out)), "ukv_sched_request_info")
+    return out
+
+
+def ukv_sched_pending(sched: int) -> int:
+    return int(lib().ukv_sched_pending(sched))
 
 
 def ukv_profile_read(pool: int) -> ukv_profile_t:

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libukv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_kernels.hip"]
+SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_sched.cpp", "ukv_kernels.hip"]
 # packed fp32 VALU forms are switched off for device code on this target
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",

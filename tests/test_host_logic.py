@@ -19,7 +19,8 @@ def _pool(services, n_pages=1024, page_bytes=16384, base=FAKE_BASE):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "ukv.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read()
+                     for h in sorted(os.listdir(os.path.join(ROOT, "include"))) if h.endswith(".h"))
     declared = set(re.findall(r"\b(ukv_[a-z_]+)\s*\(", header))
     assert declared == set(U.EXPORTS), declared ^ set(U.EXPORTS)
     L = C.CDLL(U.LIB_PATH)

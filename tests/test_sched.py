@@ -198,3 +198,106 @@ def test_planted_scheduler_mistake_is_caught(name, monkeypatch):
     mod = _load_copy(text.replace(old, new))
     with pytest.raises(AssertionError):
         _pins(mod, monkeypatch)
+
+
+# ------------------------------------------------------------------ the C++ scheduler against the oracle
+
+
+def _trace_parity(seed, n_steps, services, profiles, max_batch, n_pages):
+    """Drive both schedulers with the same seeded arrivals, execution times and finishes; pages come from
+    the library's real free list.  Every decision must be identical."""
+    rng = np.random.default_rng(seed)
+    pool = U.ukv_pool_create(FAKE_BASE, n_pages * PAGE, PAGE, services)
+    sched = U.ukv_sched_create(pool, profiles, max_batch)
+    ref = dbs.DBScheduler([dbs.ServiceProfile(m, s, t, sv.token_bytes) for (m, s, t), sv in zip(profiles, services)],
+                          PAGE, max_batch)
+    owned, now, rid = {}, 0.0, 0
+    n_batches = n_empty = n_prefill = 0
+    try:
+        for _ in range(n_steps):
+            for _ in range(int(rng.integers(0, 3))):
+                svc, plen = int(rng.integers(0, len(services))), int(rng.integers(1, 300))
+                U.ukv_sched_add_request(sched, rid, svc, plen, now)
+                ref.add_request(rid, svc, plen, now)
+                rid += 1
+            free = int(U.ukv_pool_info(pool, 0).free_pages)
+            got = U.ukv_sched_next_batch(sched, now, free, cap=max_batch)
+            want = ref.next_batch(now, free)
+            assert got == (want[0], want[1], want[2]), (got, want)
+            ids, svc, queue = got
+            if not ids:
+                n_empty += 1
+                now += 0.05
+                # make room: finish the request that owns the most pages
+                if owned and U.ukv_sched_pending(sched):
+                    victim = max(owned, key=lambda k: len(owned[k]))
+                    info = U.ukv_sched_request_info(sched, victim)
+                    if info.queue == U.UKV_SCHED_DECODING:
+                        U.ukv_sched_complete(sched, [victim], [1], 0.0, now)
+                        ref.complete([victim], [True], 0.0, now)
+                        U.ukv_pages_free(pool, owned.pop(victim))
+                continue
+            n_batches += 1
+            n_prefill += queue == U.UKV_SCHED_WAIT
+            for i in ids:                                   # take the pages the iteration needs
+                need = U.ukv_sched_pages_needed(sched, i)
+                assert need == ref.pages_needed(ref.requests[i])
+                if need:
+                    owned.setdefault(i, []).extend(U.ukv_pages_alloc(pool, need).tolist())
+            elapsed = float(rng.uniform(0.01, 0.3))
+            now += elapsed
+            fin = [bool(queue == U.UKV_SCHED_DECODING and rng.random() < 0.03) for _ in ids]
+            U.ukv_sched_complete(sched, ids, fin, elapsed, now)
+            ref.complete(ids, fin, elapsed, now)
+            for i, f in zip(ids, fin):
+                if f and i in owned:
+                    U.ukv_pages_free(pool, owned.pop(i))
+            for i, f in zip(ids, fin):                     # state of the survivors
+                if not f:
+                    a, b = U.ukv_sched_request_info(sched, i), ref.requests[i]
+                    assert (a.queue, a.ctx_len, a.doublings, a.budget, a.priority) == \
+                           (b.queue, b.ctx_len, b.doublings, b.budget, b.priority)
+        assert U.ukv_sched_pending(sched) == len(ref.requests)
+    finally:
+        U.ukv_sched_destroy(sched)
+        U.ukv_pool_destroy(pool)
+    return n_batches, n_empty, n_prefill
+
+
+def test_cpp_scheduler_matches_the_oracle_decision_by_decision():
+    services = [SHAPES["7b"], SHAPES["8b"], SHAPES["13b"], SHAPES["h12"]]
+    profiles = [(1.0, 0.5, 4.0), (0.3, 0.1, 4.0), (2.5, 2.0, 6.0), (0.1, 0.05, 2.0)]
+    n_batches, n_empty, n_prefill = _trace_parity(11, 1500, services, profiles, max_batch=16, n_pages=6000)
+    assert n_batches > 1000 and n_prefill > 100
+    # a small pool: EnoughResource() cuts batches short and sometimes nothing fits
+    n_batches, n_empty, _ = _trace_parity(12, 1200, services, profiles, max_batch=8, n_pages=700)
+    assert n_batches > 300 and n_empty > 10
+    # no starvation thresholds in reach, one request per batch
+    _trace_parity(13, 600, services[:2], [(1.0, 0.0, 1e30), (3.0, 1.0, 1e30)], max_batch=1, n_pages=4000)
+
+
+def test_cpp_scheduler_rejects_bad_arguments():
+    services = [SHAPES["7b"], SHAPES["8b"]]
+    pool = U.ukv_pool_create(FAKE_BASE, 64 * PAGE, PAGE, services)
+    try:
+        with pytest.raises(U.UkvError):
+            U.ukv_sched_create(pool, [(1.0, 0.0, 1.0)], 4)                      # one profile per service
+        with pytest.raises(U.UkvError):
+            U.ukv_sched_create(pool, [(0.0, 0.0, 1.0), (1.0, 0.0, 1.0)], 4)     # mean_time must be positive
+        with pytest.raises(U.UkvError):
+            U.ukv_sched_create(pool, [(1.0, 0.0, 1.0), (1.0, 0.0, 1.0)], 0)
+        sched = U.ukv_sched_create(pool, [(1.0, 0.0, 1.0), (1.0, 0.0, 1.0)], 4)
+        U.ukv_sched_add_request(sched, 5, 1, 10, 0.0)
+        for bad in ((5, 0, 10), (6, 2, 10), (7, 0, 0)):                         # duplicate id, bad service, empty prompt
+            with pytest.raises(U.UkvError):
+                U.ukv_sched_add_request(sched, *bad, 0.0)
+        with pytest.raises(U.UkvError):
+            U.ukv_sched_complete(sched, [99], [0], 1.0, 1.0)
+        with pytest.raises(U.UkvError) as e:
+            U.ukv_sched_next_batch(sched, 0.0, 100, cap=2)
+        assert e.value.code == U.UKV_ENOSPC
+        assert U.ukv_sched_next_batch(sched, 0.0, 0, cap=4) == ([], 1, U.UKV_SCHED_WAIT)   # nothing fits
+        assert U.ukv_sched_next_batch(sched, 0.0, 100, cap=4) == ([5], 1, U.UKV_SCHED_WAIT)
+        U.ukv_sched_destroy(sched)
+    finally:
+        U.ukv_pool_destroy(pool)
