@@ -155,8 +155,8 @@ int ukv_decode_step(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace,
  * All ctx_len[i] tokens, the chunk's own included, must already be in the pool (ukv_scatter or
  * ukv_append) and hold finite values; bytes past ctx_len are never read.  q: DEVICE bf16 [q_len][n_q_heads][head_dim] per request at element offset q_off[i];
  * out: DEVICE fp32, same shape, at out_off[i]; q_len: HOST [n], 0 <= q_len[i] <= ctx_len[i].
- * fp32 accumulation as in ukv_decode_attention.  Services with head_dim 128 (g = 1, 2, 4, 8) only:
- * others give UKV_EINVAL.  workspace: DEVICE, 256-byte aligned, at least
+ * fp32 accumulation as in ukv_decode_attention.  Every shape ukv_pool_create accepts is supported
+ * (requests of head_dim 128 and of head_dim 64 run as two launches).  workspace: DEVICE, 256-byte aligned, at least
  * ukv_prefill_workspace_bytes(pool, n_requests, sum of q_len) bytes; else UKV_ENOSPC.
  * Uses service_id, ctx_len, table_off, page_table, q, q_off, out, out_off. */
 size_t ukv_prefill_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests, uint64_t total_q_rows);
@@ -208,7 +208,8 @@ int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
 int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 
 /* Kernel times collected while UKV_PARAM_PROFILE is 1 (HIP events on the caller's stream).
- * Reading waits for the recorded events and resets the accumulators. */
+ * Reading waits for the recorded events and resets the accumulators.  At most 8192 unread
+ * timings are kept; past that the oldest are dropped. */
 typedef struct {
     uint32_t n_decode, n_reduce, n_append, n_prefill;
     double decode_ms, reduce_ms, append_ms, prefill_ms; /* sums over the launches */

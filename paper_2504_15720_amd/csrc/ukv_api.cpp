@@ -59,6 +59,8 @@ int stage_release_after(ukv_pool::Stage *st, hipStream_t s) {
 
 // Profiling: the kernel's own start/stop timestamps, attached to its dispatch (no extra
 // barriers on the stream).  get() hands out a pair when profiling is on, else nulls.
+static constexpr size_t kMaxPendingTimings = 8192; // launches timed but not yet read by ukv_profile_read
+
 struct ProfPair {
     ukv_pool *p;
     int which;
@@ -66,6 +68,10 @@ struct ProfPair {
     int get() {
         if (!p->tun.profile)
             return UKV_OK;
+        if (p->ev_used.size() >= kMaxPendingTimings) { // nobody reads the profile: drop the oldest timings
+            p->ev_free.insert(p->ev_free.end(), p->ev_used.begin(), p->ev_used.end());
+            p->ev_used.clear();
+        }
         if (p->ev_free.empty()) { // create a batch at once, so the timed loop rarely creates events
             for (int k = 0; k < 64; ++k) {
                 ukv_pool::EvPair e{nullptr, nullptr, 0};
@@ -526,8 +532,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         }
         if (q_len[i] == 0)
             continue;
-        if (c.d != 128 || 16 % c.g != 0) {
-            set_error("prefill attention supports head_dim 128 with group 1, 2, 4 or 8");
+        if ((c.d != 128 && c.d != 64) || 16 % c.g != 0) {
+            set_error("prefill attention supports head_dim 128 or 64 with group 1, 2, 4, 8 or 16");
             return UKV_EINVAL;
         }
         total_rows += q_len[i];
@@ -540,34 +546,45 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     if (groups.empty())
         return UKV_OK;
     std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
-    // heaviest group first onto the least loaded of the XCD queues
+    // One record list (= one launch) per head_dim.  Within a list: heaviest group first onto the least
+    // loaded of the XCD queues, then the queues interleaved (padded with fillers to the longest).
     const uint32_t n_queues = p->tun.prefill_xcd ? kXcds : 1;
-    std::vector<std::vector<PrefillRec>> queue(n_queues);
-    std::vector<uint64_t> load(n_queues, 0);
-    for (const Group &g : groups) {
-        const uint32_t k = (uint32_t)(std::min_element(load.begin(), load.end()) - load.begin());
-        load[k] += g.cost;
-        const uint32_t i = g.req;
-        const ClassRec &c = p->classes.c[b->service_id[i]];
-        const uint32_t rows = kPrefillCols / c.g;
-        const uint32_t n_tiles = (q_len[i] + rows - 1) / rows;
-        for (uint32_t t = n_tiles; t-- > 0;) { // the last rows look at the most tokens: they go first
-            PrefillRec r{};
-            r.table_off = b->table_off[i];
-            r.q_off = b->q_off[i];
-            r.out_off = b->out_off[i];
-            r.ctx_len = b->ctx_len[i];
-            r.q_len = q_len[i];
-            r.cls = b->service_id[i];
-            r.kvh = g.kvh;
-            r.r0 = t * rows;
-            queue[k].push_back(r);
+    static const uint32_t kDims[2] = {128, 64};
+    std::vector<PrefillRec> list[2];
+    for (int di = 0; di < 2; ++di) {
+        std::vector<std::vector<PrefillRec>> queue(n_queues);
+        std::vector<uint64_t> load(n_queues, 0);
+        for (const Group &g : groups) {
+            const uint32_t i = g.req;
+            const ClassRec &c = p->classes.c[b->service_id[i]];
+            if (c.d != kDims[di])
+                continue;
+            const uint32_t k = (uint32_t)(std::min_element(load.begin(), load.end()) - load.begin());
+            load[k] += g.cost;
+            const uint32_t rows = kPrefillCols / c.g;
+            const uint32_t n_tiles = (q_len[i] + rows - 1) / rows;
+            for (uint32_t t = n_tiles; t-- > 0;) { // the last rows look at the most tokens: they go first
+                PrefillRec r{};
+                r.table_off = b->table_off[i];
+                r.q_off = b->q_off[i];
+                r.out_off = b->out_off[i];
+                r.ctx_len = b->ctx_len[i];
+                r.q_len = q_len[i];
+                r.cls = b->service_id[i];
+                r.kvh = g.kvh;
+                r.r0 = t * rows;
+                queue[k].push_back(r);
+            }
         }
+        size_t longest = 0;
+        for (auto &qv : queue)
+            longest = std::max(longest, qv.size());
+        list[di].assign(longest * n_queues, PrefillRec{}); // q_len == 0: filler
+        for (uint32_t k = 0; k < n_queues; ++k)
+            for (size_t e = 0; e < queue[k].size(); ++e)
+                list[di][e * n_queues + k] = queue[k][e];
     }
-    size_t longest = 0;
-    for (auto &qv : queue)
-        longest = std::max(longest, qv.size());
-    const size_t n_recs = longest * n_queues;
+    const size_t n_recs = list[0].size() + list[1].size();
     const size_t off_recs = align_up(sizeof(ClassTable));
     const size_t total = align_up(off_recs + n_recs * sizeof(PrefillRec));
     if (total > ws_bytes) {
@@ -581,10 +598,10 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     unsigned char *h = (unsigned char *)st->host;
     std::memcpy(h, &p->classes, sizeof(ClassTable));
     PrefillRec *recs = (PrefillRec *)(h + off_recs);
-    std::memset(recs, 0, n_recs * sizeof(PrefillRec)); // q_len == 0: filler
-    for (uint32_t k = 0; k < n_queues; ++k)
-        for (size_t e = 0; e < queue[k].size(); ++e)
-            recs[e * n_queues + k] = queue[k][e];
+    if (!list[0].empty())
+        std::memcpy(recs, list[0].data(), list[0].size() * sizeof(PrefillRec));
+    if (!list[1].empty())
+        std::memcpy(recs + list[0].size(), list[1].data(), list[1].size() * sizeof(PrefillRec));
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(launch_stage_copy(workspace, st->mapped, total, nullptr, nullptr, nullptr, 0, s), "launch plan upload");
     if ((rc = stage_release_after(st, s)) != UKV_OK)
@@ -597,12 +614,18 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     a.q = (const uint16_t *)b->q;
     a.out = (float *)b->out;
     a.classes = (const ClassRec *)w;
-    a.recs = (const PrefillRec *)(w + off_recs);
-    ProfPair pp{p, 3};
-    if ((rc = pp.get()) != UKV_OK)
-        return rc;
-    HIP_TRY(launch_prefill(a, (uint32_t)n_recs, s, pp.ev.a, pp.ev.b), "launch prefill kernel");
-    pp.done();
+    size_t first = 0;
+    for (int di = 0; di < 2; ++di) {
+        if (list[di].empty())
+            continue;
+        a.recs = (const PrefillRec *)(w + off_recs) + first;
+        ProfPair pp{p, 3};
+        if ((rc = pp.get()) != UKV_OK)
+            return rc;
+        HIP_TRY(launch_prefill(a, (uint32_t)list[di].size(), kDims[di], s, pp.ev.a, pp.ev.b), "launch prefill kernel");
+        pp.done();
+        first += list[di].size();
+    }
     (void)total_rows;
     return UKV_OK;
 }

@@ -136,7 +136,8 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
                          uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
                          const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1);
-hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, hipStream_t s, hipEvent_t ev0,
+                          hipEvent_t ev1);
 hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                               const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
                               hipStream_t s);

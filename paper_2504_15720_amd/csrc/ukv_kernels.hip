@@ -840,25 +840,31 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
 // stays at weight 0 without inf - inf.
 static constexpr float kMinusBig = -1.0e30f;
 static constexpr float kLazy = 6.0f; // log2 of the largest weight tolerated before the reference moves
-// A staged tile in LDS: 32 K rows, then 32 V rows, 256 B each, written by global-to-LDS loads (no
-// registers in between; lane L of a wave instruction fills bytes [16 L, 16 L + 16) of a 1 KiB stretch,
-// from any global address).  A K row keeps its sixteen 16-byte pieces at positions piece ^ (token % 16),
+// A staged tile in LDS: 32 K rows, then 32 V rows, 2 head_dim bytes each, written by global-to-LDS loads
+// (no registers in between; lane L of a wave instruction fills bytes [16 L, 16 L + 16) of a 1 KiB stretch,
+// from any global address).  A K row keeps its 16-byte pieces at positions piece ^ (token % pieces),
 // so that the operand reads of eight adjacent lanes (one piece of eight rows) fall on different banks;
 // the V reads of eight adjacent lanes are 128 contiguous bytes of one row.  Two tiles: one is read
 // while the next is written.
 static constexpr int kPfTabWindow = 1024;
-static constexpr uint32_t kPfVOff = 32 * 256, kPfTileBytes = 2 * kPfVOff;
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef const __attribute__((address_space(1))) void *global_ptr_t;
 
-template <int NB, int NW>
+template <int NB, int NW, int D>
 __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
-    constexpr int D = 128, NT = 64 * NW; // NW = 4 or 8 waves
-    constexpr uint32_t TPW = 32 / NW;    // tokens of a tile each wave stages
+    constexpr int NT = 64 * NW;             // NW = 4 or 8 waves; D = 128 or 64
+    constexpr uint32_t KB = 2 * D;          // bytes of the K (or V) part of a head-row
+    constexpr uint32_t PIECES = KB / 16;    // 16-byte pieces of it
+    constexpr int KSTEPS = D / 32;          // products of 32 along head_dim for one score tile
+    constexpr int MM = D / 16;              // products of 16 output rows (head_dim elements) for O^T
+    constexpr uint32_t RPI = 1024 / KB;     // head-rows one staging instruction (1 KiB) covers
+    constexpr uint32_t KI = 32 / RPI / NW;  // staging instructions per wave, tile and part (K, V)
+    static_assert(KI >= 1, "too many waves for this head_dim");
+    constexpr uint32_t kVOff = 32 * KB, kTileBytes = 2 * kVOff;
     __shared__ PrefillRec s_rec;
     __shared__ ClassRec s_cls;
-    __shared__ __align__(16) unsigned char s_kv[2 * kPfTileBytes];
-    __shared__ __align__(16) uint4 s_q[NB * 4 * NT]; // each lane's own q operands (parked here, not in 16 NB registers)
+    __shared__ __align__(16) unsigned char s_kv[2 * kTileBytes];
+    __shared__ __align__(16) uint4 s_q[NB * KSTEPS * NT]; // each lane's own q operands (parked here, not in registers)
     __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
                                              // a workgroup sets how many of them fit a CU)
     if (threadIdx.x == 0) {
@@ -881,8 +887,8 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     const uint32_t j = lane & 15, q = lane >> 4;
     const uint32_t lg = a.log2_page;
     const uint64_t page_mask = (1ull << lg) - 1;
-    // this lane's share of a staged tile: piece position (lane % 16) of tokens TPW wave + 4 x + lane / 16
-    const uint32_t ld_tok = TPW * wave + (lane >> 4), ld_pos = lane & 15;
+    // this lane's share of a staged tile: piece position lane % PIECES of tokens RPI (KI wave + x) + lane / PIECES
+    const uint32_t ld_tok = RPI * KI * wave + lane / PIECES, ld_pos = lane % PIECES;
     const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
     const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
     const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
@@ -890,7 +896,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     // per block: this lane's column (row, head), its position, and the q operand
     uint32_t col_pos[NB];
     bool col_ok[NB];
-    f32x4_t oacc[NB][8];
+    f32x4_t oacc[NB][MM];
     float m[NB], l[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -900,14 +906,14 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         const uint4 *qp = reinterpret_cast<const uint4 *>(a.q + q_off + ((uint64_t)(col_ok[b] ? row : 0) * n_q + kvh * G +
                                                                          j % G) * D) + q;
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
+        for (int st = 0; st < KSTEPS; ++st) {
             uint4 w = ld_g16(qp + st * 4);
             if (!col_ok[b])
                 w = make_uint4(0, 0, 0, 0);
-            s_q[(b * 4 + st) * NT + tid] = w; // read back by this lane only
+            s_q[(b * KSTEPS + st) * NT + tid] = w; // read back by this lane only
         }
 #pragma unroll
-        for (int mm = 0; mm < 8; ++mm)
+        for (int mm = 0; mm < MM; ++mm)
             oacc[b][mm] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         m[b] = kMinusBig;
         l[b] = 0.f;
@@ -949,19 +955,19 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 const int32_t pg = tab[off >> lg];
                 return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
             };
-            // Tile staging: each wave fetches TPW of the tile's 32 head-rows (K | V, 512 B each), four rows
-            // per pair of global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in
-            // the scores).
+            // Tile staging: each wave fetches RPI KI of the tile's 32 head-rows (K | V), RPI rows per pair of
+            // global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in the
+            // scores).
             auto issue = [&](uint32_t tb, uint32_t buf) {
 #pragma unroll
-                for (uint32_t x = 0; x < TPW / 4; ++x) {
-                    const uint32_t tok = ld_tok + 4 * x;
+                for (uint32_t x = 0; x < KI; ++x) {
+                    const uint32_t tok = ld_tok + RPI * x;
                     const unsigned char *rp = row_ptr(min(tb + tok, last));
-                    unsigned char *dst = s_kv + buf * kPfTileBytes + ((TPW / 4) * wave + x) * 1024;
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + ((ld_pos ^ (tok & 15)) * 16)), (lds_ptr_t)dst, 16,
-                                                     0, 0);
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + 2 * D + ld_pos * 16), (lds_ptr_t)(dst + kPfVOff),
+                    unsigned char *dst = s_kv + buf * kTileBytes + (KI * wave + x) * 1024;
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + ((ld_pos ^ (tok % PIECES)) * 16)), (lds_ptr_t)dst,
                                                      16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + KB + ld_pos * 16), (lds_ptr_t)(dst + kVOff), 16,
+                                                     0, 0);
                 }
             };
             auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
@@ -980,13 +986,13 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     s1[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
                 }
 #pragma unroll
-                for (int st = 0; st < 4; ++st) { // K rows of tokens j and 16+j, pieces st*4+q
-                    const uint32_t pc = ((st * 4 + q) ^ j) * 16; // (16 + j) % 16 == j
-                    const u32x4 k0 = *reinterpret_cast<const u32x4 *>(kv + j * 256 + pc);
-                    const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kv + (16 + j) * 256 + pc);
+                for (int st = 0; st < KSTEPS; ++st) { // K rows of tokens j and 16+j, pieces st*4+q
+                    const uint32_t pc = ((st * 4 + q) ^ (j % PIECES)) * 16; // (16 + j) % PIECES == j % PIECES
+                    const u32x4 k0 = *reinterpret_cast<const u32x4 *>(kv + j * KB + pc);
+                    const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kv + (16 + j) * KB + pc);
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        const bf16x8_t qb = as_bf16x8(s_q[(b * 4 + st) * NT + tq]);
+                        const bf16x8_t qb = as_bf16x8(s_q[(b * KSTEPS + st) * NT + tq]);
                         s0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0), qb, s0[b], 0, 0, 0);
                         s1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1), qb, s1[b], 0, 0, 0);
                     }
@@ -1053,19 +1059,31 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
 #pragma unroll
                     for (int b = 0; b < NB; ++b)
 #pragma unroll
-                        for (int mm = 0; mm < 8; ++mm)
+                        for (int mm = 0; mm < MM; ++mm)
                             oacc[b][mm] *= alpha[b];
                 }
                 // V from LDS (rows of the 8 tokens tau(q, .), piece j), transposed one output row group at
                 // a time and multiplied into every block.  The scheduling barrier keeps these 32 registers
                 // from being loaded before the scores are done with theirs.
                 __builtin_amdgcn_sched_barrier(0);
-                u32x4 vr[8];
+                // lane (j, q): MM consecutive elements (d = MM j ...) of the rows of its 8 tokens
+                uint32_t vr[8][MM / 2];
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    vr[e] = *reinterpret_cast<const u32x4 *>(kv + kPfVOff + tau(0, e) * 256 + j * 16);
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned char *vp = kv + kVOff + tau(0, e) * KB + j * (2 * MM);
+                    if (MM == 8) {
+                        const u32x4 w = *reinterpret_cast<const u32x4 *>(vp);
 #pragma unroll
-                for (int mm = 0; mm < 8; ++mm) {
+                        for (int c = 0; c < MM / 2; ++c)
+                            vr[e][c] = w[c];
+                    } else {
+                        const uint2 w = *reinterpret_cast<const uint2 *>(vp);
+                        vr[e][0] = w.x;
+                        vr[e][1] = w.y;
+                    }
+                }
+#pragma unroll
+                for (int mm = 0; mm < MM; ++mm) {
                     const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
                     uint32_t vt[4];
 #pragma unroll
@@ -1088,7 +1106,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 if (more)
                     issue(tb + 32, cur ^ 1); // lands in the other tile while this one is computed
                 if (tb < r1) {
-                    const unsigned char *kv = s_kv + cur * kPfTileBytes;
+                    const unsigned char *kv = s_kv + cur * kTileBytes;
                     // wave-uniform: all 32 tokens lie in the window and at or before the wave's first row,
                     // and every column of the wave is a valid row
                     if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full)
@@ -1104,7 +1122,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         w0 = w1;
     }
 
-    // lane (j, q) holds O[column j][d = 32q + 8r + mm] in oacc[b][mm][r]; l is a per-lane partial sum
+    // lane (j, q) holds O[column j][d = MM (4q + r) + mm] in oacc[b][mm][r]; l is a per-lane partial sum
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         float lb = l[b];
@@ -1114,13 +1132,13 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             continue;
         const float inv = lb > 0.f ? 1.f / lb : 0.f;
         const uint32_t row = col_pos[b] - pos0;
-        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 32 * q;
+        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 4 * MM * q;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            st_g16(dst + 8 * r, oacc[b][0][r] * inv, oacc[b][1][r] * inv, oacc[b][2][r] * inv, oacc[b][3][r] * inv);
-            st_g16(dst + 8 * r + 4, oacc[b][4][r] * inv, oacc[b][5][r] * inv, oacc[b][6][r] * inv,
-                   oacc[b][7][r] * inv);
-        }
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < MM; c += 4)
+                st_g16(dst + MM * r + c, oacc[b][c][r] * inv, oacc[b][c + 1][r] * inv, oacc[b][c + 2][r] * inv,
+                       oacc[b][c + 3][r] * inv);
     }
 }
 
@@ -1336,12 +1354,17 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
     return hipGetLastError();
 }
 
-hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, hipStream_t s, hipEvent_t ev0,
+                          hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
     static_assert(kPrefillCols == kPrefillWaves * kPrefillBlocks * 16, "NW waves x NB blocks of 16 columns");
-    hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves>), dim3(n_recs), dim3(64 * kPrefillWaves), 0, s, ev0,
-                          ev1, 0, a);
+    if (head_dim == 128)
+        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 128>), dim3(n_recs),
+                              dim3(64 * kPrefillWaves), 0, s, ev0, ev1, 0, a);
+    else
+        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 64>), dim3(n_recs),
+                              dim3(64 * kPrefillWaves), 0, s, ev0, ev1, 0, a);
     return hipGetLastError();
 }
 

@@ -89,6 +89,34 @@ def test_chunks_and_edge_cases():
         db.close()
 
 
+def test_head_dim_64_services_alone_and_mixed_with_128():
+    """head_dim 64 (12/12, 8/8 and a grouped 8/4 shape) takes its own launch; mixed batches split by head_dim."""
+    say("prefill: head_dim 64")
+    services = [SHAPES["h12"], SHAPES["tiny"], Service(8, 4, 64), SHAPES["8b"]]
+    sid = np.array([0, 1, 2, 3, 0, 1, 2, 0])
+    ctx = np.array([130, 33, 257, 96, 1, 64, 700, 385])
+    q_len = np.array([130, 33, 257, 96, 1, 10, 123, 385])
+    rng = np.random.default_rng(37)
+    b = make_batch(services, sid, ctx, 2048, "permutation", rng, pool_seed=9)
+    db = DeviceBatch(b)
+    try:
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        _check_rows(b, out_t.cpu().numpy(), q_bits, q_len, q_off, out_off, tag="head_dim 64 and 128 mixed")
+    finally:
+        db.close()
+    b = make_batch(services[:3], np.array([0, 2, 1]), np.array([300, 200, 77]), 4096, "permutation", rng,
+                   page_bytes=1024, pool_seed=10)
+    db = DeviceBatch(b)
+    try:
+        q_len = np.array([300, 64, 77])
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        _check_rows(b, out_t.cpu().numpy(), q_bits, q_len, q_off, out_off, tag="head_dim 64, 1 KiB pages")
+    finally:
+        db.close()
+
+
 def test_small_pages_long_table_windows():
     """1 KiB pages: a 13B-shaped token spans 20 pages, so a few hundred tokens need several page-table
     windows; the kv heads of a request sit at different places of the window."""
@@ -150,10 +178,7 @@ def test_prefill_errors():
     try:
         q_len = np.array([40, 0])
         q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
-        db.prefill(q_len, q_bits, q_off, out_off, n_el)                      # a d = 64 request with no rows is fine
-        with pytest.raises(U.UkvError) as e:
-            db.prefill(np.array([40, 8]), *draw_prefill_inputs(b, np.array([40, 8]), rng))
-        assert e.value.code == U.UKV_EINVAL                                  # head_dim 64 is not supported
+        db.prefill(q_len, q_bits, q_off, out_off, n_el)
         with pytest.raises(U.UkvError) as e:
             db.prefill(np.array([41, 0]), *draw_prefill_inputs(b, np.array([41, 0]), rng))
         assert e.value.code == U.UKV_EINVAL                                  # more rows than tokens
