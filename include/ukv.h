@@ -12,7 +12,8 @@
  * bf16.  One such K|V pair is a head-row of R = 4*head_dim bytes; a token occupies
  * T = n_kv_heads*R bytes (= n_kv_heads*head_dim*2*sizeof(bf16)).  Stream byte s lives in
  * physical page  page_table[table_off + s / page_bytes]  at in-page offset
- * s % page_bytes (the second index; it is derived, not stored).  page_bytes must be a
+ * s % page_bytes (the second index; it is derived, not stored).  page_bytes is a power of
+ * two between 1 KiB and 1 MiB and must be a
  * multiple of every service's R, so a head-row never straddles pages; token rows may.
  * A request of n tokens owns ceil(n*T/page_bytes) pages.
  *

@@ -586,6 +586,15 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
 __device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
 
+// Maximum over the lanes l, l^16, l^32, l^48 (the four k-blocks of one column), in every one of
+// them: two lane swaps instead of two round trips through the LDS permute path.
+__device__ __forceinline__ float max_over_kblocks(float x) {
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1])); // lanes [0,32) and [32,64) exchanged
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])); // odd and even rows of 16 exchanged
+}
+
 template <int NT>
 __device__ __forceinline__ void process_item_gqa() {
     const DecodeArgs a = ctx_args();
@@ -659,19 +668,19 @@ __device__ __forceinline__ void process_item_gqa() {
 
         if (live) {
             const uint32_t last = r1 - 1; // only used when the window holds a pool token
-            // K rows: tokens tb+j and tb+16+j, chunk (step*4 + q) -> kA[half*4 + step]; V: chunk j of the
-            // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token and
-            // masked in the scores.  All ten page lookups are issued before the first is used.
+            // Window-relative byte offsets fit 32 bits (a window spans at most kTabWindow pages of at most 1 MiB).
+            const uint32_t c0 = (uint32_t)(((uint64_t)w0 * T + row0) - (s_lo << lg));
+            const uint32_t T32 = (uint32_t)T, mask32 = (uint32_t)page_mask;
             auto row_ptr = [&](uint32_t t) -> const unsigned char * { // head-row of (token t, this kv head)
-                const uint64_t off = (uint64_t)t * T + row0;
-                const int32_t pg = tab[(uint32_t)((off >> lg) - s_lo)];
-                return a.pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask);
+                const uint32_t off = (t - w0) * T32 + c0;
+                const int32_t pg = tab[off >> lg];
+                return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
             };
             // K rows: tokens tb+j and tb+16+j, chunk (step*4 + q) -> kA[half*4 + step]; V: chunk j of the
-            // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token and masked
-            // in the scores.
+            // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token (and
+            // masked in the scores of the range's last tile).
             auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
-            auto load_tile = [&](uint32_t tb, u32x4 (&kA)[8], u32x4 (&vr)[8]) {
+            auto load_k = [&](uint32_t tb, u32x4 (&kA)[8]) {
                 const unsigned char *p0 = row_ptr(min(tb + j, last)) + q * 16;
                 const unsigned char *p1 = row_ptr(min(tb + 16 + j, last)) + q * 16;
 #pragma unroll
@@ -679,27 +688,41 @@ __device__ __forceinline__ void process_item_gqa() {
                     kA[st] = ld_kv4(p0 + st * 64);
                     kA[4 + st] = ld_kv4(p1 + st * 64);
                 }
+            };
+            auto load_v = [&](uint32_t tb, u32x4 (&vr)[8]) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     vr[e] = ld_kv4(row_ptr(min(tau(tb, e), last)) + 2 * D + j * 16);
             };
-            auto compute_tile = [&](uint32_t tb, uint32_t t_lim, const u32x4 (&kA)[8], const u32x4 (&vr)[8]) {
-                f32x4_t s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f}, s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            // raw scores q . K of the tile: s0 = tokens tb + 4q + r, s1 = tokens tb + 16 + 4q + r
+            auto scores = [&](const u32x4 (&kA)[8], f32x4_t &s0, f32x4_t &s1) {
+                s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
                     s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[st], s0, 0, 0, 0);
                     s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[4 + st]), qB[st], s1, 0, 0, 0);
                 }
-                float sc[8];
+            };
+            // Online softmax of the tile's scores and O^T += V^T P^T.  MASKED: only tokens below t_lim
+            // count (the range's last tile, the new token's tile); the tile's first token always counts,
+            // so the tile's maximum is finite.  Scores are scaled before the maximum is taken, so that
+            // the largest one gets the weight 1 exactly (a one-token context returns that token's V).
+            auto softmax_pv = [&](uint32_t tb, uint32_t t_lim, const f32x4_t &s0, const f32x4_t &s1,
+                                  const u32x4 (&vr)[8], auto masked) {
+                constexpr bool MASKED = decltype(masked)::value;
+                float sr[8];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    sc[r] = (tb + 4 * q + r < t_lim) ? s0[r] * c.scale_log2e : -INFINITY;
-                    sc[4 + r] = (tb + 16 + 4 * q + r < t_lim) ? s1[r] * c.scale_log2e : -INFINITY;
+                    sr[r] = s0[r] * c.scale_log2e;
+                    sr[4 + r] = s1[r] * c.scale_log2e;
+                    if (MASKED) {
+                        sr[r] = (tb + 4 * q + r < t_lim) ? sr[r] : -INFINITY;
+                        sr[4 + r] = (tb + 16 + 4 * q + r < t_lim) ? sr[4 + r] : -INFINITY;
+                    }
                 }
-                float mt = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
-                                 fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-                mt = fmaxf(mt, __shfl_xor(mt, 16));
-                mt = fmaxf(mt, __shfl_xor(mt, 32)); // the tile's first token is always valid: mt is finite
+                const float mt = max_over_kblocks(fmaxf(fmaxf(fmaxf(sr[0], sr[1]), fmaxf(sr[2], sr[3])),
+                                                        fmaxf(fmaxf(sr[4], sr[5]), fmaxf(sr[6], sr[7]))));
                 const float mn = fmaxf(m, mt);
                 const float alpha = fast_exp2(m - mn);
                 m = mn;
@@ -709,13 +732,13 @@ __device__ __forceinline__ void process_item_gqa() {
                 float psum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; e += 2) {
-                    const float p0 = fast_exp2(sc[e] - mn), p1 = fast_exp2(sc[e + 1] - mn);
+                    const float p0 = fast_exp2(sr[e] - mn), p1 = fast_exp2(sr[e + 1] - mn);
                     psum += p0 + p1;
                     const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
-                    const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);
-                    const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+                    const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
+                    const float x1 = p1 - __uint_as_float(u1 & 0xffff0000u);
                     ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
-                    pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+                    pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
                 }
                 l = fmaf(l, alpha, psum);
                 if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
@@ -751,12 +774,30 @@ __device__ __forceinline__ void process_item_gqa() {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     vr[e] = nV;
-                compute_tile(it.t1 - 1, it.t1, kA, vr);
+                f32x4_t s0, s1;
+                scores(kA, s0, s1);
+                softmax_pv(it.t1 - 1, it.t1, s0, s1, vr, std::true_type{});
             }
-            for (uint32_t tb = w0; tb < r1; tb += 32) {
+            if (w0 < r1) {
+                // The K registers of a tile are free once its scores are taken, the V registers once the
+                // second product has read them: the next tile's K loads are issued right after the
+                // first, its V loads right after the second, so one of the two is always in flight
+                // behind the arithmetic without a second set of registers.  All tiles but the last are
+                // whole, so only the last one takes the masked path.
                 u32x4 kA[8], vr[8];
-                load_tile(tb, kA, vr);
-                compute_tile(tb, r1, kA, vr);
+                load_k(w0, kA);
+                load_v(w0, vr);
+                uint32_t tb = w0;
+                for (; tb + 32 < r1; tb += 32) {
+                    f32x4_t s0, s1;
+                    scores(kA, s0, s1);
+                    load_k(tb + 32, kA);
+                    softmax_pv(tb, r1, s0, s1, vr, std::false_type{});
+                    load_v(tb + 32, vr);
+                }
+                f32x4_t s0, s1;
+                scores(kA, s0, s1);
+                softmax_pv(tb, r1, s0, s1, vr, std::true_type{});
             }
         }
         w0 = w1;
@@ -863,7 +904,10 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     constexpr uint32_t kVOff = 32 * KB, kTileBytes = 2 * kVOff;
     __shared__ PrefillRec s_rec;
     __shared__ ClassRec s_cls;
-    __shared__ __align__(16) unsigned char s_kv[2 * kTileBytes];
+    // Two staged tiles, one array each: with distinct arrays the compiler can tell that reading one tile
+    // does not depend on the global-to-LDS loads that fill the other, and lets those loads stay in flight.
+    __shared__ __align__(16) unsigned char s_kv0[kTileBytes];
+    __shared__ __align__(16) unsigned char s_kv1[kTileBytes];
     __shared__ __align__(16) uint4 s_q[NB * KSTEPS * NT]; // each lane's own q operands (parked here, not in registers)
     __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
                                              // a workgroup sets how many of them fit a CU)
@@ -958,12 +1002,12 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             // Tile staging: each wave fetches RPI KI of the tile's 32 head-rows (K | V), RPI rows per pair of
             // global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in the
             // scores).
-            auto issue = [&](uint32_t tb, uint32_t buf) {
+            auto issue = [&](uint32_t tb, unsigned char *tile) {
 #pragma unroll
                 for (uint32_t x = 0; x < KI; ++x) {
                     const uint32_t tok = ld_tok + RPI * x;
                     const unsigned char *rp = row_ptr(min(tb + tok, last));
-                    unsigned char *dst = s_kv + buf * kTileBytes + (KI * wave + x) * 1024;
+                    unsigned char *dst = tile + (KI * wave + x) * 1024;
                     __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + ((ld_pos ^ (tok % PIECES)) * 16)), (lds_ptr_t)dst,
                                                      16, 0, 0);
                     __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + KB + ld_pos * 16), (lds_ptr_t)(dst + kVOff), 16,
@@ -1097,16 +1141,12 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     }
                 }
             };
-            issue(w0, 0);
-            __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tile is in LDS
-            __syncthreads();
-            uint32_t cur = 0;
-            for (uint32_t tb = w0; tb < w1; tb += 32) { // workgroup-uniform
-                const bool more = tb + 32 < w1;
-                if (more)
-                    issue(tb + 32, cur ^ 1); // lands in the other tile while this one is computed
+            // One tile: start the loads of the next one into the other array, compute this one, then wait
+            // for this wave's share of the next and meet the other waves.  Workgroup-uniform control flow.
+            auto tile = [&](uint32_t tb, const unsigned char *kv, unsigned char *kv_next) {
+                if (tb + 32 < w1)
+                    issue(tb + 32, kv_next); // lands in the other tile while this one is computed
                 if (tb < r1) {
-                    const unsigned char *kv = s_kv + cur * kTileBytes;
                     // wave-uniform: all 32 tokens lie in the window and at or before the wave's first row,
                     // and every column of the wave is a valid row
                     if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full)
@@ -1116,7 +1156,14 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 }
                 __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the next tile is in LDS
                 __syncthreads(); // the next tile is complete; the one just read may be overwritten
-                cur ^= 1;
+            };
+            issue(w0, s_kv0);
+            __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tile is in LDS
+            __syncthreads();
+            for (uint32_t tb = w0; tb < w1; tb += 64) { // workgroup-uniform; tiles alternate between the arrays
+                tile(tb, s_kv0, s_kv1);
+                if (tb + 32 < w1)
+                    tile(tb + 32, s_kv1, s_kv0);
             }
         }
         w0 = w1;

@@ -99,8 +99,9 @@ int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out) {
         return fail(UKV_EINVAL, "null argument");
     *out = nullptr;
     const uint32_t P = desc->page_bytes;
-    if (P < 1024 || (P & (P - 1)) != 0)
-        return fail(UKV_EINVAL, "page_bytes must be a power of two >= 1024");
+    // Upper bound: the kernels address a page-table window (at most 2048 pages) with 32-bit offsets.
+    if (P < 1024 || P > (1u << 20) || (P & (P - 1)) != 0)
+        return fail(UKV_EINVAL, "page_bytes must be a power of two in [1 KiB, 1 MiB]");
     if (!desc->base || ((uintptr_t)desc->base % P) != 0)
         return fail(UKV_EINVAL, "pool base must be non-null and page_bytes-aligned");
     if (desc->bytes / P == 0 || desc->bytes / P > 0x7fffffffull)

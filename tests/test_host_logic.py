@@ -49,6 +49,7 @@ def test_pool_info_matches_the_paper_closed_form():
 @pytest.mark.parametrize("kwargs,services", [
     (dict(page_bytes=1000), [SHAPES["7b"]]),
     (dict(page_bytes=512), [SHAPES["tiny"]]),
+    (dict(page_bytes=2 << 20, n_pages=8), [SHAPES["7b"]]),   # above the 1 MiB page limit
     (dict(base=FAKE_BASE + 64), [SHAPES["7b"]]),
     (dict(), [Service(32, 32, 96)]),            # unsupported head_dim
     (dict(), [Service(30, 4, 128)]),            # q heads not a multiple of kv heads
