@@ -901,13 +901,13 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     constexpr uint32_t RPI = 1024 / KB;     // head-rows one staging instruction (1 KiB) covers
     constexpr uint32_t KI = 32 / RPI / NW;  // staging instructions per wave, tile and part (K, V)
     static_assert(KI >= 1, "too many waves for this head_dim");
-    constexpr uint32_t kVOff = 32 * KB, kTileBytes = 2 * kVOff;
+    constexpr uint32_t kPartBytes = 32 * KB; // the K rows (or the V rows) of a 32-token tile
     __shared__ PrefillRec s_rec;
     __shared__ ClassRec s_cls;
     // Two staged tiles, one array each: with distinct arrays the compiler can tell that reading one tile
     // does not depend on the global-to-LDS loads that fill the other, and lets those loads stay in flight.
-    __shared__ __align__(16) unsigned char s_kv0[kTileBytes];
-    __shared__ __align__(16) unsigned char s_kv1[kTileBytes];
+    __shared__ __align__(16) unsigned char s_k0[kPartBytes], s_k1[kPartBytes];
+    __shared__ __align__(16) unsigned char s_v0[kPartBytes], s_v1[kPartBytes];
     __shared__ __align__(16) uint4 s_q[NB * KSTEPS * NT]; // each lane's own q operands (parked here, not in registers)
     __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
                                              // a workgroup sets how many of them fit a CU)
@@ -933,6 +933,27 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     const uint64_t page_mask = (1ull << lg) - 1;
     // this lane's share of a staged tile: piece position lane % PIECES of tokens RPI (KI wave + x) + lane / PIECES
     const uint32_t ld_tok = RPI * KI * wave + lane / PIECES, ld_pos = lane % PIECES;
+    // V rows keep their 16-byte pieces at piece ^ vswz(token), which spreads the 32-byte stretches that one
+    // transposing read takes from 8 different rows over all banks.  Such a read hands lane i of a group of
+    // 16 the element i%4 of what the lanes 4x + i/4 (x = 0..3) of the group addressed: with lane s pointing
+    // at elements 16 mm + 4 (s%4) .. +3 of token 4q + s/4, lane i receives V[4q + x][16 mm + i], x = 0..3.
+    auto vswz = [](uint32_t tok) { return 2 * ((tok / (256 / KB)) % (KB / 32)); };
+    uint32_t voff[MM]; // this lane's read offsets into a staged V tile, one per group of 16 output rows
+    {
+        const uint32_t tok = 4 * q + j / 4, h = j % 4;
+#pragma unroll
+        for (int mm = 0; mm < MM; ++mm)
+            voff[mm] = tok * KB + (((2 * mm + h / 2) ^ vswz(tok)) * 16) + (h % 2) * 8;
+    }
+    auto vt_operand = [&](const unsigned char *p) { // tokens tau(q, 0..3) from p, tau(q, 4..7) 16 rows further
+        typedef __attribute__((address_space(3))) s16x4_t *lds_s16x4_ptr;
+        struct {
+            s16x4_t lo, hi;
+        } w;
+        w.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+        w.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 16 * KB));
+        return __builtin_bit_cast(bf16x8_t, w);
+    };
     const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
     const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
     const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
@@ -941,7 +962,8 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     uint32_t col_pos[NB];
     bool col_ok[NB];
     f32x4_t oacc[NB][MM];
-    float m[NB], l[NB];
+    float m[NB];
+    f32x4_t lacc[NB]; // running sums of the weights, every element the same (see pv)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const uint32_t row = row_w + b * rpb + j / G;
@@ -960,7 +982,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         for (int mm = 0; mm < MM; ++mm)
             oacc[b][mm] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         m[b] = kMinusBig;
-        l[b] = 0.f;
+        lacc[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     }
     // tokens this wave / this workgroup has to look at: up to the position of the last valid row
     auto hi_of = [&](uint32_t first_row, uint32_t n_rows) -> uint32_t {
@@ -999,31 +1021,39 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 const int32_t pg = tab[off >> lg];
                 return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
             };
-            // Tile staging: each wave fetches RPI KI of the tile's 32 head-rows (K | V), RPI rows per pair of
-            // global-to-LDS loads.  Tokens past the window's end are copies of its last token (masked in the
-            // scores).
-            auto issue = [&](uint32_t tb, unsigned char *tile) {
+            // Tile staging: each wave fetches RPI KI of the tile's 32 K rows (or V rows), RPI rows per
+            // global-to-LDS load.  Tokens past the window's end are copies of its last token (masked in the
+            // scores).  A tile's K is requested one step before its V, so the row addresses are worked out
+            // once, for K, and kept for V.
+            struct RowPtrs {
+                const unsigned char *p[KI];
+            };
+            auto rows_of = [&](uint32_t tb) {
+                RowPtrs r;
+#pragma unroll
+                for (uint32_t x = 0; x < KI; ++x)
+                    r.p[x] = row_ptr(min(tb + ld_tok + RPI * x, last));
+                return r;
+            };
+            auto issue_k = [&](const RowPtrs &r, unsigned char *kt) {
 #pragma unroll
                 for (uint32_t x = 0; x < KI; ++x) {
                     const uint32_t tok = ld_tok + RPI * x;
-                    const unsigned char *rp = row_ptr(min(tb + tok, last));
-                    unsigned char *dst = tile + (KI * wave + x) * 1024;
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + ((ld_pos ^ (tok % PIECES)) * 16)), (lds_ptr_t)dst,
-                                                     16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(rp + KB + ld_pos * 16), (lds_ptr_t)(dst + kVOff), 16,
-                                                     0, 0);
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x] + ((ld_pos ^ (tok % PIECES)) * 16)),
+                                                     (lds_ptr_t)(kt + (KI * wave + x) * 1024), 16, 0, 0);
                 }
             };
+            auto issue_v = [&](const RowPtrs &r, unsigned char *vt) {
+#pragma unroll
+                for (uint32_t x = 0; x < KI; ++x)
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x] + KB + (ld_pos ^ vswz(ld_tok + RPI * x)) * 16),
+                                                     (lds_ptr_t)(vt + (KI * wave + x) * 1024), 16, 0, 0);
+            };
             auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
-            // One tile against all NB blocks of the wave, stage by stage over the blocks, so that the
-            // blocks' independent instruction chains can overlap.  MASKED: the tile reaches past some
-            // column's position (or past the window); otherwise every score counts and the compares are
-            // skipped.  A block that lies wholly before the tile just sees every score masked.
-            auto tile_step = [&](uint32_t tb, const unsigned char *kv, auto masked) {
-                constexpr bool MASKED = decltype(masked)::value;
+            // Raw scores S^T = K Q^T of one staged K tile against all NB blocks of the wave.
+            auto scores = [&](const unsigned char *kt, f32x4_t (&s0)[NB], f32x4_t (&s1)[NB]) {
                 uint32_t tq = tid; // opaque per tile: keeps the q reads below inside the loop (out of registers)
                 asm volatile("" : "+v"(tq));
-                f32x4_t s0[NB], s1[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     s0[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
@@ -1032,8 +1062,8 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
 #pragma unroll
                 for (int st = 0; st < KSTEPS; ++st) { // K rows of tokens j and 16+j, pieces st*4+q
                     const uint32_t pc = ((st * 4 + q) ^ (j % PIECES)) * 16; // (16 + j) % PIECES == j % PIECES
-                    const u32x4 k0 = *reinterpret_cast<const u32x4 *>(kv + j * KB + pc);
-                    const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kv + (16 + j) * KB + pc);
+                    const u32x4 k0 = *reinterpret_cast<const u32x4 *>(kt + j * KB + pc);
+                    const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kt + (16 + j) * KB + pc);
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
                         const bf16x8_t qb = as_bf16x8(s_q[(b * KSTEPS + st) * NT + tq]);
@@ -1041,37 +1071,41 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                         s1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1), qb, s1[b], 0, 0, 0);
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                float sc[NB][8], mt[NB];
+            };
+            // Online softmax of the tile at tb from its raw scores, stage by stage over the blocks, so
+            // that the blocks' independent instruction chains can overlap.  MASKED: the tile reaches past
+            // some column's position (or past the window); otherwise every score counts and the compares
+            // are skipped.  A block that lies wholly before the tile just sees every score masked.
+            // Returns whether some accumulator has to be rescaled by alpha before the tile is added.
+            auto softmax = [&](uint32_t tb, const f32x4_t (&s0)[NB], const f32x4_t (&s1)[NB], bf16x8_t (&Ph)[NB],
+                               bf16x8_t (&Pl)[NB], float (&alpha)[NB], auto masked) -> bool {
+                constexpr bool MASKED = decltype(masked)::value;
+                // Raw scores; the scale (times log2 e, positive) is applied to the maximum and folded into
+                // the multiply-add under the exponential.
+                float sr[NB][8], mt[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        sr[b][r] = s0[b][r];
+                        sr[b][4 + r] = s1[b][r];
+                    }
                     if (MASKED) {
                         // causal mask: token t counts for this column if t <= its position (and lies in
                         // this window: tokens past it were loaded as copies of the window's last token)
                         const uint32_t t_lim = col_ok[b] ? min(col_pos[b] + 1, r1) : 0;
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            sc[b][r] = (tb + 4 * q + r < t_lim) ? s0[b][r] * scale_log2e : -INFINITY;
-                            sc[b][4 + r] = (tb + 16 + 4 * q + r < t_lim) ? s1[b][r] * scale_log2e : -INFINITY;
-                        }
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            sc[b][r] = s0[b][r] * scale_log2e;
-                            sc[b][4 + r] = s1[b][r] * scale_log2e;
+                            sr[b][r] = (tb + 4 * q + r < t_lim) ? sr[b][r] : -INFINITY;
+                            sr[b][4 + r] = (tb + 16 + 4 * q + r < t_lim) ? sr[b][4 + r] : -INFINITY;
                         }
                     }
-                    mt[b] = fmaxf(fmaxf(fmaxf(sc[b][0], sc[b][1]), fmaxf(sc[b][2], sc[b][3])),
-                                  fmaxf(fmaxf(sc[b][4], sc[b][5]), fmaxf(sc[b][6], sc[b][7])));
+                    mt[b] = fmaxf(fmaxf(fmaxf(sr[b][0], sr[b][1]), fmaxf(sr[b][2], sr[b][3])),
+                                  fmaxf(fmaxf(sr[b][4], sr[b][5]), fmaxf(sr[b][6], sr[b][7])));
                 }
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
-                    mt[b] = fmaxf(mt[b], __shfl_xor(mt[b], 16));
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    mt[b] = fmaxf(mt[b], __shfl_xor(mt[b], 32));
-                float alpha[NB];
-                bf16x8_t Ph[NB], Pl[NB];
+                    mt[b] = max_over_kblocks(mt[b]) * scale_log2e;
                 bool rescale = false;
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
@@ -1084,56 +1118,37 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     m[b] = mn;
                     // P as two bf16 parts by truncation (see process_item_gqa)
                     uint32_t ph[4], pl[4];
-                    float psum = 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
-                        const float p0 = fast_exp2(sc[b][e] - mn), p1 = fast_exp2(sc[b][e + 1] - mn);
-                        psum += p0 + p1;
+                        const float p0 = fast_exp2(fmaf(sr[b][e], scale_log2e, -mn));
+                        const float p1 = fast_exp2(fmaf(sr[b][e + 1], scale_log2e, -mn));
                         const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
                         const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
                         const float x1 = p1 - __uint_as_float(u1 & 0xffff0000u);
                         ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
                         pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
                     }
-                    l[b] = fmaf(l[b], alpha[b], psum);
                     Ph[b] = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
                     Pl[b] = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
                 }
-                if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
+                return __builtin_amdgcn_ballot_w64(rescale) != 0;
+            };
+            // O^T += V^T P^T for one staged V tile: rows of the 8 tokens tau(q, .), piece j, transposed one
+            // output row group at a time and multiplied into every block.
+            // The weights' running sums ride along as one more product with an all-ones left operand: every row
+            // of its result is the column sum of the (two-part) weights, over all four k-blocks at once.
+            auto pv = [&](const unsigned char *vt, const bf16x8_t (&Ph)[NB], const bf16x8_t (&Pl)[NB]) {
+                const bf16x8_t ones = as_bf16x8(make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u));
 #pragma unroll
-                    for (int b = 0; b < NB; ++b)
-#pragma unroll
-                        for (int mm = 0; mm < MM; ++mm)
-                            oacc[b][mm] *= alpha[b];
+                for (int b = 0; b < NB; ++b) {
+                    lacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, Ph[b], lacc[b], 0, 0, 0);
+                    lacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, Pl[b], lacc[b], 0, 0, 0);
                 }
-                // V from LDS (rows of the 8 tokens tau(q, .), piece j), transposed one output row group at
-                // a time and multiplied into every block.  The scheduling barrier keeps these 32 registers
-                // from being loaded before the scores are done with theirs.
-                __builtin_amdgcn_sched_barrier(0);
-                // lane (j, q): MM consecutive elements (d = MM j ...) of the rows of its 8 tokens
-                uint32_t vr[8][MM / 2];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const unsigned char *vp = kv + kVOff + tau(0, e) * KB + j * (2 * MM);
-                    if (MM == 8) {
-                        const u32x4 w = *reinterpret_cast<const u32x4 *>(vp);
-#pragma unroll
-                        for (int c = 0; c < MM / 2; ++c)
-                            vr[e][c] = w[c];
-                    } else {
-                        const uint2 w = *reinterpret_cast<const uint2 *>(vp);
-                        vr[e][0] = w.x;
-                        vr[e][1] = w.y;
-                    }
-                }
+                // Left operand of the product for output rows d = 16 mm + i (lane i of 16): V[token][d] for the
+                // lane's 8 tokens tau(q, .), fetched by two transposing LDS reads (tokens 4q.. and 16+4q..).
 #pragma unroll
                 for (int mm = 0; mm < MM; ++mm) {
-                    const uint32_t sel = (mm & 1) ? 0x07060302u : 0x05040100u;
-                    uint32_t vt[4];
-#pragma unroll
-                    for (int pr = 0; pr < 4; ++pr)
-                        vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][mm / 2], vr[2 * pr][mm / 2], sel);
-                    const bf16x8_t Vt = as_bf16x8(make_uint4(vt[0], vt[1], vt[2], vt[3]));
+                    const bf16x8_t Vt = vt_operand(vt + voff[mm]);
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
                         oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Ph[b], oacc[b][mm], 0, 0, 0);
@@ -1141,51 +1156,112 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     }
                 }
             };
-            // One tile: start the loads of the next one into the other array, compute this one, then wait
-            // for this wave's share of the next and meet the other waves.  Workgroup-uniform control flow.
-            auto tile = [&](uint32_t tb, const unsigned char *kv, unsigned char *kv_next) {
+            // Scheduling request for the block that holds one tile's score products and another tile's
+            // softmax: the operand reads of the first k-step, then one matrix instruction at a time with a
+            // share of the vector instructions (and the next k-step's operand reads) behind it, so that the
+            // vector units work while the matrix core does.
+            auto interleave_phase1 = [&]() {
+#ifndef UKV_PF_SGB
+#define UKV_PF_SGB 8
+#endif
+                constexpr int kVectorPerMatrix = UKV_PF_SGB; // vector (and transcendental) instructions per product
+                if (kVectorPerMatrix == 0)
+                    return;
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 + NB, 0); // LDS reads
+#pragma unroll
+                for (int i = 0; i < 2 * NB * KSTEPS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // matrix
+                    __builtin_amdgcn_sched_group_barrier(0x402, kVectorPerMatrix, 0);   // vector, transcendental
+                    if (i % (2 * NB) == 0 && i / (2 * NB) + 1 < KSTEPS)
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2 + NB, 0);         // LDS reads of the next k-step
+                }
+            };
+            RowPtrs rows; // row addresses of the tile whose K was requested last
+            // One step of the pipeline over the window's tiles.  On entry the raw scores of the tile at tb
+            // are in s_cur, K of the next tile is in k_next and V of this tile in v_cur.  The step starts
+            // the loads of K two tiles ahead (into the array this tile's K has left) and of the next V,
+            // then takes the next tile's scores on the matrix cores while the vector units do this tile's
+            // softmax -- the two are independent, which is the point of the arrangement -- and finally
+            // adds this tile's V^T P^T.  Control flow is workgroup-uniform up to the barrier; a wave past
+            // its own rows (tb >= r1) only loads and waits.
+            auto step = [&](uint32_t tb, const unsigned char *k_next, const unsigned char *v_cur, unsigned char *k_fill,
+                            unsigned char *v_fill, const f32x4_t (&c0s)[NB], const f32x4_t (&c1s)[NB],
+                            f32x4_t (&n0s)[NB], f32x4_t (&n1s)[NB]) {
                 if (tb + 32 < w1)
-                    issue(tb + 32, kv_next); // lands in the other tile while this one is computed
+                    issue_v(rows, v_fill); // rows: those of the tile at tb + 32, from the previous step
+                if (tb + 64 < w1) {
+                    rows = rows_of(tb + 64);
+                    issue_k(rows, k_fill);
+                }
                 if (tb < r1) {
+                    bf16x8_t Ph[NB], Pl[NB];
+                    float alpha[NB];
+                    bool rescale;
+                    // The next tile's scores are taken whether or not this wave (or the window) has a next
+                    // tile: without one they are computed from stale LDS contents and never used.
+                    // (Inside either branch, so that the two share a basic block and get interleaved.)
                     // wave-uniform: all 32 tokens lie in the window and at or before the wave's first row,
                     // and every column of the wave is a valid row
-                    if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full)
-                        tile_step(tb, kv, std::false_type{});
-                    else
-                        tile_step(tb, kv, std::true_type{});
+                    if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full) {
+                        scores(k_next, n0s, n1s);
+                        rescale = softmax(tb, c0s, c1s, Ph, Pl, alpha, std::false_type{});
+                        interleave_phase1();
+                    } else {
+                        scores(k_next, n0s, n1s);
+                        rescale = softmax(tb, c0s, c1s, Ph, Pl, alpha, std::true_type{});
+                        interleave_phase1();
+                    }
+                    if (rescale) {
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) {
+                            lacc[b] *= alpha[b];
+#pragma unroll
+                            for (int mm = 0; mm < MM; ++mm)
+                                oacc[b][mm] *= alpha[b];
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0); // keeps the V registers from being loaded before the scores are done with theirs
+                    pv(v_cur, Ph, Pl);
                 }
-                __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the next tile is in LDS
-                __syncthreads(); // the next tile is complete; the one just read may be overwritten
+                __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tiles just requested is in LDS
+                __syncthreads(); // they are complete; the arrays just read may be overwritten
             };
-            issue(w0, s_kv0);
-            __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tile is in LDS
-            __syncthreads();
+            f32x4_t sa0[NB], sa1[NB], sb0[NB], sb1[NB];
+            rows = rows_of(w0);
+            issue_k(rows, s_k0);
+            issue_v(rows, s_v0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads(); // the first tile is staged
+            if (w0 + 32 < w1) {
+                rows = rows_of(w0 + 32);
+                issue_k(rows, s_k1);
+            }
+            if (w0 < r1)
+                scores(s_k0, sa0, sa1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads(); // K of the second tile is staged; every wave is done with the first tile's K
             for (uint32_t tb = w0; tb < w1; tb += 64) { // workgroup-uniform; tiles alternate between the arrays
-                tile(tb, s_kv0, s_kv1);
+                step(tb, s_k1, s_v0, s_k0, s_v1, sa0, sa1, sb0, sb1);
                 if (tb + 32 < w1)
-                    tile(tb + 32, s_kv1, s_kv0);
+                    step(tb + 32, s_k0, s_v1, s_k1, s_v0, sb0, sb1, sa0, sa1);
             }
         }
         w0 = w1;
     }
 
-    // lane (j, q) holds O[column j][d = MM (4q + r) + mm] in oacc[b][mm][r]; l is a per-lane partial sum
+    // lane (j, q) holds O[column j][d = 16 mm + 4q + r] in oacc[b][mm][r] and the column's sum of weights in lacc[b]
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        float lb = l[b];
-        lb += __shfl_xor(lb, 16);
-        lb += __shfl_xor(lb, 32);
+        const float lb = lacc[b][0];
         if (!col_ok[b])
             continue;
         const float inv = lb > 0.f ? 1.f / lb : 0.f;
         const uint32_t row = col_pos[b] - pos0;
-        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 4 * MM * q;
+        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 4 * q;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int c = 0; c < MM; c += 4)
-                st_g16(dst + MM * r + c, oacc[b][c][r] * inv, oacc[b][c + 1][r] * inv, oacc[b][c + 2][r] * inv,
-                       oacc[b][c + 3][r] * inv);
+        for (int mm = 0; mm < MM; ++mm)
+            st_g16(dst + 16 * mm, oacc[b][mm][0] * inv, oacc[b][mm][1] * inv, oacc[b][mm][2] * inv,
+                   oacc[b][mm][3] * inv);
     }
 }
 
