@@ -1076,9 +1076,9 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             // that the blocks' independent instruction chains can overlap.  MASKED: the tile reaches past
             // some column's position (or past the window); otherwise every score counts and the compares
             // are skipped.  A block that lies wholly before the tile just sees every score masked.
-            // Returns whether some accumulator has to be rescaled by alpha before the tile is added.
+            // Returns whether some accumulator has to be rescaled before the tile is added: by 2^(-grow[b]).
             auto softmax = [&](uint32_t tb, const f32x4_t (&s0)[NB], const f32x4_t (&s1)[NB], bf16x8_t (&Ph)[NB],
-                               bf16x8_t (&Pl)[NB], float (&alpha)[NB], auto masked) -> bool {
+                               bf16x8_t (&Pl)[NB], float (&grow)[NB], auto masked) -> bool {
                 constexpr bool MASKED = decltype(masked)::value;
                 // Raw scores; the scale (times log2 e, positive) is applied to the maximum and folded into
                 // the multiply-add under the exponential.
@@ -1113,8 +1113,8 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     // more than 2^kLazy: weights then stay below 2^kLazy, and the accumulators are rescaled
                     // rarely.
                     const float mn = mt[b] > m[b] + kLazy ? mt[b] : m[b]; // finite: m starts at kMinusBig
-                    alpha[b] = fast_exp2(m[b] - mn);
-                    rescale |= alpha[b] != 1.f;
+                    grow[b] = mn - m[b]; // how far the reference point moved: 0 almost always
+                    rescale |= grow[b] != 0.f;
                     m[b] = mn;
                     // P as two bf16 parts by truncation (see process_item_gqa)
                     uint32_t ph[4], pl[4];
@@ -1156,26 +1156,6 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     }
                 }
             };
-            // Scheduling request for the block that holds one tile's score products and another tile's
-            // softmax: the operand reads of the first k-step, then one matrix instruction at a time with a
-            // share of the vector instructions (and the next k-step's operand reads) behind it, so that the
-            // vector units work while the matrix core does.
-            auto interleave_phase1 = [&]() {
-#ifndef UKV_PF_SGB
-#define UKV_PF_SGB 8
-#endif
-                constexpr int kVectorPerMatrix = UKV_PF_SGB; // vector (and transcendental) instructions per product
-                if (kVectorPerMatrix == 0)
-                    return;
-                __builtin_amdgcn_sched_group_barrier(0x100, 2 + NB, 0); // LDS reads
-#pragma unroll
-                for (int i = 0; i < 2 * NB * KSTEPS; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // matrix
-                    __builtin_amdgcn_sched_group_barrier(0x402, kVectorPerMatrix, 0);   // vector, transcendental
-                    if (i % (2 * NB) == 0 && i / (2 * NB) + 1 < KSTEPS)
-                        __builtin_amdgcn_sched_group_barrier(0x100, 2 + NB, 0);         // LDS reads of the next k-step
-                }
-            };
             RowPtrs rows; // row addresses of the tile whose K was requested last
             // One step of the pipeline over the window's tiles.  On entry the raw scores of the tile at tb
             // are in s_cur, K of the next tile is in k_next and V of this tile in v_cur.  The step starts
@@ -1195,7 +1175,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 }
                 if (tb < r1) {
                     bf16x8_t Ph[NB], Pl[NB];
-                    float alpha[NB];
+                    float grow[NB];
                     bool rescale;
                     // The next tile's scores are taken whether or not this wave (or the window) has a next
                     // tile: without one they are computed from stale LDS contents and never used.
@@ -1204,20 +1184,19 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     // and every column of the wave is a valid row
                     if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full) {
                         scores(k_next, n0s, n1s);
-                        rescale = softmax(tb, c0s, c1s, Ph, Pl, alpha, std::false_type{});
-                        interleave_phase1();
+                        rescale = softmax(tb, c0s, c1s, Ph, Pl, grow, std::false_type{});
                     } else {
                         scores(k_next, n0s, n1s);
-                        rescale = softmax(tb, c0s, c1s, Ph, Pl, alpha, std::true_type{});
-                        interleave_phase1();
+                        rescale = softmax(tb, c0s, c1s, Ph, Pl, grow, std::true_type{});
                     }
                     if (rescale) {
 #pragma unroll
                         for (int b = 0; b < NB; ++b) {
-                            lacc[b] *= alpha[b];
+                            const float alpha = fast_exp2(-grow[b]);
+                            lacc[b] *= alpha;
 #pragma unroll
                             for (int mm = 0; mm < MM; ++mm)
-                                oacc[b][mm] *= alpha[b];
+                                oacc[b][mm] *= alpha;
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0); // keeps the V registers from being loaded before the scores are done with theirs
