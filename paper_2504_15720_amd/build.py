@@ -12,7 +12,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libukv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_sched.cpp", "ukv_kernels.hip"]
+SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_sched.cpp", "ukv_decode.hip", "ukv_prefill.hip",
+           "ukv_copy.hip"]
 # packed fp32 VALU forms are switched off for device code on this target
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
@@ -43,7 +44,7 @@ def build_library(verbose: bool = False) -> str:
             print(out, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -1,11 +1,6 @@
-// HIP kernels of the unified-KV decode path for gfx950 (CDNA4, wave64).
-//
-//   decode_kernel : split-KV decode attention over a mixed-service batch, one launch.
-//   reduce_kernel : merges the partial (max, sum, accumulator) triples of cut sequences.
-//   append_kernel : scatters each request's new K/V token into its pages (store side) and
-//                   writes the call's new page-table entries.
-//   patch_kernel  : page-table entries alone (used when a token spans more than four pages).
-//   copy_tokens_kernel : paged <-> contiguous copy of whole requests (gather / scatter).
+// Decode attention over the unified pool: decode_kernel (split-KV decode over a mixed-service batch in
+// one launch, fused merge of split partials, fused append) and reduce_kernel (the merge as a second
+// launch).
 //
 // Decode is bound by HBM: every cached K/V byte is read once per step (decode phase, section
 // 2.1; merged blocks are chosen for read locality, section 4.4).  The design therefore keeps
@@ -13,90 +8,11 @@
 // read by d/8 adjacent lanes, 16 bytes each, so one wave instruction covers whole 128-byte
 // lines, and the lanes of a workgroup cover `hs` consecutive heads of `ti` consecutive
 // tokens, i.e. contiguous stretches of the request's byte stream inside 16 KiB pages.
-#include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
-
-#include <type_traits>
-
-#include "ukv_internal.h"
+#include "ukv_device.h"
 
 namespace ukv {
 
 static constexpr int kTabWindow = 2048; // page-table entries staged in LDS at a time
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-__device__ __forceinline__ void unpack8(const uint4 &w, float *f) {
-    f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x);
-    f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
-    f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z);
-    f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
-}
-
-// Sum over the LPR (8 or 16) adjacent lanes that share a row; every lane gets the total.
-template <int LPR>
-__device__ __forceinline__ float row_sum(float x) {
-    x += dpp_f<0xB1>(x);  // quad_perm [1,0,3,2]
-    x += dpp_f<0x4E>(x);  // quad_perm [2,3,0,1]
-    x += dpp_f<0x141>(x); // row_half_mirror
-    if (LPR == 16)
-        x += dpp_f<0x140>(x); // row_mirror
-    return x;
-}
-
-// 128-bit load of K or V payload.  Every KV byte is used exactly once per launch, so the load
-// is marked non-temporal (streaming): it keeps the L2 for page tables, q and partials.
-// Pointers that reach the item functions through LDS have lost their address space; these
-// casts put it back (global memory), so loads are global_load, not flat_load (which would also
-// tie them to the LDS wait counter).
-#define UKV_GLOBAL __attribute__((address_space(1)))
-template <class T>
-__device__ __forceinline__ const UKV_GLOBAL T *as_global(const T *p) {
-    return (const UKV_GLOBAL T *)(p);
-}
-template <class T>
-__device__ __forceinline__ UKV_GLOBAL T *as_global(T *p) {
-    return (UKV_GLOBAL T *)(p);
-}
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4g __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 ld_kv(const uint4 *p) {
-    const u32x4 v = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ u32x4 ld_kv4(const void *p) {
-    return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
-}
-// plain 128-bit global load / store
-__device__ __forceinline__ uint4 ld_g16(const void *p) {
-    const u32x4 v = *as_global(reinterpret_cast<const u32x4 *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void st_g16(float *p, float x, float y, float z, float w) {
-    *as_global(reinterpret_cast<f32x4g *>(p)) = (f32x4g){x, y, z, w};
-}
-__device__ __forceinline__ u32x4 ld_g16v(const void *p) { return *as_global(reinterpret_cast<const u32x4 *>(p)); }
-// 128-bit streaming store (the new token's pieces: written once, read by later launches only)
-__device__ __forceinline__ void st_g16v(void *p, const u32x4 &v) {
-    __builtin_nontemporal_store(v, as_global(reinterpret_cast<u32x4 *>(p)));
-}
-__device__ __forceinline__ void st_g16v(void *p, const uint4 &v) { st_g16v(p, (u32x4){v.x, v.y, v.z, v.w}); }
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Values that are the same in every lane of the workgroup, moved to scalar registers.
-__device__ __forceinline__ uint32_t uni(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
-__device__ __forceinline__ uint64_t uni(uint64_t x) {
-    return ((uint64_t)uni((uint32_t)(x >> 32)) << 32) | uni((uint32_t)x);
-}
-__device__ __forceinline__ float uni(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
 
 // Workgroup state in LDS.  The kernel body only picks items and publishes them in s_ctx; the
 // per-kind item functions take their (workgroup-uniform) inputs from there and move them to
@@ -579,21 +495,6 @@ __device__ __forceinline__ void process_item() {
 // 256-byte rows per 16 lanes) and transposed inside the lane with byte permutes; output row
 // (MFMA m, lane i) is d = 8i + m.  P is split into bf16 high and low parts (two products), so the
 // weights keep 16 mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
-__device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4 &w) { return __builtin_bit_cast(bf16x8_t, w); }
-
-// Maximum over the lanes l, l^16, l^32, l^48 (the four k-blocks of one column), in every one of
-// them: two lane swaps instead of two round trips through the LDS permute path.
-__device__ __forceinline__ float max_over_kblocks(float x) {
-    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1])); // lanes [0,32) and [32,64) exchanged
-    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])); // odd and even rows of 16 exchanged
-}
 
 template <int NT>
 __device__ __forceinline__ void process_item_gqa() {
@@ -866,384 +767,6 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Prefill phase (section 2.1): the queries of a chunk of prompt tokens attend, causally, to the
-// request's cache (their own K/V included; the caller has stored them with the bulk store).
-//
-// Same matrix-core formulation as the grouped-query decode path, with the 16 columns of a product
-// now (query row, query head of the group) pairs: a workgroup of four waves owns kPrefillCols = 128
-// such columns of one (request, kv head), each wave NB = 2 blocks of 16.  A wave walks the tokens
-// 0 .. (last position of its columns) in tiles of 32; the K rows and the transposed V of a tile are
-// loaded once and used for both blocks.  Column j of a block is row r0 + blk*(16/G) + j/G, head
-// j%G; the score of (token t, column) counts if t <= position(column) -- only the last tiles of a
-// block are partly masked, tiles wholly behind a block's rows are skipped.  The running maximum
-// starts at a large finite negative number, so that a column none of whose tokens has been seen yet
-// stays at weight 0 without inf - inf.
-static constexpr float kMinusBig = -1.0e30f;
-static constexpr float kLazy = 6.0f; // log2 of the largest weight tolerated before the reference moves
-// A staged tile in LDS: 32 K rows, then 32 V rows, 2 head_dim bytes each, written by global-to-LDS loads
-// (no registers in between; lane L of a wave instruction fills bytes [16 L, 16 L + 16) of a 1 KiB stretch,
-// from any global address).  A K row keeps its 16-byte pieces at positions piece ^ (token % pieces),
-// so that the operand reads of eight adjacent lanes (one piece of eight rows) fall on different banks;
-// the V reads of eight adjacent lanes are 128 contiguous bytes of one row.  Two tiles: one is read
-// while the next is written.
-static constexpr int kPfTabWindow = 1024;
-typedef __attribute__((address_space(3))) void *lds_ptr_t;
-typedef const __attribute__((address_space(1))) void *global_ptr_t;
-
-template <int NB, int NW, int D>
-__global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
-    constexpr int NT = 64 * NW;             // NW = 4 or 8 waves; D = 128 or 64
-    constexpr uint32_t KB = 2 * D;          // bytes of the K (or V) part of a head-row
-    constexpr uint32_t PIECES = KB / 16;    // 16-byte pieces of it
-    constexpr int KSTEPS = D / 32;          // products of 32 along head_dim for one score tile
-    constexpr int MM = D / 16;              // products of 16 output rows (head_dim elements) for O^T
-    constexpr uint32_t RPI = 1024 / KB;     // head-rows one staging instruction (1 KiB) covers
-    constexpr uint32_t KI = 32 / RPI / NW;  // staging instructions per wave, tile and part (K, V)
-    static_assert(KI >= 1, "too many waves for this head_dim");
-    constexpr uint32_t kPartBytes = 32 * KB; // the K rows (or the V rows) of a 32-token tile
-    __shared__ PrefillRec s_rec;
-    __shared__ ClassRec s_cls;
-    // Two staged tiles, one array each: with distinct arrays the compiler can tell that reading one tile
-    // does not depend on the global-to-LDS loads that fill the other, and lets those loads stay in flight.
-    __shared__ __align__(16) unsigned char s_k0[kPartBytes], s_k1[kPartBytes];
-    __shared__ __align__(16) unsigned char s_v0[kPartBytes], s_v1[kPartBytes];
-    __shared__ __align__(16) uint4 s_q[NB * KSTEPS * NT]; // each lane's own q operands (parked here, not in registers)
-    __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
-                                             // a workgroup sets how many of them fit a CU)
-    if (threadIdx.x == 0) {
-        s_rec = a.recs[blockIdx.x];
-        s_cls = a.classes[s_rec.cls];
-    }
-    __syncthreads();
-    const uint32_t q_len = uni(s_rec.q_len);
-    if (q_len == 0)
-        return; // filler
-    const uint64_t table_off = uni(s_rec.table_off), q_off = uni(s_rec.q_off), out_off = uni(s_rec.out_off);
-    const uint32_t ctx_len = uni(s_rec.ctx_len), kvh = uni(s_rec.kvh), r0 = uni(s_rec.r0);
-    const uint32_t G = uni(s_cls.g), n_q = uni(s_cls.n_q);
-    const uint64_t T = uni(s_cls.token_bytes);
-    const float scale_log2e = uni(s_cls.scale_log2e);
-    int32_t *tab = s_ptab;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const uint32_t wave = uni((uint32_t)(tid >> 6));
-    const uint32_t j = lane & 15, q = lane >> 4;
-    const uint32_t lg = a.log2_page;
-    const uint64_t page_mask = (1ull << lg) - 1;
-    // this lane's share of a staged tile: piece position lane % PIECES of tokens RPI (KI wave + x) + lane / PIECES
-    const uint32_t ld_tok = RPI * KI * wave + lane / PIECES, ld_pos = lane % PIECES;
-    // V rows keep their 16-byte pieces at piece ^ vswz(token), which spreads the 32-byte stretches that one
-    // transposing read takes from 8 different rows over all banks.  Such a read hands lane i of a group of
-    // 16 the element i%4 of what the lanes 4x + i/4 (x = 0..3) of the group addressed: with lane s pointing
-    // at elements 16 mm + 4 (s%4) .. +3 of token 4q + s/4, lane i receives V[4q + x][16 mm + i], x = 0..3.
-    auto vswz = [](uint32_t tok) { return 2 * ((tok / (256 / KB)) % (KB / 32)); };
-    uint32_t voff[MM]; // this lane's read offsets into a staged V tile, one per group of 16 output rows
-    {
-        const uint32_t tok = 4 * q + j / 4, h = j % 4;
-#pragma unroll
-        for (int mm = 0; mm < MM; ++mm)
-            voff[mm] = tok * KB + (((2 * mm + h / 2) ^ vswz(tok)) * 16) + (h % 2) * 8;
-    }
-    auto vt_operand = [&](const unsigned char *p) { // tokens tau(q, 0..3) from p, tau(q, 4..7) 16 rows further
-        typedef __attribute__((address_space(3))) s16x4_t *lds_s16x4_ptr;
-        struct {
-            s16x4_t lo, hi;
-        } w;
-        w.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-        w.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 16 * KB));
-        return __builtin_bit_cast(bf16x8_t, w);
-    };
-    const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
-    const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
-    const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
-
-    // per block: this lane's column (row, head), its position, and the q operand
-    uint32_t col_pos[NB];
-    bool col_ok[NB];
-    f32x4_t oacc[NB][MM];
-    float m[NB];
-    f32x4_t lacc[NB]; // running sums of the weights, every element the same (see pv)
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const uint32_t row = row_w + b * rpb + j / G;
-        col_ok[b] = row < q_len;
-        col_pos[b] = pos0 + row;
-        const uint4 *qp = reinterpret_cast<const uint4 *>(a.q + q_off + ((uint64_t)(col_ok[b] ? row : 0) * n_q + kvh * G +
-                                                                         j % G) * D) + q;
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st) {
-            uint4 w = ld_g16(qp + st * 4);
-            if (!col_ok[b])
-                w = make_uint4(0, 0, 0, 0);
-            s_q[(b * KSTEPS + st) * NT + tid] = w; // read back by this lane only
-        }
-#pragma unroll
-        for (int mm = 0; mm < MM; ++mm)
-            oacc[b][mm] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-        m[b] = kMinusBig;
-        lacc[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    }
-    // tokens this wave / this workgroup has to look at: up to the position of the last valid row
-    auto hi_of = [&](uint32_t first_row, uint32_t n_rows) -> uint32_t {
-        if (first_row >= q_len)
-            return 0;
-        const uint32_t last_row = min(first_row + n_rows, q_len) - 1;
-        return pos0 + last_row + 1;
-    };
-    const uint32_t wave_hi = hi_of(row_w, NB * rpb);
-    const uint32_t wg_hi = hi_of(r0, NW * NB * rpb);
-    const uint32_t wave_lo = pos0 + row_w;                     // position of the wave's first row
-    const bool wave_full = row_w + NB * rpb <= q_len;          // all the wave's columns are valid rows
-
-    const uint64_t row_off = (uint64_t)kvh * (4 * D);
-    uint32_t w0 = 0;
-    while (w0 < wg_hi) { // workgroup-uniform: one pass per page-table window
-        const uint64_t s_lo = ((uint64_t)w0 * T + row_off) >> lg;
-        const uint64_t lim = (s_lo + kPfTabWindow) << lg;
-        const uint64_t tmax = (lim - (row_off + 4 * D)) / T; // last token whose head-row ends inside the window
-        const uint32_t w1 = (uint32_t)(tmax + 1 < (uint64_t)wg_hi ? tmax + 1 : (uint64_t)wg_hi);
-        const uint32_t n_ent = (uint32_t)((((uint64_t)(w1 - 1) * T + row_off + 4 * D - 1) >> lg) - s_lo) + 1;
-        if (w0 != 0)
-            __syncthreads();
-        for (uint32_t e = tid; e < n_ent; e += NT)
-            tab[e] = as_global(a.page_table)[table_off + s_lo + e];
-        __syncthreads();
-
-        const uint32_t r1 = min(w1, wave_hi); // this wave's tokens of the window end here
-        {
-            const uint32_t last = w1 - 1;
-            // Window-relative byte offsets fit 32 bits (a window spans at most kPfTabWindow pages).
-            const uint32_t c0 = (uint32_t)(((uint64_t)w0 * T + row_off) - (s_lo << lg));
-            const uint32_t T32 = (uint32_t)T, mask32 = (uint32_t)page_mask;
-            auto row_ptr = [&](uint32_t t) -> const unsigned char * {
-                const uint32_t off = (t - w0) * T32 + c0;
-                const int32_t pg = tab[off >> lg];
-                return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
-            };
-            // Tile staging: each wave fetches RPI KI of the tile's 32 K rows (or V rows), RPI rows per
-            // global-to-LDS load.  Tokens past the window's end are copies of its last token (masked in the
-            // scores).  A tile's K is requested one step before its V, so the row addresses are worked out
-            // once, for K, and kept for V.
-            struct RowPtrs {
-                const unsigned char *p[KI];
-            };
-            auto rows_of = [&](uint32_t tb) {
-                RowPtrs r;
-#pragma unroll
-                for (uint32_t x = 0; x < KI; ++x)
-                    r.p[x] = row_ptr(min(tb + ld_tok + RPI * x, last));
-                return r;
-            };
-            auto issue_k = [&](const RowPtrs &r, unsigned char *kt) {
-#pragma unroll
-                for (uint32_t x = 0; x < KI; ++x) {
-                    const uint32_t tok = ld_tok + RPI * x;
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x] + ((ld_pos ^ (tok % PIECES)) * 16)),
-                                                     (lds_ptr_t)(kt + (KI * wave + x) * 1024), 16, 0, 0);
-                }
-            };
-            auto issue_v = [&](const RowPtrs &r, unsigned char *vt) {
-#pragma unroll
-                for (uint32_t x = 0; x < KI; ++x)
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x] + KB + (ld_pos ^ vswz(ld_tok + RPI * x)) * 16),
-                                                     (lds_ptr_t)(vt + (KI * wave + x) * 1024), 16, 0, 0);
-            };
-            auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
-            // Raw scores S^T = K Q^T of one staged K tile against all NB blocks of the wave.
-            auto scores = [&](const unsigned char *kt, f32x4_t (&s0)[NB], f32x4_t (&s1)[NB]) {
-                uint32_t tq = tid; // opaque per tile: keeps the q reads below inside the loop (out of registers)
-                asm volatile("" : "+v"(tq));
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    s0[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-                    s1[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-                }
-#pragma unroll
-                for (int st = 0; st < KSTEPS; ++st) { // K rows of tokens j and 16+j, pieces st*4+q
-                    const uint32_t pc = ((st * 4 + q) ^ (j % PIECES)) * 16; // (16 + j) % PIECES == j % PIECES
-                    const u32x4 k0 = *reinterpret_cast<const u32x4 *>(kt + j * KB + pc);
-                    const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kt + (16 + j) * KB + pc);
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        const bf16x8_t qb = as_bf16x8(s_q[(b * KSTEPS + st) * NT + tq]);
-                        s0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0), qb, s0[b], 0, 0, 0);
-                        s1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1), qb, s1[b], 0, 0, 0);
-                    }
-                }
-            };
-            // Online softmax of the tile at tb from its raw scores, stage by stage over the blocks, so
-            // that the blocks' independent instruction chains can overlap.  MASKED: the tile reaches past
-            // some column's position (or past the window); otherwise every score counts and the compares
-            // are skipped.  A block that lies wholly before the tile just sees every score masked.
-            // Returns whether some accumulator has to be rescaled before the tile is added: by 2^(-grow[b]).
-            auto softmax = [&](uint32_t tb, const f32x4_t (&s0)[NB], const f32x4_t (&s1)[NB], bf16x8_t (&Ph)[NB],
-                               bf16x8_t (&Pl)[NB], float (&grow)[NB], auto masked) -> bool {
-                constexpr bool MASKED = decltype(masked)::value;
-                // Raw scores; the scale (times log2 e, positive) is applied to the maximum and folded into
-                // the multiply-add under the exponential.
-                float sr[NB][8], mt[NB];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        sr[b][r] = s0[b][r];
-                        sr[b][4 + r] = s1[b][r];
-                    }
-                    if (MASKED) {
-                        // causal mask: token t counts for this column if t <= its position (and lies in
-                        // this window: tokens past it were loaded as copies of the window's last token)
-                        const uint32_t t_lim = col_ok[b] ? min(col_pos[b] + 1, r1) : 0;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            sr[b][r] = (tb + 4 * q + r < t_lim) ? sr[b][r] : -INFINITY;
-                            sr[b][4 + r] = (tb + 16 + 4 * q + r < t_lim) ? sr[b][4 + r] : -INFINITY;
-                        }
-                    }
-                    mt[b] = fmaxf(fmaxf(fmaxf(sr[b][0], sr[b][1]), fmaxf(sr[b][2], sr[b][3])),
-                                  fmaxf(fmaxf(sr[b][4], sr[b][5]), fmaxf(sr[b][6], sr[b][7])));
-                }
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    mt[b] = max_over_kblocks(mt[b]) * scale_log2e;
-                bool rescale = false;
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    // The reference point of the exponentials only moves when the maximum has grown by
-                    // more than 2^kLazy: weights then stay below 2^kLazy, and the accumulators are rescaled
-                    // rarely.
-                    const float mn = mt[b] > m[b] + kLazy ? mt[b] : m[b]; // finite: m starts at kMinusBig
-                    grow[b] = mn - m[b]; // how far the reference point moved: 0 almost always
-                    rescale |= grow[b] != 0.f;
-                    m[b] = mn;
-                    // P as two bf16 parts by truncation (see process_item_gqa)
-                    uint32_t ph[4], pl[4];
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) {
-                        const float p0 = fast_exp2(fmaf(sr[b][e], scale_log2e, -mn));
-                        const float p1 = fast_exp2(fmaf(sr[b][e + 1], scale_log2e, -mn));
-                        const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
-                        const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
-                        const float x1 = p1 - __uint_as_float(u1 & 0xffff0000u);
-                        ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
-                        pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
-                    }
-                    Ph[b] = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
-                    Pl[b] = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
-                }
-                return __builtin_amdgcn_ballot_w64(rescale) != 0;
-            };
-            // O^T += V^T P^T for one staged V tile: rows of the 8 tokens tau(q, .), piece j, transposed one
-            // output row group at a time and multiplied into every block.
-            // The weights' running sums ride along as one more product with an all-ones left operand: every row
-            // of its result is the column sum of the (two-part) weights, over all four k-blocks at once.
-            auto pv = [&](const unsigned char *vt, const bf16x8_t (&Ph)[NB], const bf16x8_t (&Pl)[NB]) {
-                const bf16x8_t ones = as_bf16x8(make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u));
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    lacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, Ph[b], lacc[b], 0, 0, 0);
-                    lacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, Pl[b], lacc[b], 0, 0, 0);
-                }
-                // Left operand of the product for output rows d = 16 mm + i (lane i of 16): V[token][d] for the
-                // lane's 8 tokens tau(q, .), fetched by two transposing LDS reads (tokens 4q.. and 16+4q..).
-#pragma unroll
-                for (int mm = 0; mm < MM; ++mm) {
-                    const bf16x8_t Vt = vt_operand(vt + voff[mm]);
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Ph[b], oacc[b][mm], 0, 0, 0);
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Pl[b], oacc[b][mm], 0, 0, 0);
-                    }
-                }
-            };
-            RowPtrs rows; // row addresses of the tile whose K was requested last
-            // One step of the pipeline over the window's tiles.  On entry the raw scores of the tile at tb
-            // are in s_cur, K of the next tile is in k_next and V of this tile in v_cur.  The step starts
-            // the loads of K two tiles ahead (into the array this tile's K has left) and of the next V,
-            // then takes the next tile's scores on the matrix cores while the vector units do this tile's
-            // softmax -- the two are independent, which is the point of the arrangement -- and finally
-            // adds this tile's V^T P^T.  Control flow is workgroup-uniform up to the barrier; a wave past
-            // its own rows (tb >= r1) only loads and waits.
-            auto step = [&](uint32_t tb, const unsigned char *k_next, const unsigned char *v_cur, unsigned char *k_fill,
-                            unsigned char *v_fill, const f32x4_t (&c0s)[NB], const f32x4_t (&c1s)[NB],
-                            f32x4_t (&n0s)[NB], f32x4_t (&n1s)[NB]) {
-                if (tb + 32 < w1)
-                    issue_v(rows, v_fill); // rows: those of the tile at tb + 32, from the previous step
-                if (tb + 64 < w1) {
-                    rows = rows_of(tb + 64);
-                    issue_k(rows, k_fill);
-                }
-                if (tb < r1) {
-                    bf16x8_t Ph[NB], Pl[NB];
-                    float grow[NB];
-                    bool rescale;
-                    // The next tile's scores are taken whether or not this wave (or the window) has a next
-                    // tile: without one they are computed from stale LDS contents and never used.
-                    // (Inside either branch, so that the two share a basic block and get interleaved.)
-                    // wave-uniform: all 32 tokens lie in the window and at or before the wave's first row,
-                    // and every column of the wave is a valid row
-                    if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full) {
-                        scores(k_next, n0s, n1s);
-                        rescale = softmax(tb, c0s, c1s, Ph, Pl, grow, std::false_type{});
-                    } else {
-                        scores(k_next, n0s, n1s);
-                        rescale = softmax(tb, c0s, c1s, Ph, Pl, grow, std::true_type{});
-                    }
-                    if (rescale) {
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-                            const float alpha = fast_exp2(-grow[b]);
-                            lacc[b] *= alpha;
-#pragma unroll
-                            for (int mm = 0; mm < MM; ++mm)
-                                oacc[b][mm] *= alpha;
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0); // keeps the V registers from being loaded before the scores are done with theirs
-                    pv(v_cur, Ph, Pl);
-                }
-                __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tiles just requested is in LDS
-                __syncthreads(); // they are complete; the arrays just read may be overwritten
-            };
-            f32x4_t sa0[NB], sa1[NB], sb0[NB], sb1[NB];
-            rows = rows_of(w0);
-            issue_k(rows, s_k0);
-            issue_v(rows, s_v0);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads(); // the first tile is staged
-            if (w0 + 32 < w1) {
-                rows = rows_of(w0 + 32);
-                issue_k(rows, s_k1);
-            }
-            if (w0 < r1)
-                scores(s_k0, sa0, sa1);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads(); // K of the second tile is staged; every wave is done with the first tile's K
-            for (uint32_t tb = w0; tb < w1; tb += 64) { // workgroup-uniform; tiles alternate between the arrays
-                step(tb, s_k1, s_v0, s_k0, s_v1, sa0, sa1, sb0, sb1);
-                if (tb + 32 < w1)
-                    step(tb + 32, s_k0, s_v1, s_k1, s_v0, sb0, sb1, sa0, sa1);
-            }
-        }
-        w0 = w1;
-    }
-
-    // lane (j, q) holds O[column j][d = 16 mm + 4q + r] in oacc[b][mm][r] and the column's sum of weights in lacc[b]
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const float lb = lacc[b][0];
-        if (!col_ok[b])
-            continue;
-        const float inv = lb > 0.f ? 1.f / lb : 0.f;
-        const uint32_t row = col_pos[b] - pos0;
-        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 4 * q;
-#pragma unroll
-        for (int mm = 0; mm < MM; ++mm)
-            st_g16(dst + 16 * mm, oacc[b][mm][0] * inv, oacc[b][mm][1] * inv, oacc[b][mm][2] * inv,
-                   oacc[b][mm][3] * inv);
-    }
-}
-
 // One 64-lane workgroup per (cut sequence, query head): out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M).
 __global__ void __launch_bounds__(64) reduce_kernel(const ReduceRec *recs, const float *partials, float *out) {
     const ReduceRec r = recs[blockIdx.x];
@@ -1281,114 +804,6 @@ __global__ void __launch_bounds__(64) reduce_kernel(const ReduceRec *recs, const
         dst[64 + lane] = o1 * inv;
 }
 
-__global__ void patch_kernel(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n) {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n)
-        page_table[entry[i]] = page[i];
-}
-
-// Workgroups [0, n_requests): one per request; each lane moves 16-byte pieces of the new token
-// row.  Page ids of table entries that are being patched in the same call come with the record
-// (r.page[k] >= 0 for the k-th page the token touches), so no workgroup reads an entry another one
-// is writing.  Workgroups [n_requests, ...): write the patched page-table entries.
-__global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, uint32_t lg, int32_t *page_table,
-                                                     const AppendRec *recs, uint32_t n_requests,
-                                                     const ClassRec *classes, const uint16_t *new_k,
-                                                     const uint16_t *new_v, const uint64_t *patch_entry,
-                                                     const int32_t *patch_page, uint32_t n_patches) {
-    if (blockIdx.x >= n_requests) {
-        const uint32_t i = (blockIdx.x - n_requests) * blockDim.x + threadIdx.x;
-        if (i < n_patches)
-            page_table[patch_entry[i]] = patch_page[i];
-        return;
-    }
-    const AppendRec r = recs[blockIdx.x];
-    if (r.ctx_len == 0)
-        return;
-    const ClassRec c = classes[r.cls];
-    const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
-    const uint32_t n_pieces = c.token_bytes / 16;
-    const uint64_t stream0 = (uint64_t)(r.ctx_len - 1) * c.token_bytes;
-    const uint64_t first_slot = stream0 >> lg;
-    const uint64_t page_mask = (1ull << lg) - 1;
-    for (uint32_t pc = threadIdx.x; pc < n_pieces; pc += blockDim.x) {
-        const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
-        const uint16_t *src = (w < half ? new_k : new_v) + r.new_off + (uint64_t)h * c.d + (w % half) * 8;
-        const uint64_t off = stream0 + (uint64_t)pc * 16;
-        const uint64_t slot = off >> lg;
-        const uint32_t k = (uint32_t)(slot - first_slot);
-        int32_t pg = k < 4 ? r.page[k] : -1;
-        if (pg < 0)
-            pg = page_table[r.table_off + slot];
-        uint4 *dst = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
-        *dst = *reinterpret_cast<const uint4 *>(src);
-    }
-}
-
-// Paged <-> contiguous copy.  One workgroup per record = tokens [t0, t1) of one request (the
-// host cuts requests into chunks of about 1 MiB); the (token, 16-byte piece) pairs of the chunk
-// are spread over the lanes, four in flight per lane.  TO_POOL = false gathers (pool ->
-// k_io/v_io), true scatters (k_io/v_io -> pool).
-template <bool TO_POOL>
-__global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_base, uint32_t lg,
-                                                          const int32_t *page_table, const GatherRec *recs,
-                                                          const ClassRec *classes, uint16_t *k_io, uint16_t *v_io) {
-    const GatherRec r = recs[blockIdx.x];
-    const ClassRec c = classes[r.cls];
-    const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
-    const uint32_t n_pieces = c.token_bytes / 16;
-    const uint64_t page_mask = (1ull << lg) - 1;
-    const uint64_t total = (uint64_t)(r.t1 - r.t0) * n_pieces;
-    auto addrs = [&](uint64_t idx, uint4 *&in_pool, uint4 *&flat) {
-        const uint32_t t = r.t0 + (uint32_t)(idx / n_pieces), pc = (uint32_t)(idx % n_pieces);
-        const uint32_t h = pc / pieces_per_row, w = pc % pieces_per_row;
-        const uint64_t off = (uint64_t)t * c.token_bytes + (uint64_t)pc * 16;
-        const int32_t pg = page_table[r.table_off + (off >> lg)];
-        in_pool = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
-        flat = reinterpret_cast<uint4 *>((w < half ? k_io : v_io) + r.kv_off + ((uint64_t)t * c.n_kv + h) * c.d +
-                                         (w % half) * 8);
-    };
-    uint64_t idx = threadIdx.x;
-    for (; idx + 3 * 256 < total; idx += 4 * 256) {
-        uint4 *pp[4], *ff[4], x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            addrs(idx + u * 256, pp[u], ff[u]);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            x[u] = TO_POOL ? *ff[u] : *pp[u];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            *(TO_POOL ? pp[u] : ff[u]) = x[u];
-    }
-    for (; idx < total; idx += 256) {
-        uint4 *p1, *f1;
-        addrs(idx, p1, f1);
-        if (TO_POOL)
-            *p1 = *f1;
-        else
-            *f1 = *p1;
-    }
-}
-
-// Plan upload: copies 16-byte pieces from pinned, device-mapped host memory into the workspace.
-// Workgroups past the copy write the step's new page-table entries (fused append), so that the
-// decode launch that follows finds them in place.
-__global__ void __launch_bounds__(256) stage_copy_kernel(uint4 *dst, const uint4 *src, uint32_t n16,
-                                                         int32_t *page_table, const uint64_t *patch_entry,
-                                                         const int32_t *patch_page, uint32_t n_patches) {
-    const uint32_t copy_blocks = (n16 + 255) / 256;
-    if (blockIdx.x >= copy_blocks) {
-        const uint32_t i = (blockIdx.x - copy_blocks) * blockDim.x + threadIdx.x;
-        if (i < n_patches)
-            page_table[patch_entry[i]] = patch_page[i];
-        return;
-    }
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n16)
-        dst[i] = src[i];
-}
-
 // ------------------------------------------------------------------ launchers
 int decode_resident_workgroups(uint32_t block_threads) {
     int dev = 0, cus = 0, per_cu = 0;
@@ -1404,18 +819,6 @@ int decode_resident_workgroups(uint32_t block_threads) {
 }
 
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps.
-hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, int32_t *page_table,
-                             const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
-                             hipStream_t s) {
-    const uint32_t n16 = (uint32_t)((bytes + 15) / 16);
-    const uint32_t blocks = (n16 + 255) / 256 + (n_patches + 255) / 256;
-    if (blocks == 0)
-        return hipSuccess;
-    hipLaunchKernelGGL(stage_copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4 *>(dst),
-                       static_cast<const uint4 *>(src_mapped), n16, page_table, patch_entry, patch_page, n_patches);
-    return hipGetLastError();
-}
-
 hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1) {
     if (n_spans == 0)
@@ -1432,55 +835,6 @@ hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_he
     if (n_recs == 0)
         return hipSuccess;
     hipExtLaunchKernelGGL(reduce_kernel, dim3(n_recs, max_heads), dim3(64), 0, s, ev0, ev1, 0, recs, partials, out);
-    return hipGetLastError();
-}
-
-hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
-                        hipStream_t s) {
-    if (n == 0)
-        return hipSuccess;
-    hipLaunchKernelGGL(patch_kernel, dim3((n + 255) / 256), dim3(256), 0, s, page_table, entry, page, n);
-    return hipGetLastError();
-}
-
-hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,
-                         uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
-                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
-                         hipEvent_t ev0, hipEvent_t ev1) {
-    const uint32_t blocks = n + (n_patches + 255) / 256;
-    if (blocks == 0)
-        return hipSuccess;
-    hipExtLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, s, ev0, ev1, 0, pool_base, log2_page, page_table,
-                          recs, n, classes, static_cast<const uint16_t *>(new_k),
-                          static_cast<const uint16_t *>(new_v), patch_entry, patch_page, n_patches);
-    return hipGetLastError();
-}
-
-hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, hipStream_t s, hipEvent_t ev0,
-                          hipEvent_t ev1) {
-    if (n_recs == 0)
-        return hipSuccess;
-    static_assert(kPrefillCols == kPrefillWaves * kPrefillBlocks * 16, "NW waves x NB blocks of 16 columns");
-    if (head_dim == 128)
-        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 128>), dim3(n_recs),
-                              dim3(64 * kPrefillWaves), 0, s, ev0, ev1, 0, a);
-    else
-        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 64>), dim3(n_recs),
-                              dim3(64 * kPrefillWaves), 0, s, ev0, ev1, 0, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
-                              const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
-                              hipStream_t s) {
-    if (n == 0)
-        return hipSuccess;
-    if (to_pool)
-        hipLaunchKernelGGL(copy_tokens_kernel<true>, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table,
-                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
-    else
-        hipLaunchKernelGGL(copy_tokens_kernel<false>, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table,
-                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
     return hipGetLastError();
 }
 
