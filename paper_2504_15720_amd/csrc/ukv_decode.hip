@@ -611,6 +611,9 @@ __device__ __forceinline__ void process_item_gqa() {
             // the largest one gets the weight 1 exactly (a one-token context returns that token's V).
             auto softmax_pv = [&](uint32_t tb, uint32_t t_lim, const f32x4_t &s0, const f32x4_t &s1,
                                   const u32x4 (&vr)[8], auto masked) {
+// The scaled score must be rounded before the maximum is subtracted from it: fused into the
+// subtraction, the largest score would no longer get the weight 1 exactly.
+#pragma clang fp contract(off)
                 constexpr bool MASKED = decltype(masked)::value;
                 float sr[8];
 #pragma unroll
