@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("UKV_LIB") or os.path.join(_HERE, "libukv.so")
 
 UKV_OK, UKV_EINVAL, UKV_ENOMEM, UKV_ENOSPC, UKV_EHIP = 0, -1, -2, -3, -4
+UKV_MAX_SERVICES = 16
 UKV_PARAM_MAX_SPANS, UKV_PARAM_MIN_SPAN_BYTES, UKV_PARAM_BLOCK_THREADS = 1, 2, 3
 UKV_PARAM_HEADS_PER_SLICE, UKV_PARAM_PROFILE, UKV_PARAM_FUSED_MERGE = 4, 5, 6
 UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT, UKV_PARAM_PREFILL_XCD = 7, 8, 9, 10

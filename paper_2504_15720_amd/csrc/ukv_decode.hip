@@ -746,7 +746,7 @@ __device__ __forceinline__ void process_item_gqa() {
 }
 
 template <int NT>
-__global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(NT, 2) decode_kernel(DecodeArgs a) { // at least two waves per SIMD
     const uint32_t i0 = uni(a.span_first[blockIdx.x]), i1 = uni(a.span_first[blockIdx.x + 1]);
     if (threadIdx.x == 0)
         s_ctx.a = a;

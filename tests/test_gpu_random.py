@@ -49,3 +49,27 @@ def test_random_batches_match_oracle(seed):
             _check_attention(db, b, f"decode {seed}, block {block}")
     finally:
         db.close()
+
+
+def test_sixteen_services_in_one_pool():
+    """The largest number of services a pool takes: every supported (head_dim, group) kind, several head
+    counts and explicit scales, one launch for decode and one per head_dim for prefill."""
+    services = [Service(32, 32, 128), Service(40, 40, 128, 0.11), Service(32, 8, 128), Service(64, 8, 128, 0.07),
+                Service(16, 8, 128), Service(4, 1, 128), Service(8, 8, 64), Service(12, 12, 64, 0.2),
+                Service(8, 4, 64), Service(2, 1, 64), Service(1, 1, 128, 0.5), Service(8, 1, 128),
+                Service(16, 16, 64), Service(24, 12, 64), Service(2, 2, 128), Service(48, 6, 128)]
+    assert len(services) == U.UKV_MAX_SERVICES
+    rng = np.random.default_rng(77)
+    sid = np.concatenate([np.arange(16), rng.integers(0, 16, size=16)])
+    ctx = rng.integers(1, 900, size=sid.size)
+    need = sum(-(-int(c) * services[int(s)].token_bytes // 16384) for c, s in zip(ctx, sid))
+    b = make_batch(services, sid, ctx, int(need * 1.3) + 64, "permutation", rng, pool_seed=7)
+    db = DeviceBatch(b)
+    try:
+        _check_attention(db, b, "16 services, decode")
+        q_len = np.minimum(ctx, rng.integers(0, 200, size=sid.size))
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        _check_rows(b, out_t.cpu().numpy(), q_bits, q_len, q_off, out_off, rows_of=_sampled_rows, tag="16 services, prefill")
+    finally:
+        db.close()
