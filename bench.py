@@ -49,7 +49,7 @@ def read_traffic(cfg: int):
         return None, None
 
 
-def cpu_baseline(batch, kv_bytes_total: int, target_s: float = 15.0):
+def cpu_baseline(batch, kv_bytes_total: int, target_s: float = 15.0, one_thread: bool = False):
     """Time the oracle (attention) on a bounded sample of the batch's requests."""
     import numpy as np
     from oracle import oracle
@@ -70,12 +70,20 @@ def cpu_baseline(batch, kv_bytes_total: int, target_s: float = 15.0):
     oracle.attention(batch, batch.pool, requests=sample)
     dt = time.perf_counter() - t0
     sb = int((batch.ctx_len[sample].astype(np.int64) * tb[sample]).sum())
-    return {
-        "value": sb / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+    cores = oracle.threads()
+    res = {
+        "value": sb / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
         "sample": f"{len(sample)} of {n} requests of the same batch ({sb / 1e9:.3f} GB of KV, one attention "
                   f"step, {dt:.1f} s, fp64, OpenMP over requests)",
         "tokens_per_s": len(sample) / dt,
     }
+    if one_thread:  # the small workloads also on a single core
+        t0 = time.perf_counter()
+        oracle.attention(batch, batch.pool, requests=sample, n_threads=1)
+        dt1 = time.perf_counter() - t0
+        oracle.attention(batch, batch.pool, requests=probe[:1], n_threads=cores)  # back to all cores
+        res["one_thread"] = {"value": round(sb / dt1 / 1e9, 4), "unit": "GB/s", "cores": 1, "seconds": round(dt1, 2)}
+    return res
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
@@ -466,7 +474,7 @@ def main():
         "setup_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(b, int(kv_per_step))
+        line["cpu_baseline"] = cpu_baseline(b, int(kv_per_step), one_thread=args.config in (1, 2))
         line["cpu_baseline"]["value"] = round(line["cpu_baseline"]["value"], 4)
         line["cpu_baseline"]["tokens_per_s"] = round(line["cpu_baseline"]["tokens_per_s"], 2)
     db.close()
