@@ -358,6 +358,9 @@ def main():
     ap.add_argument("--split-page-bytes", type=int, default=0, help="block size of the split layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="skip grow+append in the step (diagnostic)")
+    ap.add_argument("--time-every", type=int, default=4,
+                    help="decode phase: HIP-event timing of every n-th launch of each kernel (a timed launch costs "
+                         "about 10 us of stream time; 1 = every launch)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; every GPU box here has one and the path uses no "
@@ -383,7 +386,7 @@ def main():
         from synth import to_split_layout
         b = to_split_layout(b, pool_seed=7, page_bytes=args.split_page_bytes or None)
     t_gen = time.perf_counter() - t_gen
-    db = DeviceBatch(b, profile=True)
+    db = DeviceBatch(b, profile=args.time_every)
     if args.block:
         U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, args.block)
     if args.max_spans:
@@ -466,6 +469,7 @@ def main():
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(b.n_requests * args.steps / wall, 1),
         "kernel_ms": {"decode": round(dec_ms, 4), "reduce": round(red_ms, 4), "append": round(app_ms, 4)},
+        "kernel_ms_launches_timed": {"decode": prof.n_decode, "every": args.time_every},
         "attention_kernels_gbs": round(kv_per_step / ((dec_ms + red_ms) * 1e-3) / 1e9, 2),
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

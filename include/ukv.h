@@ -197,7 +197,8 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_MIN_SPAN_BYTES 2   /* do not cut spans smaller than this many KV bytes (default 512 KiB) */
 #define UKV_PARAM_BLOCK_THREADS 3    /* 256 or 512 (default 512; 256 where every service has d = 128 and g > 1) */
 #define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
-#define UKV_PARAM_PROFILE 5          /* 1 = time kernels with HIP events (see ukv_profile_read) */
+#define UKV_PARAM_PROFILE 5          /* 0 = off; n >= 1 = time every n-th launch of each kernel with HIP events (see
+                                        ukv_profile_read).  A timed launch costs about 10 us of stream time. */
 #define UKV_PARAM_FUSED_MERGE 6      /* 1 (default) = merge partials inside the decode launch; 0 = second launch */
 #define UKV_PARAM_SLOTS 7            /* decode workgroups resident at once; 0 (default) = ask the device */
 #define UKV_PARAM_GQA_COST_PCT 9     /* planner cost of a KV byte of a matrix-core service (d = 128, g > 1), in percent of
@@ -208,7 +209,7 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
 int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 
-/* Kernel times collected while UKV_PARAM_PROFILE is 1 (HIP events on the caller's stream).
+/* Kernel times collected while UKV_PARAM_PROFILE is on (HIP events on the caller's stream).
  * Reading waits for the recorded events and resets the accumulators.  At most 8192 unread
  * timings are kept; past that the oldest are dropped. */
 typedef struct {

@@ -68,6 +68,8 @@ struct ProfPair {
     int get() {
         if (!p->tun.profile)
             return UKV_OK;
+        if (p->prof_seq[which]++ % (uint64_t)p->tun.profile != 0) // one launch in `profile` of each kind is timed
+            return UKV_OK;
         if (p->ev_used.size() >= kMaxPendingTimings) { // nobody reads the profile: drop the oldest timings
             p->ev_free.insert(p->ev_free.end(), p->ev_used.begin(), p->ev_used.end());
             p->ev_used.clear();

@@ -207,6 +207,7 @@ struct ukv_pool {
         int which;
     };
     std::vector<EvPair> ev_used, ev_free;
+    uint64_t prof_seq[4] = {0, 0, 0, 0}; // launches seen per kind (decode, reduce, append, prefill)
 };
 
 namespace ukv {

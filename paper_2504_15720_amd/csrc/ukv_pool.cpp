@@ -263,7 +263,9 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
         p->tun.heads_per_slice = value;
         return derive_classes(p);
     case UKV_PARAM_PROFILE:
-        p->tun.profile = value ? 1 : 0;
+        if (value < 0 || value > 1024)
+            return fail(UKV_EINVAL, "profile must be 0 (off) or a stride in [1, 1024]");
+        p->tun.profile = value;
         return UKV_OK;
     case UKV_PARAM_FUSED_MERGE:
         p->tun.fused_merge = value ? 1 : 0;

@@ -40,8 +40,8 @@ class DeviceBatch:
         self.newv_t = torch.zeros(b.new_elems, dtype=torch.int16, device=self.dev)
         self.ws_bytes = U.ukv_decode_workspace_bytes(self.pool, b.n_requests)
         self.ws_t = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
-        if profile:
-            U.ukv_set_param(self.pool, U.UKV_PARAM_PROFILE, 1)
+        if profile:  # True = every launch; an integer n = every n-th launch of each kernel
+            U.ukv_set_param(self.pool, U.UKV_PARAM_PROFILE, int(profile))
 
     def close(self):
         if self.pool:
