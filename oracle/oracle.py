@@ -76,8 +76,10 @@ def gather(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, n_kv_heads:
     return k, v
 
 
-def scatter(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, k: np.ndarray, v: np.ndarray) -> None:
-    """Write contiguous bf16 bit patterns K[n,H,d], V[n,H,d] as tokens [0, n) of one request, in place."""
+def scatter(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, k: np.ndarray, v: np.ndarray,
+            first_token: int = 0) -> None:
+    """Write contiguous bf16 bit patterns K[n,H,d], V[n,H,d] as tokens [first_token, first_token + n) of one
+    request, in place (first_token > 0: the bulk append of a chunk behind the tokens already stored)."""
     lib = _load()
     pool = pool_u16.view(np.uint8)
     assert pool.flags.writeable and pool.flags.c_contiguous
@@ -86,7 +88,7 @@ def scatter(pool_u16: np.ndarray, page_bytes: int, table: np.ndarray, k: np.ndar
     n, H, d = k.shape
     rc = lib.ukv_oracle_scatter(_p(pool, C.c_uint8), C.c_uint64(pool.size), C.c_uint32(page_bytes),
                                 _p(table, C.c_int32), C.c_uint64(table.size), C.c_uint32(H), C.c_uint32(d),
-                                C.c_uint64(n), _p(k, C.c_uint16), _p(v, C.c_uint16))
+                                C.c_uint64(first_token), C.c_uint64(n), _p(k, C.c_uint16), _p(v, C.c_uint16))
     _check(rc, "scatter")
 
 

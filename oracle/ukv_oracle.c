@@ -112,11 +112,14 @@ int ukv_oracle_gather(const uint8_t *pool, uint64_t pool_bytes, uint32_t page_by
     return ORC_OK;
 }
 
-/* The inverse of gather: write contiguous k_in[n][H][d], v_in[n][H][d] as tokens [0, n) of one
- * request's stream (bulk store after prefill, or the receiving side of a migration). */
+/* The inverse of gather, for a run of tokens: write contiguous k_in[n][H][d], v_in[n][H][d] as tokens
+ * [first_token, first_token + n) of one request's stream.  first_token = 0 is the bulk store after a
+ * whole-prompt prefill or the receiving side of a migration; first_token > 0 is the bulk append of a
+ * chunk in chunked prefill (section 2.1: the pass over a chunk leaves its KV pairs in the cache behind
+ * those of the earlier chunks). */
 int ukv_oracle_scatter(uint8_t *pool, uint64_t pool_bytes, uint32_t page_bytes, const int32_t *table,
-                       uint64_t table_len, uint32_t n_kv_heads, uint32_t head_dim, uint64_t n_tokens,
-                       const uint16_t *k_in, const uint16_t *v_in)
+                       uint64_t table_len, uint32_t n_kv_heads, uint32_t head_dim, uint64_t first_token,
+                       uint64_t n_tokens, const uint16_t *k_in, const uint16_t *v_in)
 {
     if (!shape_ok(page_bytes, n_kv_heads, n_kv_heads, head_dim))
         return ORC_EINVAL;
@@ -124,7 +127,7 @@ int ukv_oracle_scatter(uint8_t *pool, uint64_t pool_bytes, uint32_t page_bytes, 
     uint64_t row = 4ull * head_dim, tok = row * n_kv_heads;
     for (uint64_t t = 0; t < n_tokens; ++t)
         for (uint64_t h = 0; h < n_kv_heads; ++h) {
-            uint64_t a = head_row_address(page_bytes, n_pages, table, table_len, tok, row, t, h);
+            uint64_t a = head_row_address(page_bytes, n_pages, table, table_len, tok, row, first_token + t, h);
             if (a == UINT64_MAX)
                 return ORC_ERANGE;
             memcpy(pool + a, k_in + (t * n_kv_heads + h) * head_dim, 2ull * head_dim);

@@ -40,6 +40,13 @@ MUTATIONS = {
     "scatter writes head rows token-minor": (
         "memcpy(pool + a, k_in + (t * n_kv_heads + h) * head_dim, 2ull * head_dim);",
         "memcpy(pool + a, k_in + (h * n_tokens + t) * head_dim, 2ull * head_dim);"),
+    "chunk scattered one token early": (
+        "uint64_t a = head_row_address(page_bytes, n_pages, table, table_len, tok, row, first_token + t, h);\n"
+        "            if (a == UINT64_MAX)\n                return ORC_ERANGE;\n"
+        "            memcpy(pool + a, k_in",
+        "uint64_t a = head_row_address(page_bytes, n_pages, table, table_len, tok, row, first_token + t - (first_token > 0), h);\n"
+        "            if (a == UINT64_MAX)\n                return ORC_ERANGE;\n"
+        "            memcpy(pool + a, k_in"),
     "prefill mask off by one (own token excluded)": (
         "head_dim, scale, 0, (uint64_t)pos[k] + 1, q_rows + (uint64_t)k * row, m,",
         "head_dim, scale, 0, (uint64_t)pos[k] + (pos[k] == 0), q_rows + (uint64_t)k * row, m,"),
@@ -69,6 +76,7 @@ def _run_pins():
     pins.test_split_and_merge_equals_whole()
     pins.test_append_touches_exactly_the_new_token(5)
     pins.test_scatter_places_every_element_and_inverts_gather("13b")
+    pins.test_scatter_of_a_chunk_is_a_bulk_append("13b")
     pins.test_prefill_equals_masked_matrix_and_torch_causal(1, 19)
     pins.test_prefill_closed_forms_and_causality()
 

@@ -337,6 +337,41 @@ def test_scatter_places_every_element_and_inverts_gather(name):
     assert np.array_equal(gk, k) and np.array_equal(gv, v)
 
 
+@pytest.mark.parametrize("name", ["h12", "13b", "70b"])
+def test_scatter_of_a_chunk_is_a_bulk_append(name):
+    """Chunks written one after the other give the image of the whole prompt written at once; a chunk touches
+    only its own tokens' bytes (sentinel elsewhere); each element sits where the test-side placement puts it;
+    a chunk of one token is the single-token append."""
+    shape = SHAPES[name]
+    rng = np.random.default_rng(78)
+    n, P = 23, 16384
+    need = -(-n * shape.token_bytes // P)
+    table = rng.permutation(need + 3)[:need].astype(np.int32)
+    k = f32_to_bits(rng.standard_normal((n, shape.n_kv_heads, shape.head_dim)).astype(np.float32))
+    v = f32_to_bits(rng.standard_normal((n, shape.n_kv_heads, shape.head_dim)).astype(np.float32))
+    whole = np.full((need + 3) * P // 2, 0xABCD, np.uint16)
+    oracle.scatter(whole, P, table, k, v)
+    pieces = np.full_like(whole, 0xABCD)
+    for lo, hi in ((0, 7), (7, 8), (8, 20), (20, 23)):
+        before = pieces.copy()
+        oracle.scatter(pieces, P, table, k[lo:hi], v[lo:hi], first_token=lo)
+        ref = before.copy()
+        build_paged_pool(ref, P, table, k[lo:hi], v[lo:hi], first_token=lo)   # element by element, test-side
+        assert np.array_equal(pieces, ref)
+        changed = np.flatnonzero(pieces != before)
+        assert changed.size <= (hi - lo) * shape.token_bytes // 2             # nothing outside the chunk's bytes
+    assert np.array_equal(pieces, whole)
+    gk, gv = oracle.gather(pieces, P, table, shape.n_kv_heads, shape.head_dim, n)
+    assert np.array_equal(gk, k) and np.array_equal(gv, v)
+    # a chunk of one token == the decode step's append of that token
+    b = _OneRequest(shape, 8, table, np.zeros((shape.n_q_heads, shape.head_dim), np.uint16), P)
+    img = np.full_like(whole, 0xABCD)
+    oracle.append(b, img, k[7].reshape(-1), v[7].reshape(-1))
+    one = np.full_like(whole, 0xABCD)
+    oracle.scatter(one, P, table, k[7:8], v[7:8], first_token=7)
+    assert np.array_equal(img, one)
+
+
 def test_oracle_rejects_missing_pages():
     shape = Service(2, 2, 8)
     b = _OneRequest(shape, 20, np.array([0, -1, 1], np.int32), np.zeros((2, 8), np.uint16), 256)
