@@ -178,6 +178,17 @@ int ukv_gather(ukv_pool_t *pool, const ukv_batch_t *batch, void *k_out, void *v_
 int ukv_scatter(ukv_pool_t *pool, const ukv_batch_t *batch, const void *k_in, const void *v_in,
                 const uint64_t *kv_off, void *stream);
 
+/* Bulk append: the store side of chunked prefill (section 2.1: the pass over a chunk of a prompt leaves the
+ * chunk's KV pairs in the cache, behind those of the earlier chunks).  Writes the n_new[i] (HOST) LAST
+ * tokens of request i, i.e. tokens [ctx_len[i] - n_new[i], ctx_len[i]), from contiguous k_in / v_in
+ * DEVICE bf16 [n_new][n_kv_heads][head_dim] at element offset kv_off[i] (HOST, a multiple of 8), bit
+ * for bit; tokens before the chunk are not touched.  n_new[i] = ctx_len[i] is ukv_scatter, n_new[i] = 1
+ * the store of ukv_append, n_new[i] = 0 writes nothing.  UKV_EINVAL if n_new[i] > ctx_len[i].  The
+ * table entries for ceil(ctx_len*T/page_bytes) pages must already be in page_table.
+ * Uses service_id, ctx_len, table_off, page_table. */
+int ukv_scatter_tokens(ukv_pool_t *pool, const ukv_batch_t *batch, const uint32_t *n_new, const void *k_in,
+                       const void *v_in, const uint64_t *kv_off, void *stream);
+
 /* Host-only view of the split-KV plan for a batch (no device work): how the launch would be cut. */
 typedef struct {
     uint32_t n_seqs;        /* (request, head-slice) sequences */

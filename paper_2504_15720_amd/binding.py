@@ -28,6 +28,7 @@ EXPORTS = [
     "ukv_prefill_workspace_bytes", "ukv_prefill_attention",
     "ukv_gather",
     "ukv_scatter",
+    "ukv_scatter_tokens",
     "ukv_plan_decode", "ukv_set_param", "ukv_get_param", "ukv_profile_read", "ukv_strerror", "ukv_last_error",
     "ukv_sched_create", "ukv_sched_destroy", "ukv_sched_add_request", "ukv_sched_next_batch", "ukv_sched_complete",
     "ukv_sched_pages_needed", "ukv_sched_request_info", "ukv_sched_pending",
@@ -117,6 +118,7 @@ def lib():
         L.ukv_prefill_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, C.c_size_t, vp]
         L.ukv_gather.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_scatter.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
+        L.ukv_scatter_tokens.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp, vp]
         L.ukv_plan_decode.argtypes = [vp, C.POINTER(ukv_batch_t), C.POINTER(ukv_plan_info_t), vp, C.c_uint32]
         L.ukv_set_param.argtypes = [vp, C.c_int, C.c_int64]
         L.ukv_get_param.argtypes = [vp, C.c_int, C.POINTER(C.c_int64)]
@@ -257,6 +259,14 @@ def ukv_gather(pool: int, batch: BatchDesc, k_out_ptr: int, v_out_ptr: int, kv_o
 def ukv_scatter(pool: int, batch: BatchDesc, k_in_ptr: int, v_in_ptr: int, kv_off, stream: int = 0) -> None:
     kv_off = np.ascontiguousarray(kv_off, np.uint64)
     _check(lib().ukv_scatter(pool, C.byref(batch.c), k_in_ptr, v_in_ptr, kv_off.ctypes.data, stream), "ukv_scatter")
+
+
+def ukv_scatter_tokens(pool: int, batch: BatchDesc, n_new, k_in_ptr: int, v_in_ptr: int, kv_off,
+                       stream: int = 0) -> None:
+    n_new = np.ascontiguousarray(n_new, np.uint32)
+    kv_off = np.ascontiguousarray(kv_off, np.uint64)
+    _check(lib().ukv_scatter_tokens(pool, C.byref(batch.c), n_new.ctypes.data, k_in_ptr, v_in_ptr, kv_off.ctypes.data,
+                                    stream), "ukv_scatter_tokens")
 
 
 def ukv_plan_decode(pool: int, batch: BatchDesc, want_items: bool = True):

@@ -404,8 +404,10 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
     return stage_release_after(st, s);
 }
 
-static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, void *k_io, void *v_io,
-                       const uint64_t *kv_off, void *stream) {
+// n_last: null = whole requests; else only the n_last[i] last tokens of request i, which is then all
+// that the contiguous arrays hold.
+static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *n_last, void *k_io,
+                       void *v_io, const uint64_t *kv_off, void *stream) {
     if (!p || !b || !k_io || !v_io || !kv_off || !b->page_table) {
         set_error("null argument");
         return UKV_EINVAL;
@@ -426,6 +428,10 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, void *
             set_error("ctx_len exceeds what the pool can hold");
             return UKV_EINVAL;
         }
+        if (n_last && n_last[i] > b->ctx_len[i]) {
+            set_error("n_new exceeds ctx_len");
+            return UKV_EINVAL;
+        }
     }
     hipStream_t s = (hipStream_t)stream;
     // one record (= one workgroup) per chunk of about 1 MiB of a request's stream
@@ -433,9 +439,10 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, void *
     for (uint32_t i = 0; i < n; ++i) {
         const uint32_t T = p->classes.c[b->service_id[i]].token_bytes;
         const uint32_t step = std::max<uint32_t>(1, (1u << 20) / T);
-        for (uint32_t t0 = 0; t0 < b->ctx_len[i]; t0 += step)
+        const uint32_t first = n_last ? b->ctx_len[i] - n_last[i] : 0;
+        for (uint32_t t0 = first; t0 < b->ctx_len[i]; t0 += step)
             chunks.push_back(GatherRec{b->table_off[i], kv_off[i], t0, std::min(b->ctx_len[i], t0 + step),
-                                       b->service_id[i], 0});
+                                       b->service_id[i], first});
     }
     if (chunks.empty())
         return UKV_OK;
@@ -457,12 +464,21 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, void *
 
 int ukv_gather(ukv_pool_t *p, const ukv_batch_t *b, void *k_out, void *v_out, const uint64_t *kv_off,
                void *stream) {
-    return copy_tokens(false, p, b, k_out, v_out, kv_off, stream);
+    return copy_tokens(false, p, b, nullptr, k_out, v_out, kv_off, stream);
 }
 
 int ukv_scatter(ukv_pool_t *p, const ukv_batch_t *b, const void *k_in, const void *v_in, const uint64_t *kv_off,
                 void *stream) {
-    return copy_tokens(true, p, b, const_cast<void *>(k_in), const_cast<void *>(v_in), kv_off, stream);
+    return copy_tokens(true, p, b, nullptr, const_cast<void *>(k_in), const_cast<void *>(v_in), kv_off, stream);
+}
+
+int ukv_scatter_tokens(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *n_new, const void *k_in, const void *v_in,
+                       const uint64_t *kv_off, void *stream) {
+    if (!n_new) {
+        set_error("n_new must be non-null");
+        return UKV_EINVAL;
+    }
+    return copy_tokens(true, p, b, n_new, const_cast<void *>(k_in), const_cast<void *>(v_in), kv_off, stream);
 }
 
 // Prefill work list: one record per (request, kv head, tile of query rows), heaviest first.  Each XCD

@@ -72,7 +72,7 @@ __global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_ba
         const uint64_t off = (uint64_t)t * c.token_bytes + (uint64_t)pc * 16;
         const int32_t pg = page_table[r.table_off + (off >> lg)];
         in_pool = reinterpret_cast<uint4 *>(pool_base + ((uint64_t)(uint32_t)pg << lg) + (off & page_mask));
-        flat = reinterpret_cast<uint4 *>((w < half ? k_io : v_io) + r.kv_off + ((uint64_t)t * c.n_kv + h) * c.d +
+        flat = reinterpret_cast<uint4 *>((w < half ? k_io : v_io) + r.kv_off + ((uint64_t)(t - r.flat_t0) * c.n_kv + h) * c.d +
                                          (w % half) * 8);
     };
     uint64_t idx = threadIdx.x;

@@ -115,10 +115,10 @@ static constexpr uint32_t kPrefillCols = 16 * kPrefillBlocks * kPrefillWaves; //
 
 struct GatherRec { // tokens [t0, t1) of one request
     uint64_t table_off;
-    uint64_t kv_off;
+    uint64_t kv_off;  // element offset of token `flat_t0` in the contiguous arrays
     uint32_t t0, t1;
     uint32_t cls;
-    uint32_t pad_;
+    uint32_t flat_t0; // first token the contiguous arrays hold (0, or the first token of a chunk)
 };
 
 // ---- kernel launchers (ukv_decode.hip, ukv_prefill.hip, ukv_copy.hip) ----

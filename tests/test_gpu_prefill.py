@@ -170,6 +170,48 @@ def test_future_tokens_do_not_leak():
     assert not np.array_equal(got[cut * row:(cut + 1) * row], base[cut * row:(cut + 1) * row])
 
 
+def test_chunked_prefill_bulk_append_then_attention():
+    """Chunked prefill end to end: the chunk's K/V are stored behind the cached tokens (ukv_scatter_tokens,
+    bit for bit against the oracle's image, nothing before the chunk touched), then the chunk's rows attend."""
+    import torch
+    from synth import normal_bf16
+    say("prefill: bulk append of a chunk, then attention")
+    services = [SHAPES["13b"], SHAPES["h12"], SHAPES["70b"], SHAPES["7b"], Service(8, 4, 64)]
+    sid = np.array([0, 1, 2, 3, 4, 0, 1, 2, 3, 4])
+    ctx = np.array([300, 77, 513, 64, 200, 5, 1, 1000, 129, 33])
+    n_new = np.array([100, 77, 1, 0, 37, 5, 1, 257, 128, 32])        # whole prompt, one token, nothing, ...
+    rng = np.random.default_rng(36)
+    b = make_batch(services, sid, ctx, 4096, "permutation", rng, pool_seed=8)
+    db = DeviceBatch(b)
+    try:
+        tok = np.array([b.services[s].n_kv_heads * b.services[s].head_dim for s in sid], np.int64)
+        sizes = n_new * tok
+        kv_off = (np.cumsum(sizes) - sizes).astype(np.uint64)
+        k_bits, v_bits = normal_bf16(int(sizes.sum()), rng), normal_bf16(int(sizes.sum()), rng)
+        expect = b.pool.copy()
+        for i in range(b.n_requests):
+            sv = b.service_of(i)
+            o, m = int(kv_off[i]), int(n_new[i])
+            if m:
+                oracle.scatter(expect, b.page_bytes, b.table_of(i),
+                               k_bits[o:o + m * int(tok[i])].reshape(m, sv.n_kv_heads, sv.head_dim),
+                               v_bits[o:o + m * int(tok[i])].reshape(m, sv.n_kv_heads, sv.head_dim),
+                               first_token=int(ctx[i]) - m)
+        k_t = torch.from_numpy(k_bits.view(np.int16).copy()).to(db.dev)
+        v_t = torch.from_numpy(v_bits.view(np.int16).copy()).to(db.dev)
+        db.scatter_tokens(n_new, k_t, v_t, kv_off)
+        assert np.array_equal(db.pool_host(), expect), "pool image after the bulk append differs"
+        b.pool[:] = expect                                          # the oracle attends over the same image
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, n_new, rng)
+        out_t, _ = db.prefill(n_new, q_bits, q_off, out_off, n_el)
+        _check_rows(b, out_t.cpu().numpy(), q_bits, n_new, q_off, out_off, tag="chunk rows after the bulk append")
+        with pytest.raises(U.UkvError) as e:
+            db.scatter_tokens(ctx + 1, k_t, v_t, kv_off)
+        assert e.value.code == U.UKV_EINVAL                          # more new tokens than tokens
+    finally:
+        db.close()
+
+
 def test_prefill_errors():
     services = [SHAPES["7b"], SHAPES["h12"]]
     rng = np.random.default_rng(35)

@@ -115,6 +115,9 @@ class DeviceBatch:
     def scatter(self, k_t, v_t, kv_off):
         U.ukv_scatter(self.pool, self.desc(), k_t.data_ptr(), v_t.data_ptr(), kv_off, self.stream())
 
+    def scatter_tokens(self, n_new, k_t, v_t, kv_off):
+        U.ukv_scatter_tokens(self.pool, self.desc(), n_new, k_t.data_ptr(), v_t.data_ptr(), kv_off, self.stream())
+
     def gather_device(self):
         kv_off, sizes = self.kv_layout()
         total = int(sizes.sum())
