@@ -28,6 +28,11 @@
  *     a time: calls on the same pool share staging and scratch buffers.
  *   - The library never allocates or frees the pool memory itself.  It owns its host
  *     object, the free list and pinned, device-mapped staging buffers (per-call records).
+ *   - What lives in host memory is checked during the call (service ids, lengths against the
+ *     pool size, page ids of patches, alignment of offsets).  What lives in device memory is
+ *     not: every page id the kernels find in page_table for a request's ceil(n*T/page_bytes)
+ *     pages must be below the pool's page count, and the offset arrays must stay inside the
+ *     caller's q / out / new_k / new_v / page_table allocations.
  *   - There is no CPU fallback: without a usable HIP device the compute calls fail with
  *     UKV_EHIP.
  */
@@ -165,7 +170,10 @@ int ukv_prefill_attention(ukv_pool_t *pool, const ukv_batch_t *batch, const uint
                           size_t ws_bytes, void *stream);
 
 /* Bulk load (also the tests' view of the pool): copy tokens [0, ctx_len[i]) of every request out of the pool into contiguous
- * k_out / v_out DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i] (HOST). */
+ * k_out / v_out DEVICE bf16 [ctx_len][n_kv_heads][head_dim] at element offset kv_off[i] (HOST).
+ * k_out / v_out (and k_in / v_in of the two calls below) may also be pinned host memory that the device
+ * can address (hipHostMalloc): the kernel then moves the bytes over the host link itself, which is how
+ * a preempted or migrating request's cache is swapped out and in (sections 4.2 and 5). */
 int ukv_gather(ukv_pool_t *pool, const ukv_batch_t *batch, void *k_out, void *v_out, const uint64_t *kv_off,
                void *stream);
 

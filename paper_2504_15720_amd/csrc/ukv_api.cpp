@@ -277,7 +277,7 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
     a.new_k = with_append ? (const uint16_t *)b->new_k : nullptr;
     a.new_v = with_append ? (const uint16_t *)b->new_v : nullptr;
 
-    {
+    if (n_spans) {
         ProfPair pp{p, 0};
         if ((rc = pp.get()) != UKV_OK)
             return rc;

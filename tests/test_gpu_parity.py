@@ -302,6 +302,40 @@ def test_migration_gather_then_scatter_into_another_pool():
         bdev.close()
 
 
+def test_swap_out_to_pinned_host_memory_and_back():
+    """Swapping a batch's cache out and in again (a preempted or migrating request, sections 4.2 and 5):
+    ukv_gather writes straight into pinned host memory, the pages are overwritten, ukv_scatter reads the
+    host copy back.  The host copy and the restored pool image are bit-exact against the oracle."""
+    import torch
+    say("swap: gather -> pinned host -> scatter")
+    b = make_config(5, mini=True)
+    db = DeviceBatch(b)
+    try:
+        kv_off, sizes = db.kv_layout()
+        total = int(sizes.sum())
+        hk = torch.zeros(total, dtype=torch.int16).pin_memory()
+        hv = torch.zeros(total, dtype=torch.int16).pin_memory()
+        U.ukv_gather(db.pool, db.desc(), hk.data_ptr(), hv.data_ptr(), kv_off, db.stream())
+        torch.cuda.synchronize()
+        expect = np.full_like(b.pool, 0xDEAD)
+        for i in range(b.n_requests):
+            sv = b.service_of(i)
+            n = int(b.ctx_len[i])
+            gk, gv = oracle.gather(b.pool, b.page_bytes, b.table_of(i), sv.n_kv_heads, sv.head_dim, n)
+            o, e = int(kv_off[i]), int(kv_off[i] + sizes[i])
+            assert np.array_equal(hk.numpy().view(np.uint16)[o:e], gk.reshape(-1)), f"host K copy differs, request {i}"
+            assert np.array_equal(hv.numpy().view(np.uint16)[o:e], gv.reshape(-1)), f"host V copy differs, request {i}"
+            oracle.scatter(expect, b.page_bytes, b.table_of(i), gk, gv)
+        db.pool_t.fill_(np.array(0xDEAD, np.uint16).view(np.int16).item())     # the pages now hold something else
+        U.ukv_scatter(db.pool, db.desc(), hk.data_ptr(), hv.data_ptr(), kv_off, db.stream())
+        assert np.array_equal(db.pool_host(), expect), "restored pool image differs"
+        db.decode()
+        ref = oracle.attention(b, b.pool)
+        assert float(np.max(np.abs(db.out_host().astype(np.float64) - ref))) <= ATOL
+    finally:
+        db.close()
+
+
 def test_many_calls_in_flight_on_a_side_stream():
     """More calls than staging slots are enqueued without synchronising, on a non-default stream;
     every call's output must still be that call's (plans and records are not overwritten early)."""
