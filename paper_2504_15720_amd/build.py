@@ -16,6 +16,9 @@ SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_sched.cpp", "u
            "ukv_copy.hip"]
 # packed fp32 VALU forms are switched off for device code on this target
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# The prefill kernel takes maxima of matrix-instruction results; without this flag every operand of a maximum is
+# first passed through a quieting v_max (its inputs must be finite anyway: see ukv_prefill_attention).
+PER_SOURCE = {"ukv_prefill.hip": ["-fno-honor-nans"]}
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
           "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
@@ -35,7 +38,7 @@ def build_library(verbose: bool = False) -> str:
 
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ_DIR, src + ".o")
-        cmd = [hipcc] + COMMON + DEVICE_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + COMMON + DEVICE_FLAGS + PER_SOURCE.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
@@ -53,18 +56,21 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-CALIB_SRC = os.path.join(HERE, "calib", "hbm_calib.hip")
-CALIB_BIN = os.path.join(HERE, "calib", "hbm_calib")
+CALIB_DIR = os.path.join(HERE, "calib")
+CALIB_PROGRAMS = ["hbm_calib", "mfma_valu_overlap"]
+CALIB_BIN = os.path.join(CALIB_DIR, "hbm_calib")
 
 
 def build_calib() -> str:
-    """The streaming copy/read program used to calibrate the profiler's HBM byte counters."""
+    """The stand-alone measuring programs: the streaming copy/read program that calibrates the profiler's HBM
+    byte counters, and the matrix/vector instruction overlap probe."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument"] + \
-        DEVICE_FLAGS + [CALIB_SRC, "-o", CALIB_BIN]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed on hbm_calib.hip:\n" + r.stdout)
+    for name in CALIB_PROGRAMS:
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument"] + \
+            DEVICE_FLAGS + [os.path.join(CALIB_DIR, name + ".hip"), "-o", os.path.join(CALIB_DIR, name)]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {name}.hip:\n" + r.stdout)
     return CALIB_BIN
 
 

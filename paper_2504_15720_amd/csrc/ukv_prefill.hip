@@ -289,14 +289,28 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 }
                 // Left operand of the product for output rows d = 16 mm + i (lane i of 16): V[token][d] for the
                 // lane's 8 tokens, fetched by two transposing LDS reads (tokens 4q..4q+3 and 16+4q..16+4q+3).
+                // The reads run two groups ahead of the products that use them (the order is pinned below):
+                // issued only when needed, every group of products would wait out a whole LDS round trip.
+                bf16x8_t Vt[MM];
+#pragma unroll
+                for (int mm = 0; mm < MM; ++mm)
+                    Vt[mm] = vt_operand(vt + voff[mm]);
 #pragma unroll
                 for (int mm = 0; mm < MM; ++mm) {
-                    const bf16x8_t Vt = vt_operand(vt + voff[mm]);
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Ph[b], oacc[b][mm], 0, 0, 0);
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt, Pl[b], oacc[b][mm], 0, 0, 0);
+                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Ph[b], oacc[b][mm], 0, 0, 0);
+                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Pl[b], oacc[b][mm], 0, 0, 0);
                     }
+                }
+                constexpr int kAhead = 2; // groups of 16 output rows whose operands are in flight
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0); // LDS reads of the first groups
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);     // the sums of the weights
+#pragma unroll
+                for (int mm = 0; mm < MM; ++mm) {
+                    if (mm + kAhead < MM)
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
                 }
             };
             RowPtrs rows; // row addresses of the tile whose K was requested last
@@ -343,7 +357,12 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0); // keeps the V registers from being loaded before the scores are done with theirs
+                    // A wave that is in its softmax goes first at the instruction issue; one that is in the
+                    // run of matrix instructions below needs an issue slot only now and then.  Two waves of a
+                    // SIMD then tend to be in different phases, so that vector and matrix units both have work.
+                    __builtin_amdgcn_s_setprio(0);
                     pv(v_cur, Ph, Pl);
+                    __builtin_amdgcn_s_setprio(2);
                 }
                 __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the tiles just requested is in LDS
                 __syncthreads(); // they are complete; the arrays just read may be overwritten
