@@ -57,7 +57,7 @@ def build_library(verbose: bool = False) -> str:
 
 
 CALIB_DIR = os.path.join(HERE, "calib")
-CALIB_PROGRAMS = ["hbm_calib", "mfma_valu_overlap"]
+CALIB_PROGRAMS = [("hbm_calib", []), ("mfma_valu_overlap", []), ("mfma_valu_overlap_vgpr", ["-DVGPR_SOURCES"])]
 CALIB_BIN = os.path.join(CALIB_DIR, "hbm_calib")
 
 
@@ -65,9 +65,10 @@ def build_calib() -> str:
     """The stand-alone measuring programs: the streaming copy/read program that calibrates the profiler's HBM
     byte counters, and the matrix/vector instruction overlap probe."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    for name in CALIB_PROGRAMS:
+    for name, extra in CALIB_PROGRAMS:
+        src = name[:-len("_vgpr")] if name.endswith("_vgpr") else name
         cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument"] + \
-            DEVICE_FLAGS + [os.path.join(CALIB_DIR, name + ".hip"), "-o", os.path.join(CALIB_DIR, name)]
+            DEVICE_FLAGS + extra + [os.path.join(CALIB_DIR, src + ".hip"), "-o", os.path.join(CALIB_DIR, name)]
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {name}.hip:\n" + r.stdout)

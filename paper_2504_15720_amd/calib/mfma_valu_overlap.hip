@@ -2,7 +2,7 @@
 // SIMD of gfx950?  Times loops of 16 matrix instructions, of 48 multiply-adds, and of both (interleaved in one
 // wave, one after the other, or in two waves of the same SIMD), with one and with two waves per SIMD.  The
 // prefill kernel's bound on the shared issue port is derived from these figures.
-// Build: hipcc --offload-arch=gfx950 -O3 mfma_valu_overlap.hip -o mfma_valu_overlap ; run without arguments.
+// Build: hipcc --offload-arch=gfx950 -O3 [-DVGPR_SOURCES] mfma_valu_overlap.hip -o mfma_valu_overlap ; run without arguments.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <vector>
@@ -19,7 +19,12 @@ __global__ void __launch_bounds__(512) k(float *out, long long *cyc, int iters) 
     f32x4 c0 = {0, 0, 0, 0}, c1 = c0, c2 = c0, c3 = c0;
     f32x16 w0 = {0}, w1 = w0;
     float x0 = lane, x1 = lane + 1, x2 = lane + 2, x3 = lane + 3, x4 = lane * 0.5f, x5 = lane * 0.25f;
+#ifdef VGPR_SOURCES // every fma reads three vector registers (else one register and two constants)
+    float m = 1.0001f + 1e-9f * lane, d = 0.5f + 1e-9f * lane;
+    asm volatile("" : "+v"(m), "+v"(d));
+#else
     const float m = 1.0001f, d = 0.5f;
+#endif
     const int wave = threadIdx.x / 64;
     // waves are placed round-robin on the 4 SIMDs: waves w and w+4 share a SIMD
     const bool second = wave >= 4;
@@ -96,6 +101,11 @@ int main() {
     CHECK(hipGetDeviceProperties(&prop, 0));
     printf("%s, %d CUs, clock %.0f MHz; one workgroup per CU, a wave per SIMD (256 lanes) or two (512)\n", prop.name,
            prop.multiProcessorCount, prop.clockRate / 1000.0);
+#ifdef VGPR_SOURCES
+    printf("fma with three vector-register sources\n");
+#else
+    printf("fma with one vector-register source and two constants\n");
+#endif
     if (run<0>("16 MFMA", 256, it)) return 1;
     if (run<1>("48 VALU fma", 256, it)) return 1;
     if (run<2>("16 x (MFMA + 3 fma) interleaved", 256, it)) return 1;

@@ -53,7 +53,6 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     // does not depend on the global-to-LDS loads that fill the other, and lets those loads stay in flight.
     __shared__ __align__(16) unsigned char s_k0[kPartBytes], s_k1[kPartBytes];
     __shared__ __align__(16) unsigned char s_v0[kPartBytes], s_v1[kPartBytes];
-    __shared__ __align__(16) uint4 s_q[NB * KSTEPS * NT]; // each lane's own q operands (parked here, not in registers)
     __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
                                              // a workgroup sets how many of them fit a CU)
     if (threadIdx.x == 0) {
@@ -106,6 +105,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     // per block: this lane's column (row, head), its position, and the q operand
     uint32_t col_pos[NB];
     bool col_ok[NB];
+    bf16x8_t qreg[NB][KSTEPS]; // the q operands stay in registers: re-reading them from LDS for every tile cost 3 %
     f32x4_t oacc[NB][MM];
     float m[NB];
     f32x4_t lacc[NB]; // running sums of the weights, every element the same (see pv)
@@ -121,7 +121,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             uint4 w = ld_g16(qp + st * 4);
             if (!col_ok[b])
                 w = make_uint4(0, 0, 0, 0);
-            s_q[(b * KSTEPS + st) * NT + tid] = w; // read back by this lane only
+            qreg[b][st] = as_bf16x8(w);
         }
 #pragma unroll
         for (int mm = 0; mm < MM; ++mm)
@@ -196,8 +196,6 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             };
             // Raw scores S^T = K Q^T of one staged K tile against all NB blocks of the wave.
             auto scores = [&](const unsigned char *kt, f32x4_t (&s0)[NB], f32x4_t (&s1)[NB]) {
-                uint32_t tq = tid; // opaque per tile: keeps the q reads below inside the loop (out of registers)
-                asm volatile("" : "+v"(tq));
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     s0[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
@@ -210,7 +208,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     const u32x4 k1 = *reinterpret_cast<const u32x4 *>(kt + (16 + j) * KB + pc);
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        const bf16x8_t qb = as_bf16x8(s_q[(b * KSTEPS + st) * NT + tq]);
+                        const bf16x8_t qb = qreg[b][st];
                         s0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0), qb, s0[b], 0, 0, 0);
                         s1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1), qb, s1[b], 0, 0, 0);
                     }
