@@ -1,11 +1,11 @@
 """Seeded random batches (services, page sizes, lengths around tile and page-table-window edges) through
-prefill attention and decode attention, against the CPU oracle."""
+prefill attention, decode attention, sequences of decode steps and the bulk copies, against the CPU oracle."""
 import numpy as np
 import pytest
 
 import paper_2504_15720_amd as U
 from synth import SHAPES, Service, draw_prefill_inputs, make_batch
-from tests.test_gpu_parity import _check_attention
+from tests.test_gpu_parity import _check_attention, _check_gather, _decode_steps
 from tests.test_gpu_prefill import _check_rows, say
 from tests.ukv_harness import DeviceBatch
 
@@ -47,6 +47,49 @@ def test_random_batches_match_oracle(seed):
             db.resize_workspace()
             U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, int(rng.choice([16 * 1024, 64 * 1024, 512 * 1024])))
             _check_attention(db, b, f"decode {seed}, block {block}")
+    finally:
+        db.close()
+
+
+STEP_SHAPES = SHAPE_POOL + [Service(2, 1, 64), Service(48, 6, 128)]
+STEP_EDGES = [0, 1, 2, 15, 16, 17] + EDGES
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_step_sequences_match_oracle(seed):
+    """A few decode iterations (new pages from the library's free list, append and attention as two calls, as
+    one launch, or alternating; merge fused or not), then gather, then a chunked scatter of the pool's own
+    last tokens, which must leave the pool image as it is."""
+    rng = np.random.default_rng(5000 + seed)
+    page = int(rng.choice([1024, 2048, 4096, 16384, 65536]))
+    k = int(rng.integers(1, 5))
+    services = [STEP_SHAPES[i] for i in rng.choice(len(STEP_SHAPES), size=k, replace=False)]
+    n = int(rng.integers(1, 12))
+    sid = rng.integers(0, k, size=n)
+    ctx = rng.integers(0, 600 if page <= 2048 else 1400, size=n)
+    for i in range(n):
+        if rng.random() < 0.35:
+            ctx[i] = int(rng.choice(STEP_EDGES))
+    steps = int(rng.integers(2, 7))
+    reserve = steps * 3 + 2
+    need = sum(-(-(int(c) + reserve) * services[int(s)].token_bytes // page) for c, s in zip(ctx, sid))
+    say(f"random steps {seed}: page {page}, ctx {ctx.tolist()}, steps {steps}")
+    b = make_batch(services, sid, ctx, int(need * 1.2) + 64, "permutation", rng, page_bytes=page, pool_seed=seed,
+                   reserve_tokens=reserve)
+    db = DeviceBatch(b)
+    try:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_BLOCK_THREADS, int(rng.choice([256, 512])))
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, int(rng.choice([16 * 1024, 64 * 1024, 512 * 1024])))
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, int(rng.choice([0, 1])))
+        db.resize_workspace()
+        _decode_steps(db, b, steps, seed=seed, fused=str(rng.choice(["no", "yes", "alternate"])))
+        _check_gather(db, b)
+        k_t, v_t, kv_off, _ = db.gather_device()
+        n_new = np.array([int(rng.integers(0, c + 1)) for c in b.ctx_len], np.uint32)
+        tok = np.array([b.services[s].n_kv_heads * b.services[s].head_dim for s in b.service_id], np.int64)
+        first = (kv_off.astype(np.int64) + (b.ctx_len.astype(np.int64) - n_new) * tok).astype(np.uint64)
+        db.scatter_tokens(n_new, k_t, v_t, first)
+        assert np.array_equal(db.pool_host(), b.pool), "chunked scatter of the pool's own tokens changed the pool"
     finally:
         db.close()
 
