@@ -464,7 +464,7 @@ def main():
                            "grow + append + attention (one launch)",
                    "layout": args.layout, "block_table_entries": int(b.pages_owned().sum()),
                    "pages_in_use": int(b.stack.used_pages),
-                   "internal_waste_bytes": int(b.pages_owned().sum()) * int(b.page_bytes) - int(kv_per_step),
+                   "internal_waste_bytes": int(b.pages_owned().sum()) * int(b.page_bytes) - int(b.kv_bytes()),
                    "kv_storage": "bf16", "decode_workgroups": info.n_spans, "work_items": info.n_items,
                    "block_threads": U.ukv_get_param(db.pool, U.UKV_PARAM_BLOCK_THREADS)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),

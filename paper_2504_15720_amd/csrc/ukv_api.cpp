@@ -87,9 +87,14 @@ struct ProfPair {
         ev.which = which;
         return UKV_OK;
     }
-    void done() {
+    void done() { // the launch went out: the pair now waits for ukv_profile_read
         if (ev.a)
             p->ev_used.push_back(ev);
+        ev.a = ev.b = nullptr;
+    }
+    ~ProfPair() { // the launch failed: the pair was never recorded and can be handed out again
+        if (ev.a)
+            p->ev_free.push_back(ev);
     }
 };
 
