@@ -505,7 +505,7 @@ static size_t prefill_rec_bound(const ukv_pool *p, uint32_t n_requests, uint64_t
 size_t ukv_prefill_workspace_bytes(const ukv_pool_t *p, uint32_t n_requests, uint64_t total_q_rows) {
     if (!p)
         return 0;
-    return align_up(sizeof(ClassTable)) + align_up(prefill_rec_bound(p, n_requests, total_q_rows) * sizeof(PrefillRec));
+    return align_up(prefill_rec_bound(p, n_requests, total_q_rows) * sizeof(PrefillRec));
 }
 
 int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q_len, void *workspace,
@@ -596,6 +596,10 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 r.cls = b->service_id[i];
                 r.kvh = g.kvh;
                 r.r0 = t * rows;
+                r.g = c.g;
+                r.n_q = c.n_q;
+                r.token_bytes = c.token_bytes;
+                r.scale_log2e = c.scale_log2e;
                 queue[k].push_back(r);
             }
         }
@@ -608,8 +612,7 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 list[di][e * n_queues + k] = queue[k][e];
     }
     const size_t n_recs = list[0].size() + list[1].size();
-    const size_t off_recs = align_up(sizeof(ClassTable));
-    const size_t total = align_up(off_recs + n_recs * sizeof(PrefillRec));
+    const size_t total = align_up(n_recs * sizeof(PrefillRec)); // the records carry what they need of their class
     if (total > ws_bytes) {
         set_error("workspace too small for this batch");
         return UKV_ENOSPC;
@@ -619,8 +622,7 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
     unsigned char *h = (unsigned char *)st->host;
-    std::memcpy(h, &p->classes, sizeof(ClassTable));
-    PrefillRec *recs = (PrefillRec *)(h + off_recs);
+    PrefillRec *recs = (PrefillRec *)h;
     if (!list[0].empty())
         std::memcpy(recs, list[0].data(), list[0].size() * sizeof(PrefillRec));
     if (!list[1].empty())
@@ -636,12 +638,11 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     a.page_table = b->page_table;
     a.q = (const uint16_t *)b->q;
     a.out = (float *)b->out;
-    a.classes = (const ClassRec *)w;
     size_t first = 0;
     for (int di = 0; di < 2; ++di) {
         if (list[di].empty())
             continue;
-        a.recs = (const PrefillRec *)(w + off_recs) + first;
+        a.recs = (const PrefillRec *)w + first;
         ProfPair pp{p, 3};
         if ((rc = pp.get()) != UKV_OK)
             return rc;

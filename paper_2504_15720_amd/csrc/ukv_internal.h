@@ -96,7 +96,10 @@ struct PrefillRec {
     uint32_t cls;
     uint32_t kvh;
     uint32_t r0;      // first query row of the tile
-    uint32_t pad_[5]; // q_len == 0: filler workgroup (keeps the XCD interleave regular)
+    // what the kernel needs of the service's class, copied here so that a workgroup starts with one load
+    uint32_t g, n_q, token_bytes;
+    float scale_log2e;
+    uint32_t pad_[1]; // q_len == 0: filler workgroup (keeps the XCD interleave regular)
 };
 static_assert(sizeof(PrefillRec) == 64, "PrefillRec layout");
 
@@ -106,7 +109,6 @@ struct PrefillArgs {
     const int32_t *page_table;
     const uint16_t *q; // bf16
     float *out;
-    const ClassRec *classes;
     const PrefillRec *recs;
 };
 static constexpr uint32_t kPrefillBlocks = 2; // 16-column blocks per wave

@@ -48,26 +48,23 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     static_assert(KI >= 1, "too many waves for this head_dim");
     constexpr uint32_t kPartBytes = 32 * KB; // the K rows (or the V rows) of a 32-token tile
     __shared__ PrefillRec s_rec;
-    __shared__ ClassRec s_cls;
     // Two staged tiles, one array each: with distinct arrays the compiler can tell that reading one tile
     // does not depend on the global-to-LDS loads that fill the other, and lets those loads stay in flight.
     __shared__ __align__(16) unsigned char s_k0[kPartBytes], s_k1[kPartBytes];
     __shared__ __align__(16) unsigned char s_v0[kPartBytes], s_v1[kPartBytes];
     __shared__ int32_t s_ptab[kPfTabWindow]; // page-table window (smaller than the decode path's: the LDS of
                                              // a workgroup sets how many of them fit a CU)
-    if (threadIdx.x == 0) {
+    if (threadIdx.x == 0)
         s_rec = a.recs[blockIdx.x];
-        s_cls = a.classes[s_rec.cls];
-    }
     __syncthreads();
     const uint32_t q_len = uni(s_rec.q_len);
     if (q_len == 0)
         return; // filler
     const uint64_t table_off = uni(s_rec.table_off), q_off = uni(s_rec.q_off), out_off = uni(s_rec.out_off);
     const uint32_t ctx_len = uni(s_rec.ctx_len), kvh = uni(s_rec.kvh), r0 = uni(s_rec.r0);
-    const uint32_t G = uni(s_cls.g), n_q = uni(s_cls.n_q);
-    const uint64_t T = uni(s_cls.token_bytes);
-    const float scale_log2e = uni(s_cls.scale_log2e);
+    const uint32_t G = uni(s_rec.g), n_q = uni(s_rec.n_q);
+    const uint64_t T = uni(s_rec.token_bytes);
+    const float scale_log2e = uni(s_rec.scale_log2e);
     int32_t *tab = s_ptab;
 
     const int tid = threadIdx.x, lane = tid & 63;
