@@ -356,6 +356,8 @@ def main():
     ap.add_argument("--layout", choices=["merged", "split"], default="merged",
                     help="split = one block stream and table per (request, kv head), the alternative of section 4.4")
     ap.add_argument("--split-page-bytes", type=int, default=0, help="block size of the split layout")
+    ap.add_argument("--as-stated-pool", action="store_true",
+                    help="keep the pool at the workload's stated size and admit requests in draw order while pages remain")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="skip grow+append in the step (diagnostic)")
     ap.add_argument("--time-every", type=int, default=4,
@@ -381,7 +383,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     t_gen = time.perf_counter()
     # tables must have room for every step's new token
-    b = make_config(args.config, reserve_tokens=args.steps + args.warmup + 1, fill_pool=args.layout == "merged")
+    b = make_config(args.config, reserve_tokens=args.steps + args.warmup + 1, fill_pool=args.layout == "merged",
+                    as_stated=args.as_stated_pool)
     if args.layout == "split":
         from synth import to_split_layout
         b = to_split_layout(b, pool_seed=7, page_bytes=args.split_page_bytes or None)
@@ -456,7 +459,9 @@ def main():
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[args.config], "n_requests": b.n_requests,
+        "config": {"workload": WORKLOAD_NAMES[args.config] + (", pool as stated: requests admitted in draw order while pages remain"
+                                                              if args.as_stated_pool else ""),
+                   "n_requests": b.n_requests, "drawn_requests": b.notes.get("drawn_requests", b.n_requests),
                    "kv_bytes_per_step": int(kv_per_step), "pool_pages": b.n_pages,
                    "stated_pool_pages": b.notes.get("stated_pages"), "page_bytes": b.page_bytes,
                    "step": "attention only" if args.attention_only else

@@ -398,11 +398,14 @@ CONFIGS: Dict[int, dict] = {
 
 
 def make_config(index: int, *, mini: bool = False, fill_pool: bool = True, seed: Optional[int] = None,
-                reserve_tokens: Optional[int] = None) -> Batch:
+                reserve_tokens: Optional[int] = None, as_stated: bool = False) -> Batch:
     """Draw workload `index` (1..5).  mini=True shrinks counts and lengths, same recipe.
 
     reserve_tokens: table entries are reserved for this many future tokens per request
-    (default: the workload's own decode steps, at least 4)."""
+    (default: the workload's own decode steps, at least 4).
+    as_stated: keep the pool at the size the workload states even where the drawn batch does not fit, and
+    admit the requests in draw order while pages remain (the admission gate of the paper's scheduler,
+    appendix algorithm: a request only joins the batch if the block manager has room for it)."""
     c = dict(CONFIGS[index])
     if mini:
         c.update(c["mini"])
@@ -421,7 +424,15 @@ def make_config(index: int, *, mini: bool = False, fill_pool: bool = True, seed:
     tb = np.array([s.token_bytes for s in services], dtype=np.int64)[sid]
     need = int(pages_for_tokens(lens + c["steps"], tb).sum())
     notes = {"stated_pages": c.get("stated_pages", c["n_pages"])}
-    if need > n_pages and "grow_pool_if_needed" in c and not mini:
+    notes["drawn_requests"] = n
+    if as_stated and not mini:
+        n_pages = notes["stated_pages"]
+        keep_tokens = max(c["steps"], 4) if reserve_tokens is None else reserve_tokens
+        per_req = pages_for_tokens(lens + keep_tokens, tb)  # what a request may hold by the end of the run
+        admitted = int(np.searchsorted(np.cumsum(per_req), n_pages, side="right"))
+        sid, lens, tb = sid[:admitted], lens[:admitted], tb[:admitted]
+        need = int(pages_for_tokens(lens + c["steps"], tb).sum())
+    elif need > n_pages and "grow_pool_if_needed" in c and not mini:
         n_pages = c["grow_pool_if_needed"]
     notes["pages_needed"] = need
     churn = dict(mix=mix, law=c["law"]) if c["churn"] else None

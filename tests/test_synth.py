@@ -79,3 +79,24 @@ def test_grow_one_token_allocates_when_a_page_boundary_is_crossed():
         after = b.pages_owned()
         assert ids.size == int((after - before).sum())
         assert np.array_equal(b.page_table[entry.astype(np.int64)], ids)
+
+
+def test_as_stated_pool_admits_a_prefix_that_fits():
+    """Workloads whose stated pool is smaller than the drawn batch: with as_stated the pool keeps the stated size
+    and the requests are admitted in draw order while pages remain."""
+    for cfg in (1, 2, 3):
+        full = make_config(cfg, fill_pool=False)
+        b = make_config(cfg, fill_pool=False, as_stated=True)
+        assert b.n_pages == b.notes["stated_pages"] < full.n_pages
+        assert 0 < b.n_requests < full.n_requests == b.notes["drawn_requests"]
+        n = b.n_requests
+        assert np.array_equal(b.ctx_len, full.ctx_len[:n]) and np.array_equal(b.service_id, full.service_id[:n])
+        assert int(b.pages_owned().sum()) <= b.n_pages
+        # with room for the tokens the run will add, the admitted requests fit and one more would not
+        reserve = int(b.notes["reserve_tokens"])
+        tb = np.array([s.token_bytes for s in full.services], np.int64)[full.service_id]
+        held = np.cumsum(pages_for_tokens(full.ctx_len + reserve, tb, full.page_bytes))
+        assert held[n - 1] <= b.n_pages < held[n]
+    for cfg in (4, 5):  # these fit as stated: nothing changes
+        a, b = make_config(cfg, fill_pool=False, mini=True), make_config(cfg, fill_pool=False, mini=True, as_stated=True)
+        assert a.n_requests == b.n_requests and a.n_pages == b.n_pages
