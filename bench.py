@@ -483,6 +483,9 @@ def main():
                      "traffic_over_algorithmic": read_traffic(args.config)[1]},
         "setup_s": round(t_gen, 1),
     }
+    if kv_per_step < 256e6:  # smaller than the 256 MB of last-level cache: the launch never goes to HBM
+        line["note"] = "working set is cache resident: the GB/s here is not an HBM figure (launch-bound workload)"
+        line["roofline"]["note"] = "cache resident, not HBM"
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(b, int(kv_per_step), one_thread=args.config in (1, 2))
         line["cpu_baseline"]["value"] = round(line["cpu_baseline"]["value"], 4)
