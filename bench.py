@@ -466,7 +466,8 @@ def main():
                    "stated_pool_pages": b.notes.get("stated_pages"), "page_bytes": b.page_bytes,
                    "step": "attention only" if args.attention_only else
                            "grow + append + attention (two launches)" if args.separate_append else
-                           "grow + append + attention (one launch)",
+                           "grow + append + attention (one launch)" if U.ukv_get_param(db.pool, U.UKV_PARAM_FUSED_MERGE) else
+                           "grow + append + attention (one launch) + merge of split partials (second launch)",
                    "layout": args.layout, "block_table_entries": int(b.pages_owned().sum()),
                    "pages_in_use": int(b.stack.used_pages),
                    "internal_waste_bytes": int(b.pages_owned().sum()) * int(b.page_bytes) - int(b.kv_bytes()),

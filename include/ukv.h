@@ -218,7 +218,8 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
 #define UKV_PARAM_PROFILE 5          /* 0 = off; n >= 1 = time every n-th launch of each kernel with HIP events (see
                                         ukv_profile_read).  A timed launch costs about 10 us of stream time. */
-#define UKV_PARAM_FUSED_MERGE 6      /* 1 (default) = merge partials inside the decode launch; 0 = second launch */
+#define UKV_PARAM_FUSED_MERGE 6      /* 1 = merge partials inside the decode launch; 0 = second launch (default: 1, and
+                                        0 where every service has d = 128 and g > 1) */
 #define UKV_PARAM_SLOTS 7            /* decode workgroups resident at once; 0 (default) = ask the device */
 #define UKV_PARAM_GQA_COST_PCT 9     /* planner cost of a KV byte of a matrix-core service (d = 128, g > 1), in percent of
                                         a byte of the other kinds (default 150, measured on mixed batches) */

@@ -130,12 +130,15 @@ int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out) {
     int rc = derive_classes(p);
     if (rc == UKV_OK) {
         // A pool whose services all run on the matrix-core path does better with four waves (four
-        // kv heads) per workgroup: smaller partials and twice the workgroups in flight.
+        // kv heads) per workgroup: smaller partials and twice the workgroups in flight.  Its partials
+        // are G times larger than those of the other kinds, and merging them in a second launch was
+        // measured faster than inside the decode launch (2 % of the step on the GQA workload).
         bool all_gqa = true;
         for (uint32_t s = 0; s < p->n_services; ++s)
             all_gqa = all_gqa && p->classes.c[s].kind == kD128GQA;
         if (all_gqa) {
             p->tun.block_threads = 256;
+            p->tun.fused_merge = 0;
             rc = derive_classes(p);
         }
     }

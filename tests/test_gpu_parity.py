@@ -88,6 +88,7 @@ def test_mini_configs_match_oracle(cfg, block):
         _check_attention(db, b, "whole-request items")
         _check_gather(db, b)
         U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 48 * 1024)      # many cuts -> merge of partials
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)                 # (the default except for all-GQA pools)
         _check_attention(db, b, "cut into many items, merge fused into the decode launch")
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
         _check_attention(db, b, "cut into many items, merge in a second launch")

@@ -221,7 +221,9 @@ def test_params_roundtrip_and_validation():
     p = _pool([SHAPES["8b"], SHAPES["70b"]])
     assert U.ukv_get_param(p, U.UKV_PARAM_BLOCK_THREADS) == 256
     assert U.ukv_pool_info(p, 1).heads_per_slice == 4
+    assert U.ukv_get_param(p, U.UKV_PARAM_FUSED_MERGE) == 0       # ... and merge their (large) partials in a second launch
     U.ukv_pool_destroy(p)
     p = _pool([SHAPES["8b"], SHAPES["7b"]])
     assert U.ukv_get_param(p, U.UKV_PARAM_BLOCK_THREADS) == 512
+    assert U.ukv_get_param(p, U.UKV_PARAM_FUSED_MERGE) == 1
     U.ukv_pool_destroy(p)
