@@ -93,6 +93,8 @@ PREFILL_WORKLOADS = {
     "chat": (("7b", "8b"), (0.5, 0.5), dict(kind="lognormal", median=1024, sigma=0.8, max=8192), 32, 1 << 17),
     "summarize": (("7b", "70b"), (0.5, 0.5), dict(kind="lognormal", median=13000, sigma=0.25, max=20000), 6,
                   1 << 17),
+    # the head_dim 64 instantiation of the kernel (the 12-head service of the four-service workload)
+    "small-heads": (("h12",), (1.0,), dict(kind="lognormal", median=4096, sigma=0.4, max=8192), 24, 1 << 17),
 }
 
 
