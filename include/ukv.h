@@ -26,6 +26,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
  *     work and return without synchronising.  One pool must be driven from one stream at
  *     a time: calls on the same pool share staging and scratch buffers.
+ *   - The compute calls do host work at call time (they plan the launch from the host arrays and write the
+ *     per-call records into a staging slot), so a call recorded into a HIP graph would replay the batch it
+ *     was recorded with; they are meant to be called, not captured.
  *   - The library never allocates or frees the pool memory itself.  It owns its host
  *     object, the free list and pinned, device-mapped staging buffers (per-call records).
  *   - What lives in host memory is checked during the call (service ids, lengths against the
