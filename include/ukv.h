@@ -216,7 +216,8 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 
 /* Tunables (integers).  Setting one never changes results beyond fp32 summation order. */
 #define UKV_PARAM_MAX_SPANS 1        /* upper limit of decode workgroups per launch */
-#define UKV_PARAM_MIN_SPAN_BYTES 2   /* do not cut spans smaller than this many KV bytes (default 512 KiB) */
+#define UKV_PARAM_MIN_SPAN_BYTES 2   /* do not cut spans smaller than this many KV bytes (default 512 KiB; until it is
+                                        set, batches too small to fill the device that way are cut down to 64 KiB) */
 #define UKV_PARAM_BLOCK_THREADS 3    /* 256 or 512 (default 512; 256 where every service has d = 128 and g > 1) */
 #define UKV_PARAM_HEADS_PER_SLICE 4  /* 0 = automatic; else forced where it divides n_kv_heads */
 #define UKV_PARAM_PROFILE 5          /* 0 = off; n >= 1 = time every n-th launch of each kernel with HIP events (see

@@ -160,6 +160,7 @@ struct Plan {
 struct Tunables {
     int64_t max_spans = 2048;
     int64_t min_span_bytes = 512 * 1024;
+    bool min_span_auto = true; // until the caller sets it: small batches get smaller spans (see build_plan)
     int64_t block_threads = 512;
     int64_t heads_per_slice = 0;
     int64_t profile = 0;

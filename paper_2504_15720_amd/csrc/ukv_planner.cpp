@@ -11,6 +11,7 @@ namespace ukv {
 static constexpr uint64_t kItemOverheadBytes = 16 * 1024; // q load, merge and output, as KV bytes
 static constexpr uint64_t kMinItemTokens = 16;
 static constexpr uint64_t kDefaultTaperPct = 88;
+static constexpr uint64_t kSmallBatchSpanBytes = 64 * 1024;
 
 // partials of different items never share a 128-byte line
 static uint32_t part_stride_of(const ClassRec &c) { return (c.hs * c.g * (c.d + 2) + 31u) & ~31u; }
@@ -117,8 +118,14 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
     // the first round's uneven finish leaves is evened out by the small rounds after it.
     std::vector<uint64_t> targets;
     {
-        const uint64_t min_span = (uint64_t)p->tun.min_span_bytes, max_spans = (uint64_t)p->tun.max_spans;
+        const uint64_t max_spans = (uint64_t)p->tun.max_spans;
         const uint64_t slots = (uint64_t)std::max<int64_t>(1, p->tun.slots);
+        // A batch too small to give every resident workgroup min_span_bytes is latency-bound, not
+        // bandwidth-bound: it is cut finer (down to 64 KiB a span), so that more CUs share the tokens of each
+        // request (8 requests of a few hundred tokens: 12 -> 118 workgroups, 19 -> 12 us).
+        uint64_t min_span = (uint64_t)p->tun.min_span_bytes;
+        if (p->tun.min_span_auto)
+            min_span = std::max<uint64_t>(std::min<uint64_t>(min_span, total_cost / slots), kSmallBatchSpanBytes);
         if (!p->tun.taper) {
             uint64_t n = std::max<uint64_t>(1, std::min<uint64_t>(total_cost / min_span, max_spans));
             targets.assign(1, (total_cost + n - 1) / n);

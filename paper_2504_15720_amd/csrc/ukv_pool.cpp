@@ -253,6 +253,7 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
         if (value < 1)
             return fail(UKV_EINVAL, "min_span_bytes must be positive");
         p->tun.min_span_bytes = value;
+        p->tun.min_span_auto = false;
         return UKV_OK;
     case UKV_PARAM_BLOCK_THREADS:
         if (value != 256 && value != 512)
