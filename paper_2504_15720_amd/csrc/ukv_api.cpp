@@ -290,11 +290,11 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
                 "launch decode kernel");
         pp.done();
     }
-    if (!fused && !plan.reduce.empty()) {
+    if (!plan.reduce.empty()) { // every cut sequence (two-launch mode), or only those with very many parts
         ProfPair pp{p, 1};
         if ((rc = pp.get()) != UKV_OK)
             return rc;
-        HIP_TRY(launch_reduce((const ReduceRec *)(w + L.reduce), (uint32_t)plan.reduce.size(),
+        HIP_TRY(launch_reduce((const ReduceRec *)(w + L.reduce), (uint32_t)plan.reduce.size(), plan.n_reduce_many,
                               plan.max_reduce_heads, a.partials, a.out, s, pp.ev.a, pp.ev.b),
                 "launch reduce kernel");
         pp.done();

@@ -275,7 +275,7 @@ template <int NT>
 __device__ __forceinline__ void finish_item(const DecodeArgs &a, const SeqRec &s, const Item &it, uint32_t n_heads,
                                             uint32_t D, uint32_t q_head0, uint32_t layout_g, int32_t *tab,
                                             float *mbuf) {
-    if (it.part == kDirect || a.counters == nullptr)
+    if (it.part == kDirect || a.counters == nullptr || !merges_in_launch(s.n_parts, s.part_stride))
         return;
     __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this lane's partial stores have completed
     __syncthreads();
@@ -772,41 +772,120 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
     }
 }
 
-// One 64-lane workgroup per (cut sequence, query head): out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M).
-__global__ void __launch_bounds__(64) reduce_kernel(const ReduceRec *recs, const float *partials, float *out) {
+// The merge as a launch of its own, one workgroup per (cut sequence, query head):
+//   out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M).
+// MANY = false: a sequence of a few parts, merged by one wave, part after part.  MANY = true: a sequence of many
+// parts (one long request alone on the device is cut into hundreds), where that would be a chain of hundreds of
+// dependent round trips: the (m, l) pairs are fetched by all lanes at once, the weights are worked out in LDS,
+// and four waves share the parts, each with several accumulator rows in flight.
+static constexpr uint32_t kReduceWaves = 4, kReduceChunk = 1024, kReduceAhead = 8;
+template <bool MANY>
+__global__ void __launch_bounds__(MANY ? 64 * kReduceWaves : 64) reduce_kernel(const ReduceRec *recs, const float *partials,
+                                                                              float *out) {
     const ReduceRec r = recs[blockIdx.x];
     const uint32_t hq = blockIdx.y;
     if (hq >= r.n_heads)
         return;
     const float *base = partials + r.part_off;
     const uint32_t ml_off = r.n_heads * r.d + hq * 2;
-    const uint32_t lane = threadIdx.x;
-    float M = -INFINITY;
-    for (uint32_t c = 0; c < r.n_parts; ++c) {
-        const float *p = base + (uint64_t)c * r.part_stride + ml_off;
-        if (p[1] > 0.f)
-            M = fmaxf(M, p[0]);
-    }
-    float L = 0.f, o0 = 0.f, o1 = 0.f;
-    const bool two = r.d > 64;
-    for (uint32_t c = 0; c < r.n_parts; ++c) {
-        const float *pc = base + (uint64_t)c * r.part_stride;
-        const float mc = pc[ml_off], lc = pc[ml_off + 1];
-        if (!(lc > 0.f))
-            continue;
-        const float w = fast_exp2(mc - M);
-        L = fmaf(lc, w, L);
-        if (lane < r.d)
-            o0 = fmaf(pc[part_pair_off(r.layout_g, r.d, hq, lane >> 2, (lane >> 1) & 1) + (lane & 1)], w, o0);
-        if (two)
-            o1 = fmaf(pc[part_pair_off(r.layout_g, r.d, hq, (64 + lane) >> 2, (lane >> 1) & 1) + (lane & 1)], w, o1);
-    }
-    const float inv = L > 0.f ? 1.f / L : 0.f;
+    const uint32_t tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const bool one = lane < r.d, two = r.d > 64;
+    // this lane's output elements are lane and 64 + lane: where they sit inside a part
+    const uint32_t off0 = part_pair_off(r.layout_g, r.d, hq, lane >> 2, (lane >> 1) & 1) + (lane & 1);
+    const uint32_t off1 = part_pair_off(r.layout_g, r.d, hq, (64 + lane) >> 2, (lane >> 1) & 1) + (lane & 1);
     float *dst = out + r.out_off + (uint64_t)hq * r.d;
-    if (lane < r.d)
-        dst[lane] = o0 * inv;
-    if (two)
-        dst[64 + lane] = o1 * inv;
+    if (!MANY) {
+        float M = -INFINITY;
+        for (uint32_t c = 0; c < r.n_parts; ++c) {
+            const float *p = base + (uint64_t)c * r.part_stride + ml_off;
+            if (p[1] > 0.f)
+                M = fmaxf(M, p[0]);
+        }
+        float L = 0.f, o0 = 0.f, o1 = 0.f;
+        for (uint32_t c = 0; c < r.n_parts; ++c) {
+            const float *pc = base + (uint64_t)c * r.part_stride;
+            const float mc = pc[ml_off], lc = pc[ml_off + 1];
+            if (!(lc > 0.f))
+                continue;
+            const float w = fast_exp2(mc - M);
+            L = fmaf(lc, w, L);
+            if (one)
+                o0 = fmaf(pc[off0], w, o0);
+            if (two)
+                o1 = fmaf(pc[off1], w, o1);
+        }
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        if (one)
+            dst[lane] = o0 * inv;
+        if (two)
+            dst[64 + lane] = o1 * inv;
+        return;
+    }
+    __shared__ float s_m[kReduceChunk], s_l[kReduceChunk];
+    __shared__ float s_red[kReduceWaves], s_o[kReduceWaves][128], s_L[kReduceWaves];
+    float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f; // M is the same in every lane of the workgroup; L, o0, o1 are this wave's shares
+    for (uint32_t c0 = 0; c0 < r.n_parts; c0 += kReduceChunk) { // workgroup-uniform
+        const uint32_t nc = min(kReduceChunk, r.n_parts - c0);
+        float mx = -INFINITY;
+        for (uint32_t c = tid; c < nc; c += 64 * kReduceWaves) {
+            const float2 ml = *reinterpret_cast<const float2 *>(base + (uint64_t)(c0 + c) * r.part_stride + ml_off);
+            const bool live = ml.y > 0.f; // an empty part carries no weight
+            s_m[c] = live ? ml.x : -INFINITY;
+            s_l[c] = live ? ml.y : 0.f;
+            mx = fmaxf(mx, s_m[c]);
+        }
+        for (int o = 32; o > 0; o >>= 1)
+            mx = fmaxf(mx, __shfl_xor(mx, o));
+        if (lane == 0)
+            s_red[wave] = mx;
+        __syncthreads();
+        float Mn = M;
+        for (uint32_t w = 0; w < kReduceWaves; ++w)
+            Mn = fmaxf(Mn, s_red[w]);
+        const float Ms = Mn == -INFINITY ? 0.f : Mn;
+        const float keep = fast_exp2(M - Ms); // what the sums so far are worth against the new maximum
+        L *= keep;
+        o0 *= keep;
+        o1 *= keep;
+        M = Mn;
+        for (uint32_t c = wave * kReduceAhead; c < nc; c += kReduceWaves * kReduceAhead) { // wave-uniform
+            float x0[kReduceAhead], x1[kReduceAhead];
+#pragma unroll
+            for (uint32_t k = 0; k < kReduceAhead; ++k) {
+                const float *pc = base + (uint64_t)(c0 + min(c + k, nc - 1)) * r.part_stride;
+                x0[k] = one && c + k < nc ? pc[off0] : 0.f;
+                x1[k] = two && c + k < nc ? pc[off1] : 0.f;
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < kReduceAhead; ++k) {
+                if (c + k >= nc)
+                    break;
+                const float w = fast_exp2(s_m[c + k] - Ms);
+                L = fmaf(s_l[c + k], w, L);
+                o0 = fmaf(x0[k], w, o0);
+                o1 = fmaf(x1[k], w, o1);
+            }
+        }
+        __syncthreads(); // s_m, s_l and s_red are rewritten by the next chunk
+    }
+    s_o[wave][lane] = o0;
+    s_o[wave][64 + lane] = o1;
+    if (lane == 0)
+        s_L[wave] = L;
+    __syncthreads();
+    if (wave == 0) {
+        float Lt = 0.f, t0 = 0.f, t1 = 0.f;
+        for (uint32_t w = 0; w < kReduceWaves; ++w) {
+            Lt += s_L[w];
+            t0 += s_o[w][lane];
+            t1 += s_o[w][64 + lane];
+        }
+        const float inv = Lt > 0.f ? 1.f / Lt : 0.f;
+        if (one)
+            dst[lane] = t0 * inv;
+        if (two)
+            dst[64 + lane] = t1 * inv;
+    }
 }
 
 // ------------------------------------------------------------------ launchers
@@ -835,11 +914,18 @@ hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_t
     return hipGetLastError();
 }
 
-hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,
-                         float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+// recs: the n_many sequences of many parts first, then the others; ev0/ev1 bracket both launches.
+hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads,
+                         const float *partials, float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
-    hipExtLaunchKernelGGL(reduce_kernel, dim3(n_recs, max_heads), dim3(64), 0, s, ev0, ev1, 0, recs, partials, out);
+    const uint32_t n_few = n_recs - n_many;
+    if (n_many)
+        hipExtLaunchKernelGGL(reduce_kernel<true>, dim3(n_many, max_heads), dim3(64 * kReduceWaves), 0, s, ev0,
+                              n_few ? nullptr : ev1, 0, recs, partials, out);
+    if (n_few)
+        hipExtLaunchKernelGGL(reduce_kernel<false>, dim3(n_few, max_heads), dim3(64), 0, s, n_many ? nullptr : ev0, ev1, 0,
+                              recs + n_many, partials, out);
     return hipGetLastError();
 }
 

@@ -35,6 +35,16 @@ struct Item {
     uint32_t seq, t0, t1, part;
 };
 static constexpr uint32_t kDirect = 0xffffffffu;
+// A sequence whose partials add up to more than this many floats (256 KiB) is never merged inside the decode
+// launch: one workgroup walking that much is a long serial chain (hundreds of microseconds for a long request
+// alone on the device); the second launch spreads the work over (query head, part) instead.
+static constexpr uint64_t kFusedMergeMaxFloats = 64 * 1024;
+__host__ __device__ inline bool merges_in_launch(uint32_t n_parts, uint32_t part_stride) {
+    return (uint64_t)n_parts * part_stride <= kFusedMergeMaxFloats;
+}
+// The second launch takes sequences of up to this many parts with one wave per (sequence, query head), part
+// after part, and longer ones with four waves that share the parts.
+static constexpr uint32_t kReduceFewParts = 24;
 
 // Per-service constants used by the kernels.
 struct ClassRec {
@@ -130,8 +140,8 @@ hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, in
                              hipStream_t s);
 hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1);
-hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t max_heads, const float *partials,
-                         float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads,
+                         const float *partials, float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s);
 hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,
@@ -149,7 +159,8 @@ struct Plan {
     std::vector<SeqRec> seqs;
     std::vector<Item> items;
     std::vector<uint32_t> span_first;
-    std::vector<ReduceRec> reduce;
+    std::vector<ReduceRec> reduce;   // sequences the second launch merges: those of many parts first
+    uint32_t n_reduce_many = 0;      // how many of them have more than kReduceFewParts parts
     std::vector<uint32_t> item_span; // span index of each item (inspection only)
     std::vector<uint32_t> seq_req;   // request index of each sequence
     uint64_t partial_floats = 0;

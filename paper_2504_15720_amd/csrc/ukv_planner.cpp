@@ -45,6 +45,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
     plan.partial_floats = 0;
     plan.kv_bytes = 0;
     plan.max_reduce_heads = 0;
+    plan.n_reduce_many = 0;
     // planner cost of one token of one head-slice: its KV bytes, weighted by the kernel kind
     auto token_cost = [&](const ClassRec &c) {
         const uint64_t bytes = (uint64_t)c.hs * c.row_bytes;
@@ -208,6 +209,8 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         for (uint32_t it = i0; it < i1; ++it)
             plan.items[it].part = it - i0;
         plan.partial_floats += (uint64_t)s.n_parts * s.part_stride;
+        if (p->tun.fused_merge && merges_in_launch(s.n_parts, s.part_stride))
+            continue; // merged inside the decode launch by the workgroup that finishes it last
         ReduceRec r{};
         r.part_off = s.part_off;
         r.out_off = s.out_off + (uint64_t)s.head0 * c.g * c.d;
@@ -219,6 +222,9 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         plan.reduce.push_back(r);
         plan.max_reduce_heads = std::max(plan.max_reduce_heads, r.n_heads);
     }
+    const auto many = std::stable_partition(plan.reduce.begin(), plan.reduce.end(),
+                                            [](const ReduceRec &r) { return r.n_parts > kReduceFewParts; });
+    plan.n_reduce_many = (uint32_t)(many - plan.reduce.begin());
     return UKV_OK;
 }
 

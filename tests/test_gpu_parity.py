@@ -337,6 +337,31 @@ def test_swap_out_to_pinned_host_memory_and_back():
         db.close()
 
 
+@pytest.mark.parametrize("shape", ["70b", "13b", "h12"])
+def test_one_long_request_cut_into_very_many_parts(shape):
+    """A request alone on the device is cut into hundreds of parts per sequence: the merge of that many partials
+    (spread over query heads and parts by the second launch, also when merging inside the decode launch is on)
+    against the oracle; then a few parts more than, and exactly, what the in-launch merge still takes."""
+    say(f"one long request, {shape}")
+    sv = SHAPES[shape]
+    rng = np.random.default_rng(41)
+    b = make_batch([sv], np.array([0]), np.array([6000]), 6000 * sv.token_bytes // 16384 + 64, "permutation", rng,
+                   reserve_tokens=4, pool_seed=9)
+    db = DeviceBatch(b)
+    try:
+        for fused in (1, 0):
+            U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, fused)
+            for span in (16 * 1024, 256 * 1024, 4 * 1024 * 1024):
+                U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, span)
+                info, _ = U.ukv_plan_decode(db.pool, db.desc(), want_items=False)
+                db.resize_workspace()
+                db.out_t.fill_(float("nan"))
+                _check_attention(db, b, f"fused {fused}, spans of {span} B: {info.n_items} items, "
+                                        f"{info.n_reduce} sequences for the second launch")
+    finally:
+        db.close()
+
+
 def test_many_calls_in_flight_on_a_side_stream():
     """More calls than staging slots are enqueued without synchronising, on a non-default stream;
     every call's output must still be that call's (plans and records are not overwritten early)."""

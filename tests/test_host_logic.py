@@ -127,8 +127,20 @@ def test_plan_covers_every_token_once(cfg, block):
     U.ukv_set_param(p, U.UKV_PARAM_BLOCK_THREADS, block)
     _check_plan(b, p)
     U.ukv_set_param(p, U.UKV_PARAM_MIN_SPAN_BYTES, 64 * 1024)     # force many cuts
-    info, _ = _check_plan(b, p)
-    assert info.n_reduce > 0
+    for fused in (1, 0):
+        # the second launch merges every cut sequence, or (merge inside the decode launch) only those whose
+        # partials add up to more than 64 Ki floats
+        U.ukv_set_param(p, U.UKV_PARAM_FUSED_MERGE, fused)
+        info, items = _check_plan(b, p)
+        key = items[:, 0].astype(np.int64) * 4096 + items[:, 1]
+        _, first, parts = np.unique(key, return_index=True, return_counts=True)
+        assert np.any(parts > 1)
+        stride = []
+        for row in items[first]:
+            si = U.ukv_pool_info(p, int(b.service_id[row[0]]))
+            stride.append(-(-(int(row[2]) * si.group * (si.head_dim + 2)) // 32) * 32)
+        big = parts * np.array(stride) > 64 * 1024
+        assert info.n_reduce == int(np.sum((parts > 1) & (big if fused else True)))
     U.ukv_set_param(p, U.UKV_PARAM_MAX_SPANS, 3)
     info, _ = _check_plan(b, p)
     assert info.n_spans <= 8
