@@ -795,24 +795,40 @@ __global__ void __launch_bounds__(MANY ? 64 * kReduceWaves : 64) reduce_kernel(c
     const uint32_t off1 = part_pair_off(r.layout_g, r.d, hq, (64 + lane) >> 2, (lane >> 1) & 1) + (lane & 1);
     float *dst = out + r.out_off + (uint64_t)hq * r.d;
     if (!MANY) {
-        float M = -INFINITY;
-        for (uint32_t c = 0; c < r.n_parts; ++c) {
-            const float *p = base + (uint64_t)c * r.part_stride + ml_off;
-            if (p[1] > 0.f)
-                M = fmaxf(M, p[0]);
-        }
-        float L = 0.f, o0 = 0.f, o1 = 0.f;
-        for (uint32_t c = 0; c < r.n_parts; ++c) {
-            const float *pc = base + (uint64_t)c * r.part_stride;
-            const float mc = pc[ml_off], lc = pc[ml_off + 1];
-            if (!(lc > 0.f))
-                continue;
-            const float w = fast_exp2(mc - M);
-            L = fmaf(lc, w, L);
-            if (one)
-                o0 = fmaf(pc[off0], w, o0);
-            if (two)
-                o1 = fmaf(pc[off1], w, o1);
+        // Four parts at a time: their (m, l) pairs and accumulator elements are requested together, so the
+        // chain of dependent round trips is a quarter of the number of parts, and the running maximum moves
+        // group by group.
+        constexpr uint32_t kGroup = 4;
+        float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f;
+        for (uint32_t c = 0; c < r.n_parts; c += kGroup) {
+            float mc[kGroup], lc[kGroup], x0[kGroup], x1[kGroup];
+#pragma unroll
+            for (uint32_t k = 0; k < kGroup; ++k) {
+                const float *pc = base + (uint64_t)min(c + k, r.n_parts - 1) * r.part_stride;
+                const float2 ml = *reinterpret_cast<const float2 *>(pc + ml_off);
+                const bool live = c + k < r.n_parts && ml.y > 0.f; // an empty part carries no weight
+                mc[k] = live ? ml.x : -INFINITY;
+                lc[k] = live ? ml.y : 0.f;
+                x0[k] = one ? pc[off0] : 0.f;
+                x1[k] = two ? pc[off1] : 0.f;
+            }
+            float Mn = M;
+#pragma unroll
+            for (uint32_t k = 0; k < kGroup; ++k)
+                Mn = fmaxf(Mn, mc[k]);
+            const float Ms = Mn == -INFINITY ? 0.f : Mn;
+            const float keep = fast_exp2(M - Ms);
+            L *= keep;
+            o0 *= keep;
+            o1 *= keep;
+            M = Mn;
+#pragma unroll
+            for (uint32_t k = 0; k < kGroup; ++k) {
+                const float w = fast_exp2(mc[k] - Ms); // 0 for a part that does not count
+                L = fmaf(lc[k], w, L);
+                o0 = fmaf(x0[k], w, o0);
+                o1 = fmaf(x1[k], w, o1);
+            }
         }
         const float inv = L > 0.f ? 1.f / L : 0.f;
         if (one)
