@@ -295,7 +295,7 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
         if ((rc = pp.get()) != UKV_OK)
             return rc;
         HIP_TRY(launch_reduce((const ReduceRec *)(w + L.reduce), (uint32_t)plan.reduce.size(), plan.n_reduce_many,
-                              plan.max_reduce_heads, a.partials, a.out, s, pp.ev.a, pp.ev.b),
+                              plan.max_reduce_heads, plan.max_reduce_units, a.partials, a.out, s, pp.ev.a, pp.ev.b),
                 "launch reduce kernel");
         pp.done();
     }

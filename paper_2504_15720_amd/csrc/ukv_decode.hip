@@ -1,5 +1,5 @@
 // Decode attention over the unified pool: decode_kernel (split-KV decode over a mixed-service batch in
-// one launch, fused merge of split partials, fused append) and reduce_kernel (the merge as a second
+// one launch, fused merge of split partials, fused append) and reduce_few_kernel / reduce_many_kernel (the merge as a second
 // launch).
 //
 // Decode is bound by HBM: every cached K/V byte is read once per step (decode phase, section
@@ -772,16 +772,95 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
     }
 }
 
-// The merge as a launch of its own, one workgroup per (cut sequence, query head):
-//   out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M).
-// MANY = false: a sequence of a few parts, merged by one wave, part after part.  MANY = true: a sequence of many
-// parts (one long request alone on the device is cut into hundreds), where that would be a chain of hundreds of
-// dependent round trips: the (m, l) pairs are fetched by all lanes at once, the weights are worked out in LDS,
-// and four waves share the parts, each with several accumulator rows in flight.
+// The merge as a launch of its own:  out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M), in two kernels; the
+// planner says which sequences go to which.
+//
+// reduce_few_kernel: sequences of a few parts.  One wave per (cut sequence, unit), a unit being a stretch of a
+// partial that is contiguous in memory: the D accumulators of one query head (ALU-path layout) or the G*128 of
+// one kv head's query group (matrix-core layout).  Lanes read a unit in memory order, 64 consecutive floats per
+// load instruction (taken query head by query head in column order, the matrix-core layout costs a cache line
+// for every 8 bytes: 20 against 11 us on the GQA workload), four parts per round trip.  Element e of a unit is
+// (query head, column) per elem_of below; all elements of a lane belong to one query head.
+static constexpr uint32_t kReduceMaxPerLane = 16;
+struct UnitElem {
+    uint32_t head, col;
+};
+__device__ __forceinline__ UnitElem elem_of(uint32_t layout_g, uint32_t D, uint32_t e) {
+    if (layout_g == 0) { // pair k of lane lir at k*(D/4) + 2*lir holds columns 8*lir + 2k + {0,1}: see part_pair_off
+        const uint32_t q4 = D >> 2, k = e / q4, rem = e % q4;
+        return UnitElem{0, 8 * (rem >> 1) + 2 * k + (rem & 1)};
+    }
+    // e = (((4r+pp)*4 + q)*G + j)*2 + b holds column 32q + 8r + 2pp + b of the group's query head j
+    const uint32_t t = e >> 1, j = t % layout_g, t2 = t / layout_g, q = t2 & 3, t3 = t2 >> 2;
+    return UnitElem{j, 32 * q + 8 * (t3 >> 2) + 2 * (t3 & 3) + (e & 1)};
+}
+
+__global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, const float *partials, float *out) {
+    const ReduceRec r = recs[blockIdx.x];
+    const uint32_t gx = r.layout_g ? r.layout_g : 1;             // query heads per unit
+    const uint32_t unit = blockIdx.y, unit_floats = gx * r.d;     // (the matrix-core path has d = 128)
+    if (unit >= r.n_heads / gx)
+        return;
+    const uint32_t lane = threadIdx.x;
+    const uint32_t ni = unit_floats / 64;                         // elements per lane: 1, 2 or 2G <= 16
+    const uint32_t head = unit * gx + elem_of(r.layout_g, r.d, lane).head; // this lane's query head
+    const float *base = partials + r.part_off;
+    const uint32_t data_off = unit * unit_floats + lane, ml_off = r.n_heads * r.d + head * 2;
+    float o[kReduceMaxPerLane];
+#pragma unroll
+    for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
+        o[i] = 0.f;
+    float M = -INFINITY, L = 0.f; // of this lane's query head
+    constexpr uint32_t kGroup = 4;
+    for (uint32_t c = 0; c < r.n_parts; c += kGroup) {
+        float mc[kGroup], lc[kGroup], x[kGroup][kReduceMaxPerLane];
+#pragma unroll
+        for (uint32_t k = 0; k < kGroup; ++k) {
+            const float *pc = base + (uint64_t)min(c + k, r.n_parts - 1) * r.part_stride;
+            const float2 ml = *reinterpret_cast<const float2 *>(pc + ml_off);
+            const bool live = c + k < r.n_parts && ml.y > 0.f; // an empty part carries no weight
+            mc[k] = live ? ml.x : -INFINITY;
+            lc[k] = live ? ml.y : 0.f;
+#pragma unroll
+            for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
+                x[k][i] = i < ni ? pc[data_off + 64 * i] : 0.f;
+        }
+        float Mn = M;
+#pragma unroll
+        for (uint32_t k = 0; k < kGroup; ++k)
+            Mn = fmaxf(Mn, mc[k]);
+        const float Ms = Mn == -INFINITY ? 0.f : Mn;
+        const float keep = fast_exp2(M - Ms);
+        L *= keep;
+#pragma unroll
+        for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
+            o[i] *= keep;
+        M = Mn;
+#pragma unroll
+        for (uint32_t k = 0; k < kGroup; ++k) {
+            const float w = fast_exp2(mc[k] - Ms); // 0 for a part that does not count
+            L = fmaf(lc[k], w, L);
+#pragma unroll
+            for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
+                o[i] = fmaf(x[k][i], w, o[i]);
+        }
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    float *dst = out + r.out_off + (uint64_t)head * r.d;
+#pragma unroll
+    for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
+        if (i < ni)
+            dst[elem_of(r.layout_g, r.d, lane + 64 * i).col] = o[i] * inv;
+}
+
+// reduce_many_kernel: sequences of many parts (one long request alone on the device is cut into hundreds), where
+// part after part would be a chain of hundreds of dependent round trips.  One workgroup of four waves per (cut
+// sequence, query head): the (m, l) pairs are fetched by all lanes at once, the weights are worked out in LDS,
+// and the waves share the parts, each with several accumulator rows in flight.  (Here the data is small and
+// there are few sequences: more workgroups matter more than whole cache lines.)
 static constexpr uint32_t kReduceWaves = 4, kReduceChunk = 1024, kReduceAhead = 8;
-template <bool MANY>
-__global__ void __launch_bounds__(MANY ? 64 * kReduceWaves : 64) reduce_kernel(const ReduceRec *recs, const float *partials,
-                                                                              float *out) {
+__global__ void __launch_bounds__(64 * kReduceWaves) reduce_many_kernel(const ReduceRec *recs, const float *partials,
+                                                                       float *out) {
     const ReduceRec r = recs[blockIdx.x];
     const uint32_t hq = blockIdx.y;
     if (hq >= r.n_heads)
@@ -794,49 +873,6 @@ __global__ void __launch_bounds__(MANY ? 64 * kReduceWaves : 64) reduce_kernel(c
     const uint32_t off0 = part_pair_off(r.layout_g, r.d, hq, lane >> 2, (lane >> 1) & 1) + (lane & 1);
     const uint32_t off1 = part_pair_off(r.layout_g, r.d, hq, (64 + lane) >> 2, (lane >> 1) & 1) + (lane & 1);
     float *dst = out + r.out_off + (uint64_t)hq * r.d;
-    if (!MANY) {
-        // Four parts at a time: their (m, l) pairs and accumulator elements are requested together, so the
-        // chain of dependent round trips is a quarter of the number of parts, and the running maximum moves
-        // group by group.
-        constexpr uint32_t kGroup = 4;
-        float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f;
-        for (uint32_t c = 0; c < r.n_parts; c += kGroup) {
-            float mc[kGroup], lc[kGroup], x0[kGroup], x1[kGroup];
-#pragma unroll
-            for (uint32_t k = 0; k < kGroup; ++k) {
-                const float *pc = base + (uint64_t)min(c + k, r.n_parts - 1) * r.part_stride;
-                const float2 ml = *reinterpret_cast<const float2 *>(pc + ml_off);
-                const bool live = c + k < r.n_parts && ml.y > 0.f; // an empty part carries no weight
-                mc[k] = live ? ml.x : -INFINITY;
-                lc[k] = live ? ml.y : 0.f;
-                x0[k] = one ? pc[off0] : 0.f;
-                x1[k] = two ? pc[off1] : 0.f;
-            }
-            float Mn = M;
-#pragma unroll
-            for (uint32_t k = 0; k < kGroup; ++k)
-                Mn = fmaxf(Mn, mc[k]);
-            const float Ms = Mn == -INFINITY ? 0.f : Mn;
-            const float keep = fast_exp2(M - Ms);
-            L *= keep;
-            o0 *= keep;
-            o1 *= keep;
-            M = Mn;
-#pragma unroll
-            for (uint32_t k = 0; k < kGroup; ++k) {
-                const float w = fast_exp2(mc[k] - Ms); // 0 for a part that does not count
-                L = fmaf(lc[k], w, L);
-                o0 = fmaf(x0[k], w, o0);
-                o1 = fmaf(x1[k], w, o1);
-            }
-        }
-        const float inv = L > 0.f ? 1.f / L : 0.f;
-        if (one)
-            dst[lane] = o0 * inv;
-        if (two)
-            dst[64 + lane] = o1 * inv;
-        return;
-    }
     __shared__ float s_m[kReduceChunk], s_l[kReduceChunk];
     __shared__ float s_red[kReduceWaves], s_o[kReduceWaves][128], s_L[kReduceWaves];
     float M = -INFINITY, L = 0.f, o0 = 0.f, o1 = 0.f; // M is the same in every lane of the workgroup; L, o0, o1 are this wave's shares
@@ -931,16 +967,16 @@ hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_t
 }
 
 // recs: the n_many sequences of many parts first, then the others; ev0/ev1 bracket both launches.
-hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads,
+hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads, uint32_t max_units,
                          const float *partials, float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
     const uint32_t n_few = n_recs - n_many;
     if (n_many)
-        hipExtLaunchKernelGGL(reduce_kernel<true>, dim3(n_many, max_heads), dim3(64 * kReduceWaves), 0, s, ev0,
+        hipExtLaunchKernelGGL(reduce_many_kernel, dim3(n_many, max_heads), dim3(64 * kReduceWaves), 0, s, ev0,
                               n_few ? nullptr : ev1, 0, recs, partials, out);
     if (n_few)
-        hipExtLaunchKernelGGL(reduce_kernel<false>, dim3(n_few, max_heads), dim3(64), 0, s, n_many ? nullptr : ev0, ev1, 0,
+        hipExtLaunchKernelGGL(reduce_few_kernel, dim3(n_few, max_units), dim3(64), 0, s, n_many ? nullptr : ev0, ev1, 0,
                               recs + n_many, partials, out);
     return hipGetLastError();
 }

@@ -140,7 +140,7 @@ hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, in
                              hipStream_t s);
 hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
                          hipEvent_t ev0, hipEvent_t ev1);
-hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads,
+hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads, uint32_t max_units,
                          const float *partials, float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s);
@@ -165,7 +165,8 @@ struct Plan {
     std::vector<uint32_t> seq_req;   // request index of each sequence
     uint64_t partial_floats = 0;
     uint64_t kv_bytes = 0;
-    uint32_t max_reduce_heads = 0;
+    uint32_t max_reduce_heads = 0;  // second launch, sequences of many parts: workgroups per sequence (query heads)
+    uint32_t max_reduce_units = 0;  // sequences of few parts: waves per sequence (query heads, or kv heads on the matrix-core path)
 };
 
 struct Tunables {

@@ -44,6 +44,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
     plan.seq_req.clear();
     plan.partial_floats = 0;
     plan.kv_bytes = 0;
+    plan.max_reduce_units = 0;
     plan.max_reduce_heads = 0;
     plan.n_reduce_many = 0;
     // planner cost of one token of one head-slice: its KV bytes, weighted by the kernel kind
@@ -221,6 +222,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         r.layout_g = c.kind == kD128GQA ? c.g : 0;
         plan.reduce.push_back(r);
         plan.max_reduce_heads = std::max(plan.max_reduce_heads, r.n_heads);
+        plan.max_reduce_units = std::max(plan.max_reduce_units, r.layout_g ? r.n_heads / r.layout_g : r.n_heads);
     }
     const auto many = std::stable_partition(plan.reduce.begin(), plan.reduce.end(),
                                             [](const ReduceRec &r) { return r.n_parts > kReduceFewParts; });
