@@ -355,6 +355,8 @@ def main():
     ap.add_argument("--taper", type=int, default=0)
     ap.add_argument("--gqa-cost-pct", type=int, default=0)
     ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")
+    ap.add_argument("--fused-merge", action="store_true",
+                    help="merge split partials inside the decode launch also where the pool's default is the second launch")
     ap.add_argument("--layout", choices=["merged", "split"], default="merged",
                     help="split = one block stream and table per (request, kv head), the alternative of section 4.4")
     ap.add_argument("--split-page-bytes", type=int, default=0, help="block size of the split layout")
@@ -410,6 +412,8 @@ def main():
         U.ukv_set_param(db.pool, U.UKV_PARAM_TAPER, 0)
     if args.unfused_merge:
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
+    if args.fused_merge:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)
     db.resize_workspace()
     rng = np.random.default_rng(1)
     _, nk, nv = b.draw_step_inputs(rng)

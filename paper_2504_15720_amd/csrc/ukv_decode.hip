@@ -172,6 +172,21 @@ __device__ __forceinline__ uint32_t part_pair_off(uint32_t layout_g, uint32_t D,
     return hh * (G * 128) + (((r << 2) + pp) * (4 * G) + q * G + j) * 2;
 }
 
+// The inverse: float e of a partial's accumulators, in memory order, is column `col` of query head `head` (of
+// the sequence's n_heads).  Readers walk partials in memory order, so that a wave's load covers whole lines.
+struct AccElem {
+    uint32_t head, col;
+};
+__device__ __forceinline__ AccElem acc_elem(uint32_t layout_g, uint32_t D, uint32_t e) {
+    if (layout_g == 0) {
+        const uint32_t q4 = D >> 2, o = e % D, k = o / q4, rem = o % q4;
+        return AccElem{e / D, 8 * (rem >> 1) + 2 * k + (rem & 1)};
+    }
+    const uint32_t G = layout_g, hh = e / (G * 128), t = (e % (G * 128)) >> 1;
+    const uint32_t j = t % G, t2 = t / G, q = t2 & 3, t3 = t2 >> 2;
+    return AccElem{hh * G + j, 32 * q + 8 * (t3 >> 2) + 2 * (t3 & 3) + (e & 1)};
+}
+
 // Merge of the partials of one cut sequence (all its query heads), executed by the workgroup
 // that finished the sequence's last item:  with M = max_c m_c,
 //   out = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M).
@@ -179,12 +194,11 @@ __device__ __forceinline__ uint32_t part_pair_off(uint32_t layout_g, uint32_t D,
 // only streams its accumulators, several parts in flight; chunks combine by the same rule.
 static constexpr uint32_t kMergeBatch = 8; // parts whose accumulators are in flight per thread
 
-// One output float4 (query head hq, columns 4*c4..) from the parts [c0, c0+nc) whose (m, l)
-// pairs are staged in lds[2*(c*n_heads + hq)]; (Mr, Lr, o) carry the running maximum, sum and
-// accumulator across chunks of parts.
+// One pair of adjacent output columns of query head hq (the two floats at xa in every part) from the parts
+// [c0, c0+nc) whose (m, l) pairs are staged in lds[2*(c*n_heads + hq)]; (Mr, Lr, o) carry the running maximum,
+// sum and accumulator across chunks of parts.
 __device__ __forceinline__ void merge_unit(const float *xa, uint32_t part_stride, const float *lds, uint32_t n_heads,
-                                           uint32_t nc, uint32_t hq, uint32_t off0, uint32_t off1, float &Mr,
-                                           float &Lr, float4 &o) {
+                                           uint32_t nc, uint32_t hq, float &Mr, float &Lr, float2 &o) {
     float Mc = Mr;
     for (uint32_t c = 0; c < nc; ++c)
         Mc = fmaxf(Mc, lds[2 * (c * n_heads + hq)]);
@@ -192,16 +206,14 @@ __device__ __forceinline__ void merge_unit(const float *xa, uint32_t part_stride
         return;
     const float f = fast_exp2(Mr - Mc);
     Lr *= f;
-    o.x *= f; o.y *= f; o.z *= f; o.w *= f;
+    o.x *= f;
+    o.y *= f;
     Mr = Mc;
     for (uint32_t c = 0; c < nc; c += kMergeBatch) {
-        float2 x0[kMergeBatch], x1[kMergeBatch];
+        float2 x[kMergeBatch];
 #pragma unroll
-        for (uint32_t k = 0; k < kMergeBatch; ++k) {
-            const uint32_t cc = min(c + k, nc - 1); // clamp: a repeated load, skipped below
-            x0[k] = ld_part2(xa + (uint64_t)cc * part_stride + off0);
-            x1[k] = ld_part2(xa + (uint64_t)cc * part_stride + off1);
-        }
+        for (uint32_t k = 0; k < kMergeBatch; ++k)
+            x[k] = ld_part2(xa + (uint64_t)min(c + k, nc - 1) * part_stride); // clamp: a repeated load, skipped below
 #pragma unroll
         for (uint32_t k = 0; k < kMergeBatch; ++k) {
             if (c + k >= nc)
@@ -209,21 +221,21 @@ __device__ __forceinline__ void merge_unit(const float *xa, uint32_t part_stride
             const uint32_t i = (c + k) * n_heads + hq;
             const float w = fast_exp2(lds[2 * i] - Mr);
             Lr = fmaf(lds[2 * i + 1], w, Lr);
-            o.x = fmaf(x0[k].x, w, o.x);
-            o.y = fmaf(x0[k].y, w, o.y);
-            o.z = fmaf(x1[k].x, w, o.z);
-            o.w = fmaf(x1[k].y, w, o.w);
+            o.x = fmaf(x[k].x, w, o.x);
+            o.y = fmaf(x[k].y, w, o.y);
         }
     }
 }
 
+// The units are the pairs of a partial in memory order (adjacent lanes read adjacent 8 bytes); only the output
+// stores are scattered.
 template <int NT>
 __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_heads, uint32_t D, uint32_t q_head0,
                             uint32_t layout_g, float *lds) {
     constexpr uint32_t kPairs = NT * 4; // (m, l) pairs that fit the LDS buffer
     const float *base = a.partials + s.part_off;
     const float *ml_base = base + (uint64_t)n_heads * D;
-    const uint32_t chunks4 = D / 4, units = n_heads * chunks4;
+    const uint32_t units = n_heads * D / 2;
     const uint32_t cmax = kPairs / n_heads;
     auto stage_ml = [&](uint32_t c0, uint32_t nc) {
         __syncthreads();
@@ -235,37 +247,35 @@ __device__ void merge_parts(const DecodeArgs &a, const SeqRec &s, uint32_t n_hea
         }
         __syncthreads();
     };
-    auto write_out = [&](uint32_t hq, uint32_t c4, float Lr, const float4 &o) {
+    auto write_out = [&](const AccElem &el, float Lr, const float2 &o) {
         const float inv = Lr > 0.f ? 1.f / Lr : 0.f;
-        st_g16(a.out + s.out_off + (uint64_t)(q_head0 + hq) * D + c4 * 4, o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+        st_g8(a.out + s.out_off + (uint64_t)(q_head0 + el.head) * D + el.col, o.x * inv, o.y * inv);
     };
     if (s.n_parts <= cmax) { // usual case: all (m, l) pairs fit, staged once for every output element
         stage_ml(0, s.n_parts);
         for (uint32_t u = threadIdx.x; u < units; u += NT) {
-            const uint32_t hq = u / chunks4, c4 = u % chunks4;
+            const AccElem el = acc_elem(layout_g, D, 2 * u);
             float Mr = -INFINITY, Lr = 0.f;
-            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-            merge_unit(base, s.part_stride, lds, n_heads, s.n_parts, hq, part_pair_off(layout_g, D, hq, c4, 0),
-                       part_pair_off(layout_g, D, hq, c4, 1), Mr, Lr, o);
-            write_out(hq, c4, Lr, o);
+            float2 o = make_float2(0.f, 0.f);
+            merge_unit(base + 2 * u, s.part_stride, lds, n_heads, s.n_parts, el.head, Mr, Lr, o);
+            write_out(el, Lr, o);
         }
         return;
     }
     for (uint32_t u0 = 0; u0 < units; u0 += NT) { // workgroup-uniform
         const uint32_t u = u0 + threadIdx.x;
         const bool act = u < units;
-        const uint32_t hq = act ? u / chunks4 : 0, c4 = act ? u % chunks4 : 0;
+        const AccElem el = acc_elem(layout_g, D, act ? 2 * u : 0);
         float Mr = -INFINITY, Lr = 0.f;
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        float2 o = make_float2(0.f, 0.f);
         for (uint32_t c0 = 0; c0 < s.n_parts; c0 += cmax) {
             const uint32_t nc = min(cmax, s.n_parts - c0);
             stage_ml(c0, nc);
             if (act)
-                merge_unit(base + (uint64_t)c0 * s.part_stride, s.part_stride, lds, n_heads, nc, hq,
-                           part_pair_off(layout_g, D, hq, c4, 0), part_pair_off(layout_g, D, hq, c4, 1), Mr, Lr, o);
+                merge_unit(base + (uint64_t)c0 * s.part_stride + 2 * u, s.part_stride, lds, n_heads, nc, el.head, Mr, Lr, o);
         }
         if (act)
-            write_out(hq, c4, Lr, o);
+            write_out(el, Lr, o);
     }
 }
 
@@ -779,22 +789,9 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
 // partial that is contiguous in memory: the D accumulators of one query head (ALU-path layout) or the G*128 of
 // one kv head's query group (matrix-core layout).  Lanes read a unit in memory order, 64 consecutive floats per
 // load instruction (taken query head by query head in column order, the matrix-core layout costs a cache line
-// for every 8 bytes: 20 against 11 us on the GQA workload), four parts per round trip.  Element e of a unit is
-// (query head, column) per elem_of below; all elements of a lane belong to one query head.
+// for every 8 bytes: 20 against 11 us on the GQA workload), four parts per round trip.  Which (query head,
+// column) a float is: acc_elem; all floats of a lane belong to one query head.
 static constexpr uint32_t kReduceMaxPerLane = 16;
-struct UnitElem {
-    uint32_t head, col;
-};
-__device__ __forceinline__ UnitElem elem_of(uint32_t layout_g, uint32_t D, uint32_t e) {
-    if (layout_g == 0) { // pair k of lane lir at k*(D/4) + 2*lir holds columns 8*lir + 2k + {0,1}: see part_pair_off
-        const uint32_t q4 = D >> 2, k = e / q4, rem = e % q4;
-        return UnitElem{0, 8 * (rem >> 1) + 2 * k + (rem & 1)};
-    }
-    // e = (((4r+pp)*4 + q)*G + j)*2 + b holds column 32q + 8r + 2pp + b of the group's query head j
-    const uint32_t t = e >> 1, j = t % layout_g, t2 = t / layout_g, q = t2 & 3, t3 = t2 >> 2;
-    return UnitElem{j, 32 * q + 8 * (t3 >> 2) + 2 * (t3 & 3) + (e & 1)};
-}
-
 __global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, const float *partials, float *out) {
     const ReduceRec r = recs[blockIdx.x];
     const uint32_t gx = r.layout_g ? r.layout_g : 1;             // query heads per unit
@@ -803,9 +800,10 @@ __global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, c
         return;
     const uint32_t lane = threadIdx.x;
     const uint32_t ni = unit_floats / 64;                         // elements per lane: 1, 2 or 2G <= 16
-    const uint32_t head = unit * gx + elem_of(r.layout_g, r.d, lane).head; // this lane's query head
+    const uint32_t data_off = unit * unit_floats + lane;          // this lane's first float of every part
+    const uint32_t head = acc_elem(r.layout_g, r.d, data_off).head; // its query head, the same for all its floats
     const float *base = partials + r.part_off;
-    const uint32_t data_off = unit * unit_floats + lane, ml_off = r.n_heads * r.d + head * 2;
+    const uint32_t ml_off = r.n_heads * r.d + head * 2;
     float o[kReduceMaxPerLane];
 #pragma unroll
     for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
@@ -850,7 +848,7 @@ __global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, c
 #pragma unroll
     for (uint32_t i = 0; i < kReduceMaxPerLane; ++i)
         if (i < ni)
-            dst[elem_of(r.layout_g, r.d, lane + 64 * i).col] = o[i] * inv;
+            dst[acc_elem(r.layout_g, r.d, data_off + 64 * i).col] = o[i] * inv;
 }
 
 // reduce_many_kernel: sequences of many parts (one long request alone on the device is cut into hundreds), where

@@ -68,6 +68,10 @@ __device__ __forceinline__ uint4 ld_g16(const void *p) {
 __device__ __forceinline__ void st_g16(float *p, float x, float y, float z, float w) {
     *as_global(reinterpret_cast<f32x4g *>(p)) = (f32x4g){x, y, z, w};
 }
+__device__ __forceinline__ void st_g8(float *p, float x, float y) {
+    typedef float f32x2g __attribute__((ext_vector_type(2)));
+    *as_global(reinterpret_cast<f32x2g *>(p)) = (f32x2g){x, y};
+}
 __device__ __forceinline__ u32x4 ld_g16v(const void *p) { return *as_global(reinterpret_cast<const u32x4 *>(p)); }
 // 128-bit streaming store (the new token's pieces: written once, read by later launches only)
 __device__ __forceinline__ void st_g16v(void *p, const u32x4 &v) {
