@@ -150,6 +150,65 @@ def main_prefill(args):
     print(json.dumps(line))
 
 
+def main_grid(args):
+    """Decode attention on uniform batches: n requests of one service, all of the same context length, from one
+    short request to a full device.  Shows where the launch is latency-bound (few, short requests), how a single
+    long request is spread over the device by the split-KV plan, and the rate the kernel reaches when the batch
+    is large and even.  One JSON line: cells of (service, requests, tokens) -> microseconds of decode + merge
+    kernels (HIP events on the dispatches) and KV TB/s."""
+    import numpy as np
+    import torch
+    import paper_2504_15720_amd as U
+    from synth import SHAPES
+    from synth.workloads import normal_bf16
+
+    dev = torch.device("cuda:0")
+    PAGE = 16384
+    noise = torch.from_numpy(normal_bf16(1 << 22, np.random.default_rng(1)).view(np.int16)).to(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    cells = []
+    for name in ("7b", "70b", "h12"):
+        sv = SHAPES[name]
+        row = sv.n_q_heads * sv.head_dim
+        for n in (1, 2, 4, 8, 16, 64):
+            for ctx in (1024, 4096, 16384, 65536):
+                n_pg = -(-ctx * sv.token_bytes // PAGE)
+                n_pages = n * n_pg + 64
+                if n_pages * PAGE > 40e9:
+                    continue
+                raw = torch.empty(n_pages * PAGE // 2 + PAGE // 2, dtype=torch.int16, device=dev)
+                skip = (-raw.data_ptr() % PAGE) // 2
+                pool_t = raw[skip:skip + n_pages * PAGE // 2]
+                pool_t.copy_(noise.repeat(-(-pool_t.numel() // noise.numel()))[:pool_t.numel()])
+                table_t = torch.from_numpy(np.random.default_rng(2).permutation(n_pages)[:n * n_pg].astype(np.int32)).to(dev)
+                pool = U.ukv_pool_create(pool_t.data_ptr(), n_pages * PAGE, PAGE, [sv])
+                U.ukv_set_param(pool, U.UKV_PARAM_PROFILE, 1)
+                q_t = noise[:n * row].clone()
+                out_t = torch.zeros(n * row, dtype=torch.float32, device=dev)
+                ws = U.ukv_decode_workspace_bytes(pool, n)
+                ws_t = torch.empty(ws, dtype=torch.uint8, device=dev)
+                off = (np.arange(n) * row).astype(np.uint64)
+                desc = U.BatchDesc([0] * n, [ctx] * n, (np.arange(n) * n_pg).astype(np.uint64), table_t.data_ptr(),
+                                   q_t.data_ptr(), off, out_t.data_ptr(), off)
+                for _ in range(3):
+                    U.ukv_decode_attention(pool, desc, ws_t.data_ptr(), ws, stream)
+                torch.cuda.synchronize()
+                U.ukv_profile_read(pool)
+                for _ in range(args.steps):
+                    U.ukv_decode_attention(pool, desc, ws_t.data_ptr(), ws, stream)
+                torch.cuda.synchronize()
+                pr = U.ukv_profile_read(pool)
+                us = 1e3 * (pr.decode_ms / pr.n_decode + (pr.reduce_ms / pr.n_reduce if pr.n_reduce else 0.0))
+                kv = n * ctx * sv.token_bytes
+                cells.append({"service": f"{sv.n_q_heads}/{sv.n_kv_heads} d={sv.head_dim}", "requests": n, "tokens": ctx,
+                              "kv_mb": round(kv / 1e6, 1), "kernels_us": round(us, 1), "tb_s": round(kv / us / 1e6, 2)})
+                torch.cuda.synchronize()
+                U.ukv_pool_destroy(pool)
+                del raw, pool_t
+    print(json.dumps({"metric": "decode attention on uniform batches: decode + merge kernel time, 1 GPU", "unit": "us",
+                      "steps": args.steps, "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
+
+
 def main_serve(args):
     """Serving loop over the unified cache driven by the doubling-budget scheduler (section 4.2): requests of
     three services arrive at once, are prefilled (bulk store + prefill attention) and decoded to their output
@@ -348,7 +407,7 @@ def main():
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
     ap.add_argument("--separate-append", action="store_true")
-    ap.add_argument("--phase", choices=["decode", "prefill", "serve"], default="decode")
+    ap.add_argument("--phase", choices=["decode", "prefill", "serve", "grid"], default="decode")
     ap.add_argument("--serve-requests", type=int, default=64, help="requests per service of the serving loop")
     ap.add_argument("--prefill-workload", choices=list(PREFILL_WORKLOADS), default="chat")
     ap.add_argument("--prefill-no-xcd", action="store_true")
@@ -377,6 +436,8 @@ def main():
         return main_prefill(args)
     if args.phase == "serve":
         return main_serve(args)
+    if args.phase == "grid":
+        return main_grid(args)
 
     import numpy as np
     import torch
