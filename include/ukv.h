@@ -140,7 +140,8 @@ size_t ukv_decode_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests);
  * reading K/V through the block tables of the unified cache (section 4.4):
  *   out[i][a][:] = sum_t softmax_t(scale * q[i][a] . K[t][a/G]) * V[t][a/G],  t < ctx_len[i],
  * fp32 accumulation over bf16 inputs, fp32 output; ctx_len == 0 gives zeros.  Bytes of the
- * pool past ctx_len never influence the result.  The batch is cut into token ranges that
+ * pool past ctx_len never influence the result (they may hold anything, NaN included); q and the K/V
+ * of the tokens in [0, ctx_len) must hold finite values.  The batch is cut into token ranges that
  * run as one split-KV launch over all services; the workgroup that finishes a cut request
  * last merges its partial results (or a second launch does, see UKV_PARAM_FUSED_MERGE).
  * workspace: DEVICE, 256-byte aligned, ws_bytes >= ukv_decode_workspace_bytes(); else UKV_ENOSPC.
