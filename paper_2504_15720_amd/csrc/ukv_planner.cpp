@@ -180,7 +180,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
                 continue;
             }
             uint64_t take = avail > 0 ? (uint64_t)avail / cost : 0;
-            take = std::max<uint64_t>(take, 1);
+            take = std::max<uint64_t>(take, std::min<uint64_t>(kMinItemTokens, rem)); // also where a span is smaller than an item's overhead
             if (take >= rem || rem - take < kMinItemTokens)
                 take = rem;
             plan.items.push_back(Item{k, (uint32_t)t, (uint32_t)(t + take), 0});

@@ -362,6 +362,29 @@ def test_one_long_request_cut_into_very_many_parts(shape):
         db.close()
 
 
+def test_one_sequence_of_more_than_a_thousand_parts():
+    """One kv head, 40 000 tokens, spans of 16 KiB: a single sequence of about 1250 parts, more than the merge
+    launch stages at a time (it goes through its parts in chunks of 1024)."""
+    say("one sequence, > 1024 parts")
+    sv = Service(4, 1, 128)
+    rng = np.random.default_rng(43)
+    b = make_batch([sv], np.array([0]), np.array([40000]), 40000 * sv.token_bytes // 16384 + 64, "permutation", rng,
+                   reserve_tokens=4, pool_seed=10)
+    db = DeviceBatch(b)
+    try:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MAX_SPANS, 4096)
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 16 * 1024)
+        db.resize_workspace()
+        info, _ = U.ukv_plan_decode(db.pool, db.desc(), want_items=False)
+        assert info.n_seqs == 1 and info.n_items > 1024 and info.n_reduce == 1
+        for fused in (1, 0):
+            U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, fused)
+            db.out_t.fill_(float("nan"))
+            _check_attention(db, b, f"fused {fused}: {info.n_items} parts")
+    finally:
+        db.close()
+
+
 def test_many_calls_in_flight_on_a_side_stream():
     """More calls than staging slots are enqueued without synchronising, on a non-default stream;
     every call's output must still be that call's (plans and records are not overwritten early)."""
