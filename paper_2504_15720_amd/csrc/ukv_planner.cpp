@@ -158,6 +158,12 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             plan.span_first.push_back((uint32_t)plan.items.size());
         fill = carry ? std::max<int64_t>(0, fill - (int64_t)C) : 0;
         C = targets[std::min<size_t>(plan.span_first.size() - 1, targets.size() - 1)];
+        // The workspace is sized for 2 * max_spans + 2 spans.  Spans can outnumber the targets (an item's overhead
+        // is not part of the budget); should they get that far, everything left goes into one last span, uncut.
+        if (plan.span_first.size() + 1 >= spans_bound(p)) {
+            C = UINT64_MAX / 4;
+            fill = 0;
+        }
     };
     for (uint32_t k = 0; k < plan.seqs.size(); ++k) {
         const SeqRec &s = plan.seqs[k];

@@ -144,6 +144,13 @@ def test_plan_covers_every_token_once(cfg, block):
     U.ukv_set_param(p, U.UKV_PARAM_MAX_SPANS, 3)
     info, _ = _check_plan(b, p)
     assert info.n_spans <= 8
+    # spans smaller than an item's overhead and a small span limit: the plan still covers everything, stays within
+    # 2 * limit + 2 spans (what the workspace is sized for) and within the workspace bound (checked by _check_plan)
+    U.ukv_set_param(p, U.UKV_PARAM_MIN_SPAN_BYTES, 16 * 1024)
+    U.ukv_set_param(p, U.UKV_PARAM_MAX_SPANS, 16)
+    info, items = _check_plan(b, p)
+    assert info.n_spans <= 2 * 16 + 2
+    assert np.all((items[:, 4] - items[:, 3] >= 16) | (items[:, 4] == b.ctx_len[items[:, 0]]) | (items[:, 3] == 0))
     U.ukv_pool_destroy(p)
 
 
