@@ -208,6 +208,50 @@ def main_grid(args):
     print(json.dumps({"metric": "decode attention on uniform batches: decode + merge kernel time, 1 GPU", "unit": "us",
                       "steps": args.steps, "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
 
+    # the same for prefill attention: n whole prompts of one length
+    cells = []
+    for name in ("7b", "70b", "h12"):
+        sv = SHAPES[name]
+        row = sv.n_q_heads * sv.head_dim
+        for n in (1, 4, 16):
+            for ctx in (512, 2048, 8192, 32768):
+                if n * ctx * row * 6 > 30e9:
+                    continue
+                n_pg = -(-ctx * sv.token_bytes // PAGE)
+                n_pages = n * n_pg + 64
+                raw = torch.empty(n_pages * PAGE // 2 + PAGE // 2, dtype=torch.int16, device=dev)
+                skip = (-raw.data_ptr() % PAGE) // 2
+                pool_t = raw[skip:skip + n_pages * PAGE // 2]
+                pool_t.copy_(noise.repeat(-(-pool_t.numel() // noise.numel()))[:pool_t.numel()])
+                table_t = torch.from_numpy(np.random.default_rng(2).permutation(n_pages)[:n * n_pg].astype(np.int32)).to(dev)
+                pool = U.ukv_pool_create(pool_t.data_ptr(), n_pages * PAGE, PAGE, [sv])
+                U.ukv_set_param(pool, U.UKV_PARAM_PROFILE, 1)
+                q_t = noise.repeat(-(-n * ctx * row // noise.numel()))[:n * ctx * row].contiguous()
+                out_t = torch.empty(n * ctx * row, dtype=torch.float32, device=dev)
+                ws = U.ukv_prefill_workspace_bytes(pool, n, n * ctx)
+                ws_t = torch.empty(ws, dtype=torch.uint8, device=dev)
+                off = (np.arange(n) * ctx * row).astype(np.uint64)
+                desc = U.BatchDesc([0] * n, [ctx] * n, (np.arange(n) * n_pg).astype(np.uint64), table_t.data_ptr(),
+                                   q_t.data_ptr(), off, out_t.data_ptr(), off)
+                q_len = np.full(n, ctx, np.uint32)
+                for _ in range(2):
+                    U.ukv_prefill_attention(pool, desc, q_len, ws_t.data_ptr(), ws, stream)
+                torch.cuda.synchronize()
+                U.ukv_profile_read(pool)
+                for _ in range(5):
+                    U.ukv_prefill_attention(pool, desc, q_len, ws_t.data_ptr(), ws, stream)
+                torch.cuda.synchronize()
+                pr = U.ukv_profile_read(pool)
+                us = 1e3 * pr.prefill_ms / pr.n_prefill
+                flops = n * 4.0 * row * ctx * (ctx + 1) / 2            # causal, counted once
+                cells.append({"service": f"{sv.n_q_heads}/{sv.n_kv_heads} d={sv.head_dim}", "prompts": n, "tokens": ctx,
+                              "kernel_us": round(us, 1), "tflops": round(flops / us / 1e6, 1)})
+                torch.cuda.synchronize()
+                U.ukv_pool_destroy(pool)
+                del raw, pool_t, q_t, out_t
+    print(json.dumps({"metric": "prefill attention on uniform batches of whole prompts: prefill kernel time, 1 GPU",
+                      "unit": "us", "steps": 5, "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
+
 
 def main_serve(args):
     """Serving loop over the unified cache driven by the doubling-budget scheduler (section 4.2): requests of
