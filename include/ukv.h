@@ -225,7 +225,7 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
                                         ukv_profile_read).  A timed launch costs about 10 us of stream time. */
 #define UKV_PARAM_FUSED_MERGE 6      /* 1 = merge partials inside the decode launch; 0 = second launch (default: 1, and
                                         0 where every service has d = 128 and g > 1) */
-#define UKV_PARAM_SLOTS 7            /* decode workgroups resident at once; 0 (default) = ask the device */
+#define UKV_PARAM_SLOTS 7            /* spans of the planner's first round; 0 (default) = one per compute unit of the device */
 #define UKV_PARAM_GQA_COST_PCT 9     /* planner cost of a KV byte of a matrix-core service (d = 128, g > 1), in percent of
                                         a byte of the other kinds (default 150, measured on mixed batches) */
 #define UKV_PARAM_PREFILL_XCD 10     /* 1 (default) = prefill workgroups of one (request, kv head) share an XCD (one L2) */

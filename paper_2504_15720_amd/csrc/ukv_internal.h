@@ -134,7 +134,7 @@ struct GatherRec { // tokens [t0, t1) of one request
 };
 
 // ---- kernel launchers (ukv_decode.hip, ukv_prefill.hip, ukv_copy.hip) ----
-int decode_resident_workgroups(uint32_t block_threads); // occupancy x compute units; 0 on failure
+int decode_resident_workgroups(uint32_t block_threads); // spans of the planner's first round: one per compute unit; 0 on failure
 hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, int32_t *page_table,
                              const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
                              hipStream_t s);

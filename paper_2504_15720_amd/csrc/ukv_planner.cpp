@@ -134,6 +134,13 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         } else {
             uint64_t R = total_cost;
             const uint64_t pct = p->tun.taper == 1 ? kDefaultTaperPct : (uint64_t)p->tun.taper;
+            // Less than two rounds of min_span spans in all: one round of equal spans.  (Tapered, the second round
+            // would be a few spans of min_span bytes that take almost as long as the first.)
+            if (R <= 2 * slots * min_span && slots <= max_spans) {
+                const uint64_t c = std::max<uint64_t>(min_span, (R + slots - 1) / slots);
+                targets.assign((size_t)((R + c - 1) / c), c);
+                R = 0;
+            }
             while (R > 0 && targets.size() < max_spans) {
                 const uint64_t c = std::max<uint64_t>(min_span, R * pct / (100 * slots));
                 uint64_t batch = std::min<uint64_t>(slots, (R + c - 1) / c);
