@@ -18,7 +18,7 @@ SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_sched.cpp", "u
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # The matrix-core paths take maxima of matrix-instruction results; without this flag every operand of a maximum is
 # first passed through a quieting v_max (q and the K/V of valid tokens must be finite anyway: see ukv.h).  Measured:
-# prefill +2.5 %, the grouped-query decode workload +2.5 %, the others unchanged.
+# prefill +2.5 %, decode within 0.5 %.
 PER_SOURCE = {"ukv_prefill.hip": ["-fno-honor-nans"], "ukv_decode.hip": ["-fno-honor-nans"]}
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
           "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
