@@ -105,7 +105,7 @@ def main_prefill(args):
     import paper_2504_15720_amd as U
     from synth import SHAPES, draw_prefill_inputs, make_batch
     from synth.workloads import draw_lengths
-    from tests.ukv_harness import DeviceBatch
+    from paper_2504_15720_amd.device_batch import DeviceBatch
 
     names, mix, law, n, pages = PREFILL_WORKLOADS[args.prefill_workload]
     rng = np.random.default_rng(20250415 + 77)
@@ -487,7 +487,7 @@ def main():
     import torch
     import paper_2504_15720_amd as U
     from synth import make_config
-    from tests.ukv_harness import DeviceBatch
+    from paper_2504_15720_amd.device_batch import DeviceBatch
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     t_gen = time.perf_counter()

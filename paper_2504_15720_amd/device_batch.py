@@ -1,10 +1,11 @@
-"""Glue shared by the GPU tests, smoke check and benchmark: puts a synthetic batch on the
-device and drives the C-ABI binding.  It performs no arithmetic of the method."""
+"""A batch on the device: copies a host-side batch description (pool image, page tables, q) into torch tensors,
+creates the pool and drives the C-ABI binding with their pointers.  Used by the benchmark, the smoke check and the
+GPU tests.  It performs no arithmetic of the method."""
 from __future__ import annotations
 
 import numpy as np
 
-import paper_2504_15720_amd as U
+from . import binding as U
 
 
 def replay_stack_log(pool: int, log) -> None:

@@ -12,7 +12,7 @@ import paper_2504_15720_amd as U
 from oracle import oracle
 from synth import SHAPES, Service, make_batch, make_config, to_split_layout
 from tests.reference_math import copy_logical_kv_to_split
-from tests.ukv_harness import DeviceBatch
+from paper_2504_15720_amd.device_batch import DeviceBatch
 
 pytestmark = pytest.mark.gpu
 ATOL = 2e-3

@@ -7,7 +7,7 @@ import pytest
 import paper_2504_15720_amd as U
 from oracle import oracle
 from synth import SHAPES, Service, draw_prefill_inputs, make_batch
-from tests.ukv_harness import DeviceBatch
+from paper_2504_15720_amd.device_batch import DeviceBatch
 
 pytestmark = pytest.mark.gpu
 ATOL = 2e-3

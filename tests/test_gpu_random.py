@@ -7,7 +7,7 @@ import paper_2504_15720_amd as U
 from synth import SHAPES, Service, draw_prefill_inputs, make_batch
 from tests.test_gpu_parity import _check_attention, _check_gather, _decode_steps
 from tests.test_gpu_prefill import _check_rows, say
-from tests.ukv_harness import DeviceBatch
+from paper_2504_15720_amd.device_batch import DeviceBatch
 
 pytestmark = pytest.mark.gpu
 
