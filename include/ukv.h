@@ -158,6 +158,38 @@ int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *works
  * costs no launch of its own.  Arguments, workspace and errors as for those two calls together. */
 int ukv_decode_step(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The same computation as ukv_decode_attention (results equal up to fp32 summation order), but
+ *   - every array of the descriptor is DEVICE memory (nothing of the batch is read on the host, so the enqueued
+ *     work follows whatever those arrays hold when it runs),
+ *   - the launch is planned on the device, and the plan and the split-KV partials live in a device array of
+ *     UKV_STATIC_SCRATCH_BYTES that is part of the library's code object: every GPU the library runs on holds one
+ *     copy from the first use until the process ends,
+ *   - the call allocates nothing (no device, pinned or staging memory, no events) and keeps no per-call state on
+ *     the host; it enqueues four launches on `stream` (plan, decode, two merge kernels; no memset, no copy) and
+ *     returns.  UKV_PARAM_PROFILE does not cover it.
+ * Limits: n_requests <= UKV_STATIC_MAX_REQUESTS and n_requests * (largest n_slices of the pool's services, see
+ * ukv_pool_info) <= 8192, else UKV_ENOSPC and nothing is enqueued; the device of the pool must be current.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams or
+ * threads) race, and so would replays of two graphs that hold such calls; calls on one stream are safe.  The
+ * array keeps the last call's contents; the plan kernel rewrites all of it that the next call reads.
+ * What the host cannot check is the caller's duty, as for page ids: ctx_len[i] * T must fit the request's table
+ * and the pool; a request whose service_id is not below the pool's service count is skipped (no output written). */
+#define UKV_STATIC_SCRATCH_BYTES (16u << 20)
+#define UKV_STATIC_MAX_REQUESTS 1024
+typedef struct {
+    uint32_t n_requests;
+    const uint32_t *service_id; /* DEVICE [n] */
+    const uint32_t *ctx_len;    /* DEVICE [n] */
+    const uint64_t *table_off;  /* DEVICE [n] */
+    const int32_t *page_table;  /* DEVICE */
+    const void *q;              /* DEVICE bf16, as in ukv_batch_t */
+    const uint64_t *q_off;      /* DEVICE [n] element offsets into q (multiples of 8) */
+    void *out;                  /* DEVICE fp32 */
+    const uint64_t *out_off;    /* DEVICE [n] element offsets into out (multiples of 4) */
+} ukv_device_batch_t;
+int ukv_decode_attention_static(ukv_pool_t *pool, const ukv_device_batch_t *batch, void *stream);
+
 /* Prefill phase (section 2.1: the tokens of a prompt, or of a chunk of it, are processed in one pass
  * that leaves their KV pairs in the cache), attention part, causal:
  *   out[i][r][a][:] = sum_t softmax_t(scale * q[i][r][a] . K[t][a/G]) * V[t][a/G],  t <= ctx_len[i] - q_len[i] + r,

@@ -25,7 +25,7 @@ UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT, UKV_PARAM_PREFILL_XCD 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",
     "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_decode_step",
-    "ukv_prefill_workspace_bytes", "ukv_prefill_attention",
+    "ukv_decode_attention_static", "ukv_prefill_workspace_bytes", "ukv_prefill_attention",
     "ukv_gather",
     "ukv_scatter",
     "ukv_scatter_tokens",
@@ -58,6 +58,15 @@ class ukv_batch_t(C.Structure):
                 ("out", C.c_void_p), ("out_off", C.c_void_p), ("new_k", C.c_void_p), ("new_v", C.c_void_p),
                 ("new_off", C.c_void_p), ("n_patches", C.c_uint32), ("patch_entry", C.c_void_p),
                 ("patch_page", C.c_void_p)]
+
+
+class ukv_device_batch_t(C.Structure):
+    _fields_ = [("n_requests", C.c_uint32), ("service_id", C.c_void_p), ("ctx_len", C.c_void_p),
+                ("table_off", C.c_void_p), ("page_table", C.c_void_p), ("q", C.c_void_p), ("q_off", C.c_void_p),
+                ("out", C.c_void_p), ("out_off", C.c_void_p)]
+
+
+UKV_STATIC_SCRATCH_BYTES, UKV_STATIC_MAX_REQUESTS = 16 << 20, 1024
 
 
 class ukv_plan_info_t(C.Structure):
@@ -113,6 +122,7 @@ def lib():
         L.ukv_decode_workspace_bytes.restype = C.c_size_t
         L.ukv_decode_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
         L.ukv_decode_step.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
+        L.ukv_decode_attention_static.argtypes = [vp, C.POINTER(ukv_device_batch_t), vp]
         L.ukv_prefill_workspace_bytes.argtypes = [vp, C.c_uint32, C.c_uint64]
         L.ukv_prefill_workspace_bytes.restype = C.c_size_t
         L.ukv_prefill_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, C.c_size_t, vp]
@@ -238,6 +248,15 @@ def ukv_decode_attention(pool: int, batch: BatchDesc, workspace_ptr: int, ws_byt
 
 def ukv_decode_step(pool: int, batch: BatchDesc, workspace_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().ukv_decode_step(pool, C.byref(batch.c), workspace_ptr, ws_bytes, stream), "ukv_decode_step")
+
+
+def ukv_decode_attention_static(pool: int, n_requests: int, service_id_ptr: int, ctx_len_ptr: int, table_off_ptr: int,
+                                page_table_ptr: int, q_ptr: int, q_off_ptr: int, out_ptr: int, out_off_ptr: int,
+                                stream: int = 0) -> None:
+    """Every pointer is device memory (see ukv_device_batch_t)."""
+    d = ukv_device_batch_t(n_requests, service_id_ptr, ctx_len_ptr, table_off_ptr, page_table_ptr, q_ptr, q_off_ptr,
+                           out_ptr, out_off_ptr)
+    _check(lib().ukv_decode_attention_static(pool, C.byref(d), stream), "ukv_decode_attention_static")
 
 
 def ukv_prefill_workspace_bytes(pool: int, n_requests: int, total_q_rows: int) -> int:

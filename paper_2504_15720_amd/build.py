@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libukv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["ukv_pool.cpp", "ukv_planner.cpp", "ukv_api.cpp", "ukv_sched.cpp", "ukv_decode.hip", "ukv_prefill.hip",
-           "ukv_copy.hip"]
+           "ukv_copy.hip", "ukv_static.hip"]
 # packed fp32 VALU forms are switched off for device code on this target
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # The matrix-core paths take maxima of matrix-instruction results; without this flag every operand of a maximum is
@@ -48,7 +48,7 @@ def build_library(verbose: bool = False) -> str:
             print(out, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -792,7 +792,10 @@ __global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
 // for every 8 bytes: 20 against 11 us on the GQA workload), four parts per round trip.  Which (query head,
 // column) a float is: acc_elem; all floats of a lane belong to one query head.
 static constexpr uint32_t kReduceMaxPerLane = 16;
-__global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, const float *partials, float *out) {
+__global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, const uint32_t *n_recs_dev,
+                                                        const float *partials, float *out) {
+    if (n_recs_dev != nullptr && blockIdx.x >= *n_recs_dev) // list length known only on the device: the grid is an upper bound
+        return;
     const ReduceRec r = recs[blockIdx.x];
     const uint32_t gx = r.layout_g ? r.layout_g : 1;             // query heads per unit
     const uint32_t unit = blockIdx.y, unit_floats = gx * r.d;     // (the matrix-core path has d = 128)
@@ -857,8 +860,11 @@ __global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, c
 // and the waves share the parts, each with several accumulator rows in flight.  (Here the data is small and
 // there are few sequences: more workgroups matter more than whole cache lines.)
 static constexpr uint32_t kReduceWaves = 4, kReduceChunk = 1024, kReduceAhead = 8;
-__global__ void __launch_bounds__(64 * kReduceWaves) reduce_many_kernel(const ReduceRec *recs, const float *partials,
-                                                                       float *out) {
+__global__ void __launch_bounds__(64 * kReduceWaves) reduce_many_kernel(const ReduceRec *recs,
+                                                                       const uint32_t *n_recs_dev,
+                                                                       const float *partials, float *out) {
+    if (n_recs_dev != nullptr && blockIdx.x >= *n_recs_dev) // workgroup-uniform
+        return;
     const ReduceRec r = recs[blockIdx.x];
     const uint32_t hq = blockIdx.y;
     if (hq >= r.n_heads)
@@ -976,10 +982,23 @@ hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many
     const uint32_t n_few = n_recs - n_many;
     if (n_many)
         hipExtLaunchKernelGGL(reduce_many_kernel, dim3(n_many, max_heads), dim3(64 * kReduceWaves), 0, s, ev0,
-                              n_few ? nullptr : ev1, 0, recs, partials, out);
+                              n_few ? nullptr : ev1, 0, recs, (const uint32_t *)nullptr, partials, out);
     if (n_few)
         hipExtLaunchKernelGGL(reduce_few_kernel, dim3(n_few, max_units), dim3(64), 0, s, n_many ? nullptr : ev0, ev1, 0,
-                              recs + n_many, partials, out);
+                              recs + n_many, (const uint32_t *)nullptr, partials, out);
+    return hipGetLastError();
+}
+
+// The same two kernels over lists whose lengths only the device knows (a plan made on the device): the grids are
+// upper bounds, workgroups past *n_many_dev / *n_few_dev leave at once.
+hipError_t launch_reduce_counted(const ReduceRec *many, const uint32_t *n_many_dev, uint32_t many_bound,
+                                 const ReduceRec *few, const uint32_t *n_few_dev, uint32_t few_bound, uint32_t max_heads,
+                                 uint32_t max_units, const float *partials, float *out, hipStream_t s) {
+    if (many_bound && max_heads)
+        hipLaunchKernelGGL(reduce_many_kernel, dim3(many_bound, max_heads), dim3(64 * kReduceWaves), 0, s, many,
+                           n_many_dev, partials, out);
+    if (few_bound && max_units)
+        hipLaunchKernelGGL(reduce_few_kernel, dim3(few_bound, max_units), dim3(64), 0, s, few, n_few_dev, partials, out);
     return hipGetLastError();
 }
 

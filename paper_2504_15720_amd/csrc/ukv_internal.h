@@ -61,6 +61,13 @@ struct ClassTable {
 
 enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kNumKinds };
 
+// floats of one split partial of a (request, head-slice) sequence: accumulators and (m, l) pairs of its query heads,
+// rounded up so that partials of different items never share a 128-byte line
+__host__ __device__ inline uint32_t part_stride_of(const ClassRec &c) { return (c.hs * c.g * (c.d + 2) + 31u) & ~31u; }
+// planner cost of one item beyond its KV bytes (q load, merge and output), in KV bytes
+static constexpr uint64_t kItemOverheadBytes = 16 * 1024;
+static constexpr uint64_t kSmallBatchSpanBytes = 64 * 1024; // batches too small to fill the device are cut down to this
+
 struct DecodeArgs {
     const unsigned char *pool_base;
     uint32_t log2_page;
@@ -142,6 +149,9 @@ hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_t
                          hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads, uint32_t max_units,
                          const float *partials, float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_reduce_counted(const ReduceRec *many, const uint32_t *n_many_dev, uint32_t many_bound,
+                                 const ReduceRec *few, const uint32_t *n_few_dev, uint32_t few_bound, uint32_t max_heads,
+                                 uint32_t max_units, const float *partials, float *out, hipStream_t s);
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s);
 hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,

@@ -8,13 +8,8 @@
 
 namespace ukv {
 
-static constexpr uint64_t kItemOverheadBytes = 16 * 1024; // q load, merge and output, as KV bytes
 static constexpr uint64_t kMinItemTokens = 16;
 static constexpr uint64_t kDefaultTaperPct = 88;
-static constexpr uint64_t kSmallBatchSpanBytes = 64 * 1024;
-
-// partials of different items never share a 128-byte line
-static uint32_t part_stride_of(const ClassRec &c) { return (c.hs * c.g * (c.d + 2) + 31u) & ~31u; }
 
 static uint32_t spans_bound(const ukv_pool *p) { return (uint32_t)(2 * p->tun.max_spans + 2); }
 
