@@ -256,186 +256,26 @@ def main_grid(args):
 def main_serve(args):
     """Serving loop over the unified cache driven by the doubling-budget scheduler (section 4.2): requests of
     three services arrive at once, are prefilled (bulk store + prefill attention) and decoded to their output
-    lengths; pages come from the pool's free list and go back when a request finishes.
-      policy db     one scheduler over all services: each iteration runs ONE batch of one service in one
-                    phase (the paper's batching rule);
-      policy mixed  one scheduler per service: each iteration takes every service's batch, and all decode
-                    batches run as ONE mixed-service launch (what the decode kernel here is built for).
-    Prints one JSON line per policy.  One attention layer; no model around it."""
-    import numpy as np
-    import torch
-    import paper_2504_15720_amd as U
-    from synth import SHAPES
-    from synth.workloads import draw_lengths, normal_bf16
+    lengths; pages come from the pool's free list and go back when a request finishes.  Policies and clocks:
+    see paper_2504_15720_amd/serving.py.  Prints one JSON line per policy.  One attention layer; no model around it."""
+    from paper_2504_15720_amd.serving import ServingLoop
+    from synth.serving import draw_serve_workload, modelled_time
 
-    dev = torch.device("cuda:0")
-    PAGE = 16384
-    services = [SHAPES["7b"], SHAPES["13b"], SHAPES["8b"]]
-    laws = [(dict(kind="lognormal", median=256, sigma=0.6, max=2048), dict(kind="lognormal", median=32, sigma=0.5, max=128)),
-            (dict(kind="lognormal", median=1024, sigma=0.5, max=2048), dict(kind="lognormal", median=96, sigma=0.5, max=256)),
-            (dict(kind="lognormal", median=512, sigma=0.6, max=2048), dict(kind="lognormal", median=64, sigma=0.5, max=192))]
-    per_service, max_batch, row_max = args.serve_requests, 32, 40 * 128
-    rng = np.random.default_rng(20250415 + 99)
-    svc = np.repeat(np.arange(3), per_service)
-    prompt = np.concatenate([np.maximum(draw_lengths(laws[s][0], per_service, rng), 16) for s in range(3)])
-    out_len = np.concatenate([np.maximum(draw_lengths(laws[s][1], per_service, rng), 4) for s in range(3)])
-    n = svc.size
-    tok_b = np.array([services[s].token_bytes for s in svc], np.int64)
-    tok_el = tok_b // 4                                         # K (or V) elements per token
-    row_el = np.array([services[s].n_q_heads * services[s].head_dim for s in svc], np.int64)
-    cap = -(-(prompt + out_len + 1) * tok_b // PAGE)
-    table_off = (np.cumsum(cap) - cap).astype(np.uint64)
-    n_pages = int(cap.sum() * 1.05) + 64
-
-    pool_raw = torch.empty(n_pages * PAGE // 2 + PAGE // 2, dtype=torch.int16, device=dev)
-    skip = (-pool_raw.data_ptr() % PAGE) // 2
-    pool_t = pool_raw[skip:skip + n_pages * PAGE // 2]
-    table_t = torch.full((int(cap.sum()),), -1, dtype=torch.int32, device=dev)
-    max_prompt = int(prompt.max())
-    pf_elems = max_batch * max_prompt * row_max                 # worst case: a full batch of the longest prompts
-
-    def noise(n_el):                                            # a 16 M-element random block, tiled
-        blk = torch.from_numpy(normal_bf16(1 << 24, rng).view(np.int16)).to(dev)
-        return blk.repeat(-(-n_el // blk.numel()))[:n_el].contiguous()
-
-    src_k, src_v, pf_q = noise(pf_elems), noise(pf_elems), noise(pf_elems)
-    pf_out = torch.empty(pf_elems, dtype=torch.float32, device=dev)
-    dq = torch.from_numpy(normal_bf16(n * row_max, rng).view(np.int16)).to(dev)
-    dnk = torch.from_numpy(normal_bf16(n * row_max, rng).view(np.int16)).to(dev)
-    dnv = torch.from_numpy(normal_bf16(n * row_max, rng).view(np.int16)).to(dev)
-    dout = torch.empty(n * row_max, dtype=torch.float32, device=dev)
-    slot_off = (np.arange(n) * row_max).astype(np.uint64)
-    stream = torch.cuda.current_stream().cuda_stream
-    # profiled execution times: proportional to the KV bytes a request of the service streams over its life
-    life = np.array([np.mean((prompt[svc == s] + out_len[svc == s] / 2) * out_len[svc == s] * services[s].token_bytes)
-                     for s in range(3)])
-    std = np.array([np.std((prompt[svc == s] + out_len[svc == s] / 2) * out_len[svc == s] * services[s].token_bytes)
-                    for s in range(3)])
-    unit = 1e-3 / life.min()                                    # shortest service about 1 ms
-    profiles = [(float(life[s] * unit), float(std[s] * unit), 0.05) for s in range(3)]
-
-    def run(policy):
-        pool = U.ukv_pool_create(pool_t.data_ptr(), n_pages * PAGE, PAGE, services)
-        scheds = ([U.ukv_sched_create(pool, profiles, max_batch)] if policy == "db"
-                  else [U.ukv_sched_create(pool, profiles, max_batch) for _ in range(3)])
-        ws_bytes = max(U.ukv_decode_workspace_bytes(pool, n), U.ukv_prefill_workspace_bytes(pool, max_batch, max_batch * max_prompt))
-        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-        ctx = np.zeros(n, np.int64)
-        owned = [[] for _ in range(n)]
-        finish = np.zeros(n)
-        kv_src_off = {}
-        checked = 0
-        t0 = time.perf_counter()
-        for r in range(n):
-            U.ukv_sched_add_request(scheds[0 if policy == "db" else int(svc[r])], r, int(svc[r]), int(prompt[r]), 0.0)
-        n_iter = n_launch = 0
-
-        def take_pages(ids, new_ctx):
-            entry, page = [], []
-            for r, c in zip(ids, new_ctx):
-                have = len(owned[r])
-                need = int(-(-c * tok_b[r] // PAGE)) - have
-                if need > 0:
-                    got = U.ukv_pages_alloc(pool, need)
-                    entry.extend(int(table_off[r]) + have + k for k in range(need))
-                    page.extend(got.tolist())
-                    owned[r].extend(got.tolist())
-            return np.array(entry, np.uint64), np.array(page, np.int32)
-
-        def prefill(ids):
-            ids = np.array(ids)
-            entry, page = take_pages(ids, prompt[ids])
-            kv_off = (np.cumsum(prompt[ids] * tok_el[ids]) - prompt[ids] * tok_el[ids]).astype(np.uint64)
-            q_off = (np.cumsum(prompt[ids] * row_el[ids]) - prompt[ids] * row_el[ids]).astype(np.uint64)
-            assert len(ids) <= max_batch and int((prompt[ids] * row_el[ids]).sum()) <= pf_elems
-            desc = U.BatchDesc(svc[ids], prompt[ids], table_off[ids], table_t.data_ptr(), pf_q.data_ptr(), q_off,
-                               pf_out.data_ptr(), q_off, 0, 0, None, entry, page)
-            U.ukv_append(pool, U.BatchDesc([], [], [], table_t.data_ptr(), 0, None, 0, None, 0, 0, None, entry, page), stream)
-            U.ukv_scatter(pool, desc, src_k.data_ptr(), src_v.data_ptr(), kv_off, stream)
-            U.ukv_prefill_attention(pool, desc, prompt[ids], ws.data_ptr(), ws_bytes, stream)
-            for r, o in zip(ids, kv_off):
-                kv_src_off[int(r)] = int(o)
-            ctx[ids] = prompt[ids]
-            return desc
-
-        def decode(ids):
-            ids = np.array(ids)
-            ctx[ids] += 1
-            entry, page = take_pages(ids, ctx[ids])
-            desc = U.BatchDesc(svc[ids], ctx[ids], table_off[ids], table_t.data_ptr(), dq.data_ptr(), slot_off[ids],
-                               dout.data_ptr(), slot_off[ids], dnk.data_ptr(), dnv.data_ptr(), slot_off[ids], entry, page)
-            U.ukv_decode_step(pool, desc, ws.data_ptr(), ws_bytes, stream)
-            return desc
-
-        def check_cache(r):
-            """The finished request's cache, read back through ukv_gather, is its prompt rows followed by
-            copies of its new-token row."""
-            c, te = int(ctx[r]), int(tok_el[r])
-            k = torch.zeros(c * te, dtype=torch.int16, device=dev)
-            v = torch.zeros(c * te, dtype=torch.int16, device=dev)
-            d1 = U.BatchDesc([svc[r]], [c], [table_off[r]], table_t.data_ptr())
-            U.ukv_gather(pool, d1, k.data_ptr(), v.data_ptr(), np.zeros(1, np.uint64), stream)
-            p, o = int(prompt[r]), kv_src_off[r]
-            exp_k = torch.cat([src_k[o:o + p * te], dnk[int(slot_off[r]):int(slot_off[r]) + te].repeat(c - p)])
-            exp_v = torch.cat([src_v[o:o + p * te], dnv[int(slot_off[r]):int(slot_off[r]) + te].repeat(c - p)])
-            assert torch.equal(k, exp_k) and torch.equal(v, exp_v), f"cache of request {r} differs"
-
-        while any(U.ukv_sched_pending(sc) for sc in scheds):
-            now = time.perf_counter() - t0
-            free = int(U.ukv_pool_info(pool, 0).free_pages)
-            batches = []
-            for sc in scheds:
-                ids, s_, queue = U.ukv_sched_next_batch(sc, now, free, cap=max_batch)
-                if ids:
-                    need = sum(U.ukv_sched_pages_needed(sc, i) for i in ids)
-                    free -= need
-                    batches.append((sc, ids, queue))
-            assert batches, "nothing fits the pool"
-            t_it = time.perf_counter()
-            dec_ids = [i for _, ids, queue in batches if queue == U.UKV_SCHED_DECODING for i in ids]
-            keep = []
-            for _, ids, queue in batches:
-                if queue == U.UKV_SCHED_WAIT:
-                    keep.append(prefill(ids))
-                    n_launch += 1
-            if dec_ids:
-                keep.append(decode(dec_ids))
-                n_launch += 1
-            torch.cuda.synchronize()
-            elapsed = time.perf_counter() - t_it
-            now = time.perf_counter() - t0
-            n_iter += 1
-            for sc, ids, queue in batches:
-                fin = [bool(ctx[i] >= prompt[i] + out_len[i]) for i in ids]
-                for i, f in zip(ids, fin):
-                    if f:
-                        finish[i] = now
-                        if checked < 4 and i % 7 == 0:
-                            check_cache(i)
-                            torch.cuda.synchronize()
-                            checked += 1
-                        U.ukv_pages_free(pool, np.array(owned[i], np.int32))
-                        owned[i] = []
-                U.ukv_sched_complete(sc, ids, fin, elapsed, now)
-        wall = time.perf_counter() - t0
-        for sc in scheds:
-            U.ukv_sched_destroy(sc)
-        U.ukv_pool_destroy(pool)
-        tokens = int(out_len.sum())
-        norm = finish / out_len
-        return {"metric": "serving loop, generated tokens/s (one attention layer), 1 GPU", "value": round(tokens / wall, 1),
-                "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True, "data": "synthetic", "dtype": "f32",
-                "config": {"workload": f"serve: 3 services (32/32, 40/40, 32/8 heads, d=128) x {per_service} requests at t=0, "
-                                       f"prompts lognormal 256/1024/512, outputs lognormal 32/96/64", "policy": policy,
-                           "max_batch": max_batch, "pool_pages": n_pages},
-                "wall_s": round(wall, 4), "iterations": n_iter, "launch_groups": n_launch,
-                "generated_tokens": tokens, "prompt_tokens": int(prompt.sum()),
-                "mean_latency_per_output_token_ms": {str(s): round(float(norm[svc == s].mean() * 1e3), 4) for s in range(3)},
-                "caches_checked_bit_exact": checked}
-
-    run("mixed")                                                # warm-up: first launches, staging buffers
+    wl = draw_serve_workload(args.serve_requests)
+    loop = ServingLoop(wl, modelled_time)
+    loop.run("mixed", clock=args.serve_clock)                   # warm-up: first launches, staging buffers
     for policy in ("db", "mixed"):
-        print(json.dumps(run(policy)))
+        r = loop.run(policy, clock=args.serve_clock)
+        print(json.dumps({
+            "metric": "serving loop, generated tokens/s (one attention layer), 1 GPU",
+            "value": round(r["generated_tokens"] / r["wall_s"], 1), "unit": "tokens/s", "n_gpus": 1,
+            "higher_is_better": True, "data": "synthetic", "dtype": "f32",
+            "config": {"workload": f"serve: 3 services (32/32, 40/40, 32/8 heads, d=128) x {args.serve_requests} requests "
+                                   f"at t=0, prompts lognormal 256/1024/512, outputs lognormal 32/96/64",
+                       "policy": policy, "clock": args.serve_clock, "max_batch": wl.max_batch, "pool_pages": wl.n_pages},
+            "wall_s": round(r["wall_s"], 4), "iterations": r["iterations"], "launch_groups": r["launch_groups"],
+            "generated_tokens": r["generated_tokens"], "prompt_tokens": r["prompt_tokens"],
+            "mean_latency_per_output_token_ms": r["mean_latency_per_output_token_ms"]}))
 
 
 def main():
@@ -453,6 +293,8 @@ def main():
     ap.add_argument("--separate-append", action="store_true")
     ap.add_argument("--phase", choices=["decode", "prefill", "serve", "grid"], default="decode")
     ap.add_argument("--serve-requests", type=int, default=64, help="requests per service of the serving loop")
+    ap.add_argument("--serve-clock", choices=["wall", "model"], default="wall",
+                    help="time charged to the scheduler's budgets: measured wall time, or a model of the batch (reproducible)")
     ap.add_argument("--prefill-workload", choices=list(PREFILL_WORKLOADS), default="chat")
     ap.add_argument("--prefill-no-xcd", action="store_true")
     ap.add_argument("--taper", type=int, default=0)
