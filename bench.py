@@ -2,10 +2,12 @@
 """Benchmark of the unified-KV decode hot path on one MI355X.
 
 A step is one pass of the whole path over one mixed-service batch: grow every request by one
-token (host: page allocation from the library's free list), then `ukv_decode_step`: the new
+token (host: page allocation from the library's free list), then `ukv_plan_step`: the new
 page-table entries, the store of every request's new K/V token into its pages and split-KV
-decode attention with the merge of cut requests, as one plan upload and one decode launch.
-`--separate-append` runs the same step as `ukv_append` + `ukv_decode_attention` (two launches).
+decode attention with the merge of cut requests, as ONE launch of a plan that is kept across
+steps (remade every 64 tokens of growth).  `--replan-each-step` plans and uploads in every step
+(`ukv_decode_step`: plan upload + decode launch); `--separate-append` runs the step as
+`ukv_append` + `ukv_decode_attention`.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
   value      whole-step KV throughput: sum over steps of ctx_len*token_bytes / wall time
@@ -291,6 +293,10 @@ def main():
     ap.add_argument("--slots", type=int, default=0)
     ap.add_argument("--no-taper", action="store_true")
     ap.add_argument("--separate-append", action="store_true")
+    ap.add_argument("--replan-each-step", action="store_true",
+                    help="ukv_decode_step in every step (host plan + upload) instead of the plan kept across steps")
+    ap.add_argument("--replan-every", type=int, default=-1, help="UKV_PARAM_REPLAN_EVERY")
+    ap.add_argument("--merge-acq-rel", action="store_true", help="UKV_PARAM_MERGE_ACQ_REL = 1")
     ap.add_argument("--phase", choices=["decode", "prefill", "serve", "grid"], default="decode")
     ap.add_argument("--serve-requests", type=int, default=64, help="requests per service of the serving loop")
     ap.add_argument("--serve-clock", choices=["wall", "model"], default="wall",
@@ -361,10 +367,17 @@ def main():
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
     if args.fused_merge:
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)
+    if args.merge_acq_rel:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MERGE_ACQ_REL, 1)
+    if args.replan_every >= 0:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_REPLAN_EVERY, args.replan_every)
     db.resize_workspace()
     rng = np.random.default_rng(1)
     _, nk, nv = b.draw_step_inputs(rng)
     db.set_new(nk, nv)
+    kept_plan = not (args.attention_only or args.separate_append or args.replan_each_step)
+    if kept_plan:
+        db.make_plan()
 
     kv_bytes = []
 
@@ -376,6 +389,10 @@ def main():
             if ids.size:
                 lib_ids = U.ukv_pages_alloc(db.pool, ids.size)
                 assert np.array_equal(lib_ids, ids)
+            if kept_plan:
+                db.plan_step(ids)
+                kv_bytes.append(b.kv_bytes())
+                return
             desc = db.desc(entry, ids)
             if args.separate_append:
                 db.append(desc)
@@ -418,9 +435,11 @@ def main():
                    "kv_bytes_per_step": int(kv_per_step), "pool_pages": b.n_pages,
                    "stated_pool_pages": b.notes.get("stated_pages"), "page_bytes": b.page_bytes,
                    "step": "attention only" if args.attention_only else
-                           "grow + append + attention (two launches)" if args.separate_append else
-                           "grow + append + attention (one launch)" if U.ukv_get_param(db.pool, U.UKV_PARAM_FUSED_MERGE) else
-                           "grow + append + attention (one launch) + merge of split partials (second launch)",
+                           "grow + append + attention (two calls)" if args.separate_append else
+                           ("grow + append + attention, plan kept across steps (one launch)" if kept_plan else
+                            "grow + append + attention, planned and uploaded every step (upload + one launch)") +
+                           ("" if U.ukv_get_param(db.pool, U.UKV_PARAM_FUSED_MERGE) else
+                            " + merge of split partials (second launch)"),
                    "layout": args.layout, "block_table_entries": int(b.pages_owned().sum()),
                    "pages_in_use": int(b.stack.used_pages),
                    "internal_waste_bytes": int(b.pages_owned().sum()) * int(b.page_bytes) - int(b.kv_bytes()),

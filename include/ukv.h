@@ -158,6 +158,41 @@ int ukv_decode_attention(ukv_pool_t *pool, const ukv_batch_t *batch, void *works
  * costs no launch of its own.  Arguments, workspace and errors as for those two calls together. */
 int ukv_decode_step(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes, void *stream);
 
+/* A decode plan that outlives its step.  ukv_decode_step plans every call on the host and uploads the plan; in
+ * steady-state decoding the batch is the same from step to step and every request grows by one token, so the plan
+ * made for one step serves the following ones: the growth goes to the last token range of every request, and the
+ * only per-step data, the page ids of the table entries the growth needs, travel in the kernel arguments.  A step is
+ * then ONE launch (plus the merge launch where UKV_PARAM_FUSED_MERGE is 0) with no host planning and no upload.
+ * Results are those of ukv_decode_step on the same lengths: pool bytes and table entries bit for bit, out up to fp32
+ * summation order.  The plan is remade (as in ukv_decode_step) on the first step, after UKV_PARAM_REPLAN_EVERY steps
+ * (default 64: the cut drifts from balance as requests grow), after ukv_set_param, and for steps that do not fit the
+ * kernel arguments (more than 766 requests or 576 new table entries).
+ *   ukv_plan_create   batch: the requests as they are NOW (ctx_len tokens in the cache; patch fields ignored); the
+ *                     host arrays are copied.  workspace: DEVICE, as for ukv_decode_step, owned by the plan until
+ *                     ukv_plan_destroy; no device work.
+ *   ukv_plan_step     advance != 0: every request grows by one token first.  Then, for every request, the token at
+ *                     index ctx_len - 1 is stored from new_k / new_v (at the batch's new_off) and attention runs
+ *                     over [0, ctx_len).  new_pages HOST [n_new_pages]: page ids for the table entries
+ *                     ceil((c-1) T / P) .. ceil(c T / P) - 1 of each request (c its length in this step), in
+ *                     request order; n_new_pages must be their exact number, else UKV_EINVAL and nothing changes.
+ *                     io (may be NULL = the batch's pointers): other page table / q / out / new_k / new_v of the same
+ *                     layout, e.g. the next layer of the same iteration, called with advance == 0 and that layer's
+ *                     page ids.  While a plan is live the caller must not change the table entries of its requests.
+ *   ukv_plan_lengths  the plan's current ctx_len, HOST [n] out. */
+typedef struct ukv_plan ukv_plan_t;
+typedef struct {
+    int32_t *page_table; /* DEVICE */
+    const void *q;       /* DEVICE bf16 */
+    void *out;           /* DEVICE fp32 */
+    const void *new_k;   /* DEVICE bf16 */
+    const void *new_v;   /* DEVICE bf16 */
+} ukv_plan_io_t;
+int ukv_plan_create(ukv_pool_t *pool, const ukv_batch_t *batch, void *workspace, size_t ws_bytes, ukv_plan_t **out);
+int ukv_plan_step(ukv_plan_t *plan, const ukv_plan_io_t *io, int advance, const int32_t *new_pages,
+                  uint32_t n_new_pages, void *stream);
+int ukv_plan_lengths(const ukv_plan_t *plan, uint32_t *ctx_len_out, uint32_t n);
+int ukv_plan_destroy(ukv_plan_t *plan);
+
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  The same computation as ukv_decode_attention (results equal up to fp32 summation order), but
  *   - every array of the descriptor is DEVICE memory (nothing of the batch is read on the host, so the enqueued
@@ -261,6 +296,12 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_GQA_COST_PCT 9     /* planner cost of a KV byte of a matrix-core service (d = 128, g > 1), in percent of
                                         a byte of the other kinds (default 150, measured on mixed batches) */
 #define UKV_PARAM_PREFILL_XCD 10     /* 1 (default) = prefill workgroups of one (request, kv head) share an XCD (one L2) */
+#define UKV_PARAM_REPLAN_EVERY 11    /* ukv_plan_step remakes its plan after this many tokens of growth (default 64; 0 = every step) */
+#define UKV_PARAM_MERGE_ACQ_REL 12   /* merge inside the decode launch: 0 (default) = workgroups publish their partial results
+                                        with agent-scope relaxed atomics, a wait for the store acknowledgements and a
+                                        barrier before they count the item; 1 = the count is an agent-scope
+                                        acquire-release, the ordering the language's memory model promises (4 to 8 % of
+                                        the launch).  UKV_PARAM_FUSED_MERGE = 0 needs neither. */
 #define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
                                         workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);

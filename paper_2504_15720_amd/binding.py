@@ -21,10 +21,12 @@ UKV_MAX_SERVICES = 16
 UKV_PARAM_MAX_SPANS, UKV_PARAM_MIN_SPAN_BYTES, UKV_PARAM_BLOCK_THREADS = 1, 2, 3
 UKV_PARAM_HEADS_PER_SLICE, UKV_PARAM_PROFILE, UKV_PARAM_FUSED_MERGE = 4, 5, 6
 UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT, UKV_PARAM_PREFILL_XCD = 7, 8, 9, 10
+UKV_PARAM_REPLAN_EVERY, UKV_PARAM_MERGE_ACQ_REL = 11, 12
 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",
     "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_decode_step",
+    "ukv_plan_create", "ukv_plan_step", "ukv_plan_lengths", "ukv_plan_destroy",
     "ukv_decode_attention_static", "ukv_prefill_workspace_bytes", "ukv_prefill_attention",
     "ukv_gather",
     "ukv_scatter",
@@ -58,6 +60,11 @@ class ukv_batch_t(C.Structure):
                 ("out", C.c_void_p), ("out_off", C.c_void_p), ("new_k", C.c_void_p), ("new_v", C.c_void_p),
                 ("new_off", C.c_void_p), ("n_patches", C.c_uint32), ("patch_entry", C.c_void_p),
                 ("patch_page", C.c_void_p)]
+
+
+class ukv_plan_io_t(C.Structure):
+    _fields_ = [("page_table", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p), ("new_k", C.c_void_p),
+                ("new_v", C.c_void_p)]
 
 
 class ukv_device_batch_t(C.Structure):
@@ -122,6 +129,10 @@ def lib():
         L.ukv_decode_workspace_bytes.restype = C.c_size_t
         L.ukv_decode_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
         L.ukv_decode_step.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, vp]
+        L.ukv_plan_create.argtypes = [vp, C.POINTER(ukv_batch_t), vp, C.c_size_t, C.POINTER(vp)]
+        L.ukv_plan_step.argtypes = [vp, C.POINTER(ukv_plan_io_t), C.c_int, vp, C.c_uint32, vp]
+        L.ukv_plan_lengths.argtypes = [vp, vp, C.c_uint32]
+        L.ukv_plan_destroy.argtypes = [vp]
         L.ukv_decode_attention_static.argtypes = [vp, C.POINTER(ukv_device_batch_t), vp]
         L.ukv_prefill_workspace_bytes.argtypes = [vp, C.c_uint32, C.c_uint64]
         L.ukv_prefill_workspace_bytes.restype = C.c_size_t
@@ -248,6 +259,30 @@ def ukv_decode_attention(pool: int, batch: BatchDesc, workspace_ptr: int, ws_byt
 
 def ukv_decode_step(pool: int, batch: BatchDesc, workspace_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().ukv_decode_step(pool, C.byref(batch.c), workspace_ptr, ws_bytes, stream), "ukv_decode_step")
+
+
+def ukv_plan_create(pool: int, batch: BatchDesc, workspace_ptr: int, ws_bytes: int) -> int:
+    out = C.c_void_p()
+    _check(lib().ukv_plan_create(pool, C.byref(batch.c), workspace_ptr, ws_bytes, C.byref(out)), "ukv_plan_create")
+    return out.value
+
+
+def ukv_plan_step(plan: int, new_pages, advance: bool = True, io=None, stream: int = 0) -> None:
+    """io: None, or (page_table_ptr, q_ptr, out_ptr, new_k_ptr, new_v_ptr)."""
+    pages = np.ascontiguousarray(new_pages, np.int32)
+    io_c = C.byref(ukv_plan_io_t(*io)) if io is not None else None
+    _check(lib().ukv_plan_step(plan, io_c, 1 if advance else 0, pages.ctypes.data if pages.size else None, pages.size,
+                               stream), "ukv_plan_step")
+
+
+def ukv_plan_lengths(plan: int, n: int) -> np.ndarray:
+    out = np.zeros(n, np.uint32)
+    _check(lib().ukv_plan_lengths(plan, out.ctypes.data, n), "ukv_plan_lengths")
+    return out
+
+
+def ukv_plan_destroy(plan: int) -> None:
+    _check(lib().ukv_plan_destroy(plan), "ukv_plan_destroy")
 
 
 def ukv_decode_attention_static(pool: int, n_requests: int, service_id_ptr: int, ctx_len_ptr: int, table_off_ptr: int,

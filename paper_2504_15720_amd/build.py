@@ -19,7 +19,10 @@ DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # The matrix-core paths take maxima of matrix-instruction results; without this flag every operand of a maximum is
 # first passed through a quieting v_max (q and the K/V of valid tokens must be finite anyway: see ukv.h).  Measured:
 # prefill +2.5 %, decode within 0.5 %.
-PER_SOURCE = {"ukv_prefill.hip": ["-fno-honor-nans"], "ukv_decode.hip": ["-fno-honor-nans"]}
+# ukv_decode.hip also keeps single-lane atomics as they are written: rewritten as a wave-wide reduction plus one
+# atomic, the result is needed at once, and the take of the next span could not stay in flight behind the item.
+PER_SOURCE = {"ukv_prefill.hip": ["-fno-honor-nans"],
+              "ukv_decode.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
           "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

@@ -4,6 +4,8 @@
 // into the workspace; the append and gather kernels read their few records in place).
 #include <algorithm>
 #include <cstring>
+#include <new>
+#include <string>
 #include <unordered_map>
 #include <vector>
 
@@ -99,24 +101,22 @@ struct ProfPair {
 };
 
 struct BlobLayout {
-    size_t classes, seqs, items, spans, reduce, counters, total;
+    size_t recs, spans, reduce, counters, queue, total;
 };
 
 BlobLayout blob_layout(size_t n_seqs, size_t n_items, size_t n_spans, size_t n_reduce) {
     BlobLayout b{};
     size_t o = 0;
-    b.classes = o;
-    o = align_up(o + sizeof(ClassTable));
-    b.seqs = o;
-    o = align_up(o + n_seqs * sizeof(SeqRec));
-    b.items = o;
-    o = align_up(o + n_items * sizeof(Item));
+    b.recs = o;
+    o = align_up(o + n_items * sizeof(ItemRec));
     b.spans = o;
     o = align_up(o + (n_spans + 1) * sizeof(uint32_t));
     b.reduce = o;
     o = align_up(o + n_reduce * sizeof(ReduceRec));
     b.counters = o;
     o = align_up(o + n_seqs * sizeof(uint32_t));
+    b.queue = o; // span queue counter; zero like the counters
+    o = align_up(o + sizeof(uint32_t));
     b.total = o;
     return b;
 }
@@ -178,10 +178,38 @@ int ukv_plan_decode(const ukv_pool_t *p, const ukv_batch_t *b, ukv_plan_info_t *
     return UKV_OK;
 }
 
+} // extern "C"
+
+// A plan kept in the caller's workspace across steps (ukv_plan_*): the launch parameters of the resident plan, the
+// host's copy of the batch arrays (lengths advance with every step) and the step's new page ids as they go into the
+// kernel arguments.
+struct ukv_plan {
+    ukv_pool *pool = nullptr;
+    uint32_t n = 0;
+    std::vector<uint32_t> service_id, ctx_len;
+    std::vector<uint64_t> table_off, q_off, out_off, new_off, patch_entry;
+    ukv_plan_io_t io{};
+    void *workspace = nullptr;
+    size_t ws_bytes = 0;
+    bool resident = false; // the workspace holds a plan
+    uint32_t delta = 0;    // tokens every request has grown since that plan was made
+    uint64_t tun_epoch = 0;
+    DecodeArgs args{};
+    uint32_t n_spans = 0;
+    uint32_t grid = 0;     // workgroups of a launch of the resident plan
+    uint32_t queue_at = 0; // value of the span queue's counter after the launches enqueued so far (mod 2^32)
+    size_t reduce_off = 0;
+    uint32_t n_reduce = 0, n_reduce_many = 0, max_reduce_heads = 0, max_reduce_units = 0;
+    StepPages sp{};
+};
+
+extern "C" {
+
 // Attention alone, or (with_append) the whole step: the new page-table entries ride with the plan
-// upload and the new tokens are stored by the decode workgroups that attend to them.
+// upload and the new tokens are stored by the decode workgroups that attend to them.  keep: where to note the
+// launch parameters, for later launches of the same plan.
 static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream,
-                       bool with_append) {
+                       bool with_append, ukv_plan *keep = nullptr) {
     if (!p || !b) {
         set_error("null pool or batch");
         return UKV_EINVAL;
@@ -247,9 +275,12 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
     if (rc != UKV_OK)
         return rc;
     unsigned char *h = (unsigned char *)st->host;
-    std::memcpy(h + L.classes, &p->classes, sizeof(ClassTable));
-    std::memcpy(h + L.seqs, plan.seqs.data(), plan.seqs.size() * sizeof(SeqRec));
-    std::memcpy(h + L.items, plan.items.data(), plan.items.size() * sizeof(Item));
+    ItemRec *recs = (ItemRec *)(h + L.recs);
+    for (size_t it = 0; it < plan.items.size(); ++it) {
+        recs[it].it = plan.items[it];
+        recs[it].s = plan.seqs[plan.items[it].seq];
+        recs[it].c = p->classes.c[recs[it].s.cls];
+    }
     std::memcpy(h + L.spans, plan.span_first.data(), plan.span_first.size() * sizeof(uint32_t));
     if (!plan.reduce.empty())
         std::memcpy(h + L.reduce, plan.reduce.data(), plan.reduce.size() * sizeof(ReduceRec));
@@ -272,21 +303,37 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
     a.page_table = b->page_table;
     a.q = b->q;
     a.out = (float *)b->out;
-    a.classes = (const ClassRec *)(w + L.classes);
-    a.seqs = (const SeqRec *)(w + L.seqs);
-    a.items = (const Item *)(w + L.items);
+    a.recs = (const ItemRec *)(w + L.recs);
     a.span_first = (const uint32_t *)(w + L.spans);
     a.partials = (float *)(w + part_off);
     const bool fused = p->tun.fused_merge != 0;
     a.counters = fused ? (uint32_t *)(w + L.counters) : nullptr;
+    a.merge_acq_rel = p->tun.merge_acq_rel ? 1u : 0u;
     a.new_k = with_append ? (const uint16_t *)b->new_k : nullptr;
     a.new_v = with_append ? (const uint16_t *)b->new_v : nullptr;
+    a.delta = 0;
+    a.queue = (uint32_t *)(w + L.queue);
+    a.queue_base = 0; // the upload has just zeroed the counter
+    a.n_spans = n_spans;
+    a.n_spans_dev = nullptr;
+    const uint32_t grid = decode_grid(n_spans, (uint32_t)p->tun.block_threads, p->kinds);
+    if (keep) {
+        keep->args = a;
+        keep->grid = grid;
+        keep->queue_at = n_spans; // where this launch leaves the counter
+        keep->n_spans = n_spans;
+        keep->reduce_off = L.reduce;
+        keep->n_reduce = (uint32_t)plan.reduce.size();
+        keep->n_reduce_many = plan.n_reduce_many;
+        keep->max_reduce_heads = plan.max_reduce_heads;
+        keep->max_reduce_units = plan.max_reduce_units;
+    }
 
     if (n_spans) {
         ProfPair pp{p, 0};
         if ((rc = pp.get()) != UKV_OK)
             return rc;
-        HIP_TRY(launch_decode(a, n_spans, (uint32_t)p->tun.block_threads, s, pp.ev.a, pp.ev.b),
+        HIP_TRY(launch_decode(a, nullptr, grid, (uint32_t)p->tun.block_threads, p->kinds, s, pp.ev.a, pp.ev.b),
                 "launch decode kernel");
         pp.done();
     }
@@ -308,6 +355,196 @@ int ukv_decode_attention(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, s
 
 int ukv_decode_step(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream) {
     return decode_impl(p, b, workspace, ws_bytes, stream, true);
+}
+
+int ukv_plan_create(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, ukv_plan_t **out) {
+    if (!p || !b || !out) {
+        set_error("null argument");
+        return UKV_EINVAL;
+    }
+    *out = nullptr;
+    const uint32_t n = b->n_requests;
+    if (n && (!b->service_id || !b->ctx_len || !b->table_off || !b->q_off || !b->out_off || !b->new_off)) {
+        set_error("batch host arrays must be non-null");
+        return UKV_EINVAL;
+    }
+    if (!b->page_table || (n && (!b->q || !b->out || !b->new_k || !b->new_v))) {
+        set_error("page_table, q, out, new_k and new_v must be non-null device pointers");
+        return UKV_EINVAL;
+    }
+    if (!workspace || ((uintptr_t)workspace & 255) || ws_bytes < ukv_decode_workspace_bytes(p, n)) {
+        set_error("workspace must be 256-byte aligned and hold ukv_decode_workspace_bytes(pool, n_requests)");
+        return workspace && !((uintptr_t)workspace & 255) ? UKV_ENOSPC : UKV_EINVAL;
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        if (b->service_id[i] >= p->n_services) {
+            set_error("service_id out of range");
+            return UKV_EINVAL;
+        }
+        if ((b->q_off[i] & 7) || (b->out_off[i] & 3) || (b->new_off[i] & 7)) {
+            set_error("q_off and new_off must be multiples of 8 elements, out_off of 4");
+            return UKV_EINVAL;
+        }
+        if (ukv_pages_for_tokens(p, b->service_id[i], b->ctx_len[i]) > p->n_pages) {
+            set_error("ctx_len exceeds what the pool can hold");
+            return UKV_EINVAL;
+        }
+    }
+    ukv_plan *pl = new (std::nothrow) ukv_plan();
+    if (!pl) {
+        set_error("host allocation failed");
+        return UKV_ENOMEM;
+    }
+    pl->pool = p;
+    pl->n = n;
+    pl->service_id.assign(b->service_id, b->service_id + n);
+    pl->ctx_len.assign(b->ctx_len, b->ctx_len + n);
+    pl->table_off.assign(b->table_off, b->table_off + n);
+    pl->q_off.assign(b->q_off, b->q_off + n);
+    pl->out_off.assign(b->out_off, b->out_off + n);
+    pl->new_off.assign(b->new_off, b->new_off + n);
+    pl->io = ukv_plan_io_t{b->page_table, b->q, b->out, b->new_k, b->new_v};
+    pl->workspace = workspace;
+    pl->ws_bytes = ws_bytes;
+    *out = pl;
+    return UKV_OK;
+}
+
+int ukv_plan_destroy(ukv_plan_t *pl) {
+    delete pl;
+    return UKV_OK;
+}
+
+int ukv_plan_lengths(const ukv_plan_t *pl, uint32_t *ctx_len_out, uint32_t n) {
+    if (!pl || (n && !ctx_len_out) || n != pl->n) {
+        set_error("bad plan, output or count");
+        return UKV_EINVAL;
+    }
+    std::memcpy(ctx_len_out, pl->ctx_len.data(), (size_t)n * sizeof(uint32_t));
+    return UKV_OK;
+}
+
+int ukv_plan_step(ukv_plan_t *pl, const ukv_plan_io_t *io_in, int advance, const int32_t *new_pages,
+                  uint32_t n_new_pages, void *stream) {
+    if (!pl || (n_new_pages && !new_pages)) {
+        set_error("null plan or page array");
+        return UKV_EINVAL;
+    }
+    ukv_pool *p = pl->pool;
+    const uint32_t n = pl->n;
+    if (n == 0)
+        return UKV_OK;
+    const ukv_plan_io_t io = io_in ? *io_in : pl->io;
+    if (!io.page_table || !io.q || !io.out || !io.new_k || !io.new_v) {
+        set_error("page_table, q, out, new_k and new_v must be non-null device pointers");
+        return UKV_EINVAL;
+    }
+    const uint32_t grow = advance ? 1u : 0u;
+    // the table entries this step adds: request i gains entries [ceil((c-1) T / P), ceil(c T / P)), c its new length
+    const bool in_args = n <= kStepMaxReq;
+    uint64_t total = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint64_t c = (uint64_t)pl->ctx_len[i] + grow;
+        const uint32_t cls = pl->service_id[i];
+        const uint64_t hi = ukv_pages_for_tokens(p, cls, c);
+        if (c > 0xffffffffull || hi > p->n_pages || (c && hi == 0)) {
+            set_error("a request outgrows the pool");
+            return UKV_EINVAL;
+        }
+        if (in_args)
+            pl->sp.first[i] = (uint16_t)std::min<uint64_t>(total, 0xffff);
+        total += c ? hi - ukv_pages_for_tokens(p, cls, c - 1) : 0;
+    }
+    if (total != n_new_pages) {
+        set_error("n_new_pages must be the number of table entries the step adds (" + std::to_string(total) + ")");
+        return UKV_EINVAL;
+    }
+    for (uint32_t k = 0; k < n_new_pages; ++k)
+        if (new_pages[k] < 0 || (uint64_t)new_pages[k] >= p->n_pages) {
+            set_error("new page id out of range");
+            return UKV_EINVAL;
+        }
+    const bool fast = pl->resident && in_args && total <= kStepMaxPages && pl->tun_epoch == p->tun_epoch &&
+                      (uint64_t)pl->delta + grow <= (uint64_t)p->tun.replan_every;
+    hipStream_t s = (hipStream_t)stream;
+    if (!fast) {
+        // Plan for the lengths as they are now and upload (the route of ukv_decode_step); the plan stays behind.
+        pl->patch_entry.clear();
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint64_t c = (uint64_t)pl->ctx_len[i] + grow;
+            if (c == 0)
+                continue;
+            const uint64_t lo = ukv_pages_for_tokens(p, pl->service_id[i], c - 1),
+                           hi = ukv_pages_for_tokens(p, pl->service_id[i], c);
+            for (uint64_t e = lo; e < hi; ++e)
+                pl->patch_entry.push_back(pl->table_off[i] + e);
+        }
+        for (uint32_t i = 0; i < n; ++i)
+            pl->ctx_len[i] += grow;
+        ukv_batch_t b{};
+        b.n_requests = n;
+        b.service_id = pl->service_id.data();
+        b.ctx_len = pl->ctx_len.data();
+        b.table_off = pl->table_off.data();
+        b.page_table = io.page_table;
+        b.q = io.q;
+        b.q_off = pl->q_off.data();
+        b.out = io.out;
+        b.out_off = pl->out_off.data();
+        b.new_k = io.new_k;
+        b.new_v = io.new_v;
+        b.new_off = pl->new_off.data();
+        b.n_patches = n_new_pages;
+        b.patch_entry = pl->patch_entry.data();
+        b.patch_page = new_pages;
+        pl->resident = false;
+        const int rc = decode_impl(p, &b, pl->workspace, pl->ws_bytes, stream, true, pl);
+        if (rc != UKV_OK) {
+            for (uint32_t i = 0; i < n; ++i)
+                pl->ctx_len[i] -= grow;
+            return rc;
+        }
+        pl->resident = true;
+        pl->delta = 0;
+        pl->tun_epoch = p->tun_epoch;
+        return UKV_OK;
+    }
+    // The resident plan serves: one launch, the new page ids in its arguments.
+    pl->sp.n_req = n;
+    pl->sp.first[n] = (uint16_t)total;
+    std::memcpy(pl->sp.page, new_pages, (size_t)n_new_pages * sizeof(int32_t));
+    DecodeArgs a = pl->args;
+    a.page_table = io.page_table;
+    a.q = io.q;
+    a.out = (float *)io.out;
+    a.new_k = (const uint16_t *)io.new_k;
+    a.new_v = (const uint16_t *)io.new_v;
+    a.delta = pl->delta + grow;
+    a.queue_base = pl->queue_at;
+    int rc;
+    if (pl->n_spans) {
+        ProfPair pp{p, 0};
+        if ((rc = pp.get()) != UKV_OK)
+            return rc;
+        HIP_TRY(launch_decode(a, &pl->sp, pl->grid, (uint32_t)p->tun.block_threads, p->kinds, s, pp.ev.a, pp.ev.b),
+                "launch decode kernel");
+        pp.done();
+        pl->queue_at += pl->n_spans;
+    }
+    for (uint32_t i = 0; i < n; ++i)
+        pl->ctx_len[i] += grow;
+    pl->delta += grow;
+    if (pl->n_reduce) {
+        ProfPair pp{p, 1};
+        if ((rc = pp.get()) != UKV_OK)
+            return rc;
+        HIP_TRY(launch_reduce((const ReduceRec *)((unsigned char *)pl->workspace + pl->reduce_off), pl->n_reduce,
+                              pl->n_reduce_many, pl->max_reduce_heads, pl->max_reduce_units, a.partials, a.out, s,
+                              pp.ev.a, pp.ev.b),
+                "launch reduce kernel");
+        pp.done();
+    }
+    return UKV_OK;
 }
 
 int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {

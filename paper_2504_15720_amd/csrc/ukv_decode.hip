@@ -20,10 +20,13 @@ static constexpr int kTabWindow = 2048; // page-table entries staged in LDS at a
 static constexpr int kMaxBlock = 512;
 struct ItemCtx {
     DecodeArgs a;
+    alignas(16) Item it; // it, s, c: the item's record as it lies in memory (ItemRec), written in 16-byte pieces
     SeqRec s;
     ClassRec c;
-    Item it;
 };
+static_assert(offsetof(ItemCtx, s) == offsetof(ItemCtx, it) + offsetof(ItemRec, s) &&
+                  offsetof(ItemCtx, c) == offsetof(ItemCtx, it) + offsetof(ItemRec, c),
+              "ItemCtx mirrors ItemRec");
 __shared__ int32_t s_tab[kTabWindow];                                  // page-table window
 __shared__ __align__(16) float s_mbuf[kMaxBlock * 8 + (kMaxBlock / 8) * 2]; // merge buffer
 __shared__ __align__(16) ItemCtx s_ctx;
@@ -49,14 +52,14 @@ __device__ __forceinline__ DecodeArgs ctx_args() {
     a.page_table = reinterpret_cast<const int32_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.page_table)));
     a.q = reinterpret_cast<const void *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.q)));
     a.out = reinterpret_cast<float *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.out)));
-    a.classes = nullptr;
-    a.seqs = nullptr;
-    a.items = nullptr;
+    a.recs = nullptr;
     a.span_first = nullptr;
     a.partials = reinterpret_cast<float *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.partials)));
     a.counters = reinterpret_cast<uint32_t *>(uni(reinterpret_cast<uint64_t>(s_ctx.a.counters)));
+    a.merge_acq_rel = uni(s_ctx.a.merge_acq_rel);
     a.new_k = nullptr; // the fused-append inputs are fetched where they are used (new_token_rows)
     a.new_v = nullptr;
+    a.delta = 0;       // already applied to the item and the sequence in LDS
     return a;
 }
 __device__ __forceinline__ SeqRec ctx_seq() {
@@ -71,6 +74,7 @@ __device__ __forceinline__ SeqRec ctx_seq() {
     s.head0 = uni(s_ctx.s.head0);
     s.n_parts = uni(s_ctx.s.n_parts);
     s.part_stride = uni(s_ctx.s.part_stride);
+    s.req = 0; // read from LDS where it is needed (step_entries)
     return s;
 }
 __device__ __forceinline__ ClassRec ctx_class() {
@@ -287,19 +291,74 @@ __device__ __forceinline__ void finish_item(const DecodeArgs &a, const SeqRec &s
                                             float *mbuf) {
     if (it.part == kDirect || a.counters == nullptr || !merges_in_launch(s.n_parts, s.part_stride))
         return;
-    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this lane's partial stores have completed
+    // Publication of the partial.  Every access to a partial or a counter is an agent-scope atomic, which the
+    // hardware performs at the level that is coherent across XCDs (cache policy sc1: stores are written through to
+    // it and acknowledged from there, loads are served from it).  (1) Each wave waits for the acknowledgement of its
+    // own partial stores (vmcnt(0)); (2) the workgroup barrier, whose release/acquire fences also keep the compiler
+    // from moving the stores below it or the increment above it; (3) one lane counts the item; (4) whoever reads
+    // n_parts - 1 knows that every other part was counted, hence acknowledged, before, and reads the partials with
+    // agent-scope loads after the next barrier.  This is the instruction sequence of an agent-scope release on the
+    // increment and acquire on the read, minus the write-back and invalidation of the whole L2 (buffer_wbl2 /
+    // buffer_inv), which serve accesses that are not agent-scope atomics: there are none here.  In the language's
+    // memory model, though, relaxed atomics plus a barrier promise no such ordering; merge_acq_rel makes the
+    // increment an acquire-release at agent scope (measured: 4 to 8 % of the launch), for whoever prefers the model's
+    // word over the hardware's.
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
     __syncthreads();
     uint32_t *flag = reinterpret_cast<uint32_t *>(tab);
     if (threadIdx.x == 0)
-        flag[0] = __hip_atomic_fetch_add(as_global(a.counters + it.seq), 1u, __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+        flag[0] = a.merge_acq_rel ? __hip_atomic_fetch_add(as_global(a.counters + it.seq), 1u, __ATOMIC_ACQ_REL,
+                                                           __HIP_MEMORY_SCOPE_AGENT)
+                                  : __hip_atomic_fetch_add(as_global(a.counters + it.seq), 1u, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    if (flag[0] == s.n_parts - 1)
+    if (flag[0] == s.n_parts - 1) {
+        if (threadIdx.x == 0) // the last one to count: nobody touches the counter again in this launch; a later
+                              // launch that reuses the plan finds it at zero
+            __hip_atomic_store(as_global(a.counters + it.seq), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         merge_parts<NT>(a, s, n_heads, D, q_head0, layout_g, mbuf);
+    }
+}
+
+// Page-table window of an item into LDS.  In a step whose new table entries ride in the kernel arguments, the
+// entries the request gains in this step are taken from there (they are not in memory yet; only the items that hold
+// the request's last token can meet them) and written to the table, for the launches to come.  Every head-slice
+// writes the entries its own window covers: each new page holds bytes of the new token, so some slice covers it
+// (slices that share a page store the same value).  Workgroup-uniform arguments; `new_n` == 0 otherwise.
+template <int NT>
+__device__ __forceinline__ void load_table_window(int32_t *tab, const DecodeArgs &a, const SeqRec &s, uint64_t s_lo,
+                                                  uint32_t n_ent, const StepPages &sp, uint64_t new_lo, uint32_t new_n,
+                                                  uint32_t new_first) {
+    const int32_t *tp = a.page_table + s.table_off;
+    for (uint32_t e = threadIdx.x; e < n_ent; e += NT) {
+        const uint64_t ent = s_lo + e;
+        int32_t pg;
+        if (ent - new_lo < (uint64_t)new_n) {
+            pg = sp.page[new_first + (uint32_t)(ent - new_lo)];
+            as_global(const_cast<int32_t *>(tp))[ent] = pg;
+        } else {
+            pg = as_global(tp)[ent];
+        }
+        tab[e] = pg;
+    }
+}
+
+// Which table entries of the item's request ride in the kernel arguments (see StepPages).
+__device__ __forceinline__ void step_entries(bool appends, const StepPages &sp, const SeqRec &s, uint64_t T, uint32_t lg,
+                                             uint64_t &new_lo, uint32_t &new_n, uint32_t &new_first) {
+    new_lo = 0;
+    new_n = 0;
+    new_first = 0;
+    if (appends && sp.n_req != 0) {
+        const uint32_t r = uni(s_ctx.s.req);
+        new_first = sp.first[r];
+        new_n = (uint32_t)sp.first[r + 1] - new_first;
+        new_lo = ((uint64_t)(s.ctx_len - 1) * T + ((1ull << lg) - 1)) >> lg;
+    }
 }
 
 template <int D, int G, int NT>
-__device__ __forceinline__ void process_item() {
+__device__ __forceinline__ void process_item(const StepPages &sp) {
     const DecodeArgs a = ctx_args();
     const SeqRec s = ctx_seq();
     const ClassRec c = ctx_class();
@@ -346,6 +405,9 @@ __device__ __forceinline__ void process_item() {
 
     const bool appends = item_appends(s, it);
     const uint32_t t_pool = appends ? it.t1 - 1 : it.t1; // tokens below this are read from the pool
+    uint64_t new_lo;
+    uint32_t new_n, new_first;
+    step_entries(appends, sp, s, T, lg, new_lo, new_n, new_first);
     uint4 nkr[1], nvr[1]; // the new token's K and V pieces of this lane (fused append)
     uint4 *new_dst = nullptr;
     uint32_t w0 = it.t0;
@@ -368,8 +430,7 @@ __device__ __forceinline__ void process_item() {
         if (w0 != it.t0)
             __syncthreads(); // later windows: every wave is done with the previous one (the first
                              // follows the workgroup barrier that published the item)
-        for (uint32_t e = tid; e < n_ent; e += NT)
-            tab[e] = as_global(a.page_table)[s.table_off + s_lo + e];
+        load_table_window<NT>(tab, a, s, s_lo, n_ent, sp, new_lo, new_n, new_first);
         __syncthreads();
         if (w0 == it.t0) {
 #pragma unroll
@@ -507,7 +568,7 @@ __device__ __forceinline__ void process_item() {
 // weights keep 16 mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
 
 template <int NT>
-__device__ __forceinline__ void process_item_gqa() {
+__device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
     const DecodeArgs a = ctx_args();
     const SeqRec s = ctx_seq();
     const ClassRec c = ctx_class();
@@ -549,6 +610,9 @@ __device__ __forceinline__ void process_item_gqa() {
 
     const bool appends = item_appends(s, it);
     const uint32_t t_pool = appends ? it.t1 - 1 : it.t1; // tokens below this are read from the pool
+    uint64_t new_lo;
+    uint32_t new_n, new_first;
+    step_entries(appends, sp, s, T, lg, new_lo, new_n, new_first);
     u32x4 nK[4], nV; // the new token's K and V pieces of this lane (fused append)
     unsigned char *new_dst = nullptr;
     uint32_t w0 = it.t0;
@@ -573,8 +637,7 @@ __device__ __forceinline__ void process_item_gqa() {
         }
         if (w0 != it.t0)
             __syncthreads(); // later windows only: see process_item
-        for (uint32_t e = tid; e < n_ent; e += NT)
-            tab[e] = as_global(a.page_table)[s.table_off + s_lo + e];
+        load_table_window<NT>(tab, a, s, s_lo, n_ent, sp, new_lo, new_n, new_first);
         __syncthreads();
 
         if (live) {
@@ -755,31 +818,84 @@ __device__ __forceinline__ void process_item_gqa() {
     finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, G, tab, mbuf);
 }
 
+// KINDS: bit k set = the launch may meet items of kind k.  A pool's launches use the instantiation for the kinds of
+// its services, so that the register count (and with it the number of workgroups a compute unit holds) is that of
+// the kinds present, not of the most demanding kind compiled.
 // (No second launch-bound argument: asking for two waves per SIMD outright gave the 256-lane kernel a
-// register assignment that measured 0.5-1 % slower; both variants fit 256 registers as they are.)
-template <int NT>
-__global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a) {
-    const uint32_t i0 = uni(a.span_first[blockIdx.x]), i1 = uni(a.span_first[blockIdx.x + 1]);
+// register assignment that measured 0.5-1 % slower; the variants fit their register classes as they are.)
+__shared__ uint32_t s_span; // the span the workgroup takes next
+
+// Spans past the first of a workgroup come from the queue (see DecodeArgs).  The take is an atomic on one word in
+// memory for the whole device, a few hundred nanoseconds each when many arrive together, and the loads its wave
+// issues afterwards return behind it.  So the first span is the workgroup's own index (no take: all workgroups start
+// at once), and the take for the next span is issued when the current span's last item begins: spans end at
+// different times, and the round trip hides behind that item.
+// (Returns the counter's value as fetched; the span is grid + value - queue_base, worked out where the span is
+// needed, so that the fetch stays in flight until then.)
+__device__ __forceinline__ uint32_t take_span(const DecodeArgs &a) {
+    return __hip_atomic_fetch_add(as_global(a.queue), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int NT, uint32_t KINDS>
+__device__ __forceinline__ void decode_body(const DecodeArgs &a, const StepPages &sp) {
     if (threadIdx.x == 0)
         s_ctx.a = a;
-    for (uint32_t i = i0; i < i1; ++i) {
-        __syncthreads(); // the previous item is done with s_ctx
-        if (threadIdx.x == 0) {
-            const Item it = a.items[i];
-            const SeqRec s = a.seqs[it.seq];
-            s_ctx.it = it;
-            s_ctx.s = s;
-            s_ctx.c = a.classes[s.cls];
+    const uint32_t grid = gridDim.x;
+    const uint32_t n_spans = a.n_spans_dev != nullptr ? uni(*as_global(a.n_spans_dev)) : a.n_spans;
+    uint32_t span = blockIdx.x;
+    // The first eight lanes of the workgroup hold one 16-byte piece each of an item's record.
+    const bool rec_lane = threadIdx.x < sizeof(ItemRec) / 16;
+    auto rec_piece = [&](uint32_t i) {
+        return ld_g16(reinterpret_cast<const unsigned char *>(a.recs + i) + 16 * threadIdx.x);
+    };
+    while (span < n_spans) { // workgroup-uniform
+        uint32_t next = 0;   // thread 0 only
+        const uint32_t i0 = uni(a.span_first[span]), i1 = uni(a.span_first[span + 1]);
+        if (i0 == i1 && threadIdx.x == 0)
+            next = take_span(a);
+        uint4 rec = make_uint4(0, 0, 0, 0), rec_next = make_uint4(0, 0, 0, 0);
+        if (i0 < i1 && rec_lane)
+            rec = rec_piece(i0);
+        for (uint32_t i = i0; i < i1; ++i) {
+            __syncthreads(); // the previous item is done with s_ctx
+            if (threadIdx.x < 64) { // the first wave publishes the record
+                // A plan that outlives its step: the sequence has grown by delta tokens since it was made, and the
+                // growth belongs to the sequence's last item (t1 == ctx_len).  t1 is word 2 of piece 0, ctx_len
+                // word 2 of piece 3 (see ItemRec).
+                const uint32_t t1 = (uint32_t)__builtin_amdgcn_readlane((int)rec.z, 0);
+                const uint32_t ctx = (uint32_t)__builtin_amdgcn_readlane((int)rec.z, 3);
+                if ((threadIdx.x == 0 && t1 == ctx) || threadIdx.x == 3)
+                    rec.z += a.delta;
+                if (rec_lane)
+                    reinterpret_cast<uint4 *>(&s_ctx.it)[threadIdx.x] = rec;
+                if (threadIdx.x == 0 && i == i1 - 1)
+                    next = take_span(a); // in flight while the span's last item is worked on
+                if (rec_lane && i + 1 < i1)
+                    rec_next = rec_piece(i + 1); // in flight while this item is worked on
+            }
+            __syncthreads();
+            const uint32_t kind = uni(s_ctx.c.kind); // workgroup-uniform: one compiled function per (head_dim, group) kind
+            if ((KINDS & (1u << kD64G1)) && kind == kD64G1)
+                process_item<64, 1, NT>(sp);
+            else if ((KINDS & (1u << kD64G2)) && kind == kD64G2)
+                process_item<64, 2, NT>(sp);
+            else if ((KINDS & (1u << kD128G1)) && kind == kD128G1)
+                process_item<128, 1, NT>(sp);
+            else if ((KINDS & (1u << kD128GQA)) && kind == kD128GQA)
+                process_item_gqa<NT>(sp);
+            rec = rec_next;
         }
+        __syncthreads(); // every wave has read the previous s_span
+        if (threadIdx.x == 0)
+            s_span = grid + next - a.queue_base;
         __syncthreads();
-        switch (uni(s_ctx.c.kind)) { // workgroup-uniform: one compiled function per (head_dim, group) kind
-        case kD64G1: process_item<64, 1, NT>(); break;
-        case kD64G2: process_item<64, 2, NT>(); break;
-        case kD128G1: process_item<128, 1, NT>(); break;
-        case kD128GQA: process_item_gqa<NT>(); break;
-        default: break;
-        }
+        span = uni(s_span);
     }
+}
+
+template <int NT, uint32_t KINDS>
+__global__ void __launch_bounds__(NT) decode_kernel(DecodeArgs a, StepPages sp) {
+    decode_body<NT, KINDS>(a, sp);
 }
 
 // The merge as a launch of its own:  out = sum_c acc_c 2^(m_c-M) / sum_c l_c 2^(m_c-M), in two kernels; the
@@ -955,22 +1071,71 @@ int decode_resident_workgroups(uint32_t block_threads) {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return 0;
     hipError_t e = block_threads == 512
-                       ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<512>, 512, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<256>, 256, 0);
+                       ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<512, kAllKinds>, 512, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<256, kAllKinds>, 256, 0);
     if (e != hipSuccess || per_cu <= 0 || cus <= 0) // (a kernel that does not fit a CU at all)
         return 0;
     return cus;
 }
 
+// The compiled sets of kinds, smallest first; a launch takes the first one that covers the pool's kinds.
+static constexpr uint32_t kKindSets[] = {1u << kD128G1, (1u << kD64G1) | (1u << kD64G2),
+                                         (1u << kD64G1) | (1u << kD64G2) | (1u << kD128G1), 1u << kD128GQA, kAllKinds};
+static constexpr int kNumKindSets = 5;
+
+static int kind_set_of(uint32_t kinds) {
+    if (kinds == 0 || (kinds & ~kAllKinds))
+        kinds = kAllKinds;
+    int set = 0;
+    while ((kinds & ~kKindSets[set]) != 0)
+        ++set; // ends at kAllKinds at the latest
+    return set;
+}
+
+typedef void (*DecodeKernelFn)(DecodeArgs, StepPages);
+static DecodeKernelFn decode_kernel_fn(int set, bool big) {
+    switch (set) {
+    case 0: return big ? decode_kernel<512, kKindSets[0]> : decode_kernel<256, kKindSets[0]>;
+    case 1: return big ? decode_kernel<512, kKindSets[1]> : decode_kernel<256, kKindSets[1]>;
+    case 2: return big ? decode_kernel<512, kKindSets[2]> : decode_kernel<256, kKindSets[2]>;
+    case 3: return big ? decode_kernel<512, kKindSets[3]> : decode_kernel<256, kKindSets[3]>;
+    default: return big ? decode_kernel<512, kAllKinds> : decode_kernel<256, kAllKinds>;
+    }
+}
+
+// Workgroups of a launch: as many as the device keeps resident of this instantiation (compute units x workgroups
+// per unit), so that none waits for a place; each takes spans from the queue until it is empty.
+uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds) {
+    static int places[2][kNumKindSets]; // per device kind this would differ; all devices of a process are alike
+    const int set = kind_set_of(kinds);
+    const bool big = block_threads == 512;
+    int &cached = places[big ? 1 : 0][set];
+    if (cached == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel_fn(set, big), big ? 512 : 256, 0) ==
+                hipSuccess &&
+            cus > 0 && per_cu > 0)
+            cached = cus * per_cu;
+        else
+            cached = -1;
+    }
+    const uint32_t cap = cached > 0 ? (uint32_t)cached : 256u;
+    return n_spans < cap ? n_spans : cap;
+}
+
+// grid: decode_grid() of the plan's spans.  sp: the step's new page ids for the kernel arguments, or null.
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps.
-hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
-                         hipEvent_t ev0, hipEvent_t ev1) {
-    if (n_spans == 0)
+hipError_t launch_decode(const DecodeArgs &a, const StepPages *sp_in, uint32_t grid, uint32_t block_threads,
+                         uint32_t kinds, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+    if (grid == 0)
         return hipSuccess;
-    if (block_threads == 512)
-        hipExtLaunchKernelGGL(decode_kernel<512>, dim3(n_spans), dim3(512), 0, s, ev0, ev1, 0, a);
-    else
-        hipExtLaunchKernelGGL(decode_kernel<256>, dim3(n_spans), dim3(256), 0, s, ev0, ev1, 0, a);
+    static const StepPages no_pages{}; // n_req == 0
+    const StepPages &sp = sp_in ? *sp_in : no_pages;
+    const bool big = block_threads == 512;
+    hipExtLaunchKernelGGL(decode_kernel_fn(kind_set_of(kinds), big), dim3(grid), dim3(big ? 512 : 256), 0, s, ev0, ev1, 0,
+                          a, sp);
     return hipGetLastError();
 }
 

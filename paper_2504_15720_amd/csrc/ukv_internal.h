@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
 #include <string>
 #include <vector>
@@ -25,7 +26,7 @@ struct SeqRec {
     uint32_t head0;       // first kv head of the slice
     uint32_t n_parts;     // work items this sequence was cut into
     uint32_t part_stride; // floats per partial: n_heads_q * (head_dim + 2), rounded up to 32 (one line)
-    uint32_t pad_[1];
+    uint32_t req;         // index of the request in the batch
 };
 static_assert(sizeof(SeqRec) == 64, "SeqRec layout");
 
@@ -59,7 +60,18 @@ struct ClassTable {
     ClassRec c[UKV_MAX_SERVICES];
 };
 
+// What a decode workgroup needs to start an item, in one 128-byte record (one load, fetched while the previous item
+// is still being worked on): the item, its sequence and the constants of the sequence's service.
+struct ItemRec {
+    Item it;
+    SeqRec s;
+    ClassRec c;
+};
+static_assert(sizeof(ItemRec) == 128 && offsetof(ItemRec, it.t1) == 8 && offsetof(ItemRec, s.ctx_len) == 56,
+              "ItemRec layout (the kernel patches t1 and ctx_len by position)");
+
 enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kNumKinds };
+static constexpr uint32_t kAllKinds = (1u << kNumKinds) - 1;
 
 // floats of one split partial of a (request, head-slice) sequence: accumulators and (m, l) pairs of its query heads,
 // rounded up so that partials of different items never share a 128-byte line
@@ -74,17 +86,42 @@ struct DecodeArgs {
     const int32_t *page_table;
     const void *q;      // bf16
     float *out;
-    const ClassRec *classes;
-    const SeqRec *seqs;
-    const Item *items;
+    const ItemRec *recs;        // one per work item, in span order
     const uint32_t *span_first; // [n_spans + 1]
     float *partials;
     uint32_t *counters; // per sequence: finished items (fused merge); null = merge in a second launch
+    uint32_t merge_acq_rel; // fused merge: count items with an agent-scope acquire-release instead of relaxed + waits
     // Fused append (null = attention only): the item that holds a request's last token takes that
     // token's K/V from here and stores it into the request's pages.
     const uint16_t *new_k;
     const uint16_t *new_v;
+    // A plan that outlives its step: every sequence has grown by `delta` tokens since the plan was made; the growth
+    // goes to the sequence's last item (the one whose t1 equals the planned ctx_len).  0 for a plan made for this call.
+    uint32_t delta;
+    // Spans are handed out through a queue in device memory: the launch has one workgroup per place the device
+    // offers (grid <= n_spans); workgroup w starts with span w, and a workgroup that has finished a span takes the
+    // next one, whichever XCD it runs on.  (The hardware deals the workgroups of a grid out to the XCDs in turn, and
+    // the XCDs do not run at the same speed: with one workgroup per span the slowest XCD finished its fixed share
+    // long after the fastest.)  A take is grid + atomic_add(queue, 1) - queue_base; values >= n_spans end the
+    // workgroup.  Every workgroup takes until it fails once, so a launch leaves the counter n_spans higher, which
+    // the host adds to queue_base of the next launch of the same plan.  n_spans_dev (may be null): the number of
+    // spans if only the device knows it; n_spans is then an upper bound and empty spans may follow the last one.
+    uint32_t *queue;
+    uint32_t queue_base;
+    uint32_t n_spans;
+    const uint32_t *n_spans_dev;
 };
+
+// The page ids of the table entries a step adds, carried in the kernel arguments (no upload of their own): request r
+// gets page[first[r]] .. page[first[r + 1] - 1] for the entries ceil((c - 1) T / P) .. ceil(c T / P) - 1 of its table,
+// c its length after the step.  n_req == 0: nothing rides here (the entries are in the table already).
+static constexpr uint32_t kStepMaxReq = 766, kStepMaxPages = 576;
+struct StepPages {
+    uint32_t n_req;
+    uint16_t first[kStepMaxReq + 2];
+    int32_t page[kStepMaxPages];
+};
+static_assert(sizeof(DecodeArgs) + sizeof(StepPages) <= 4096, "decode kernel arguments exceed 4 KiB");
 
 struct ReduceRec {
     uint64_t part_off;
@@ -142,11 +179,13 @@ struct GatherRec { // tokens [t0, t1) of one request
 
 // ---- kernel launchers (ukv_decode.hip, ukv_prefill.hip, ukv_copy.hip) ----
 int decode_resident_workgroups(uint32_t block_threads); // spans of the planner's first round: one per compute unit; 0 on failure
+// workgroups to launch for n_spans spans: one per place the device offers the kernel instantiation, at most n_spans
+uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds);
 hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, int32_t *page_table,
                              const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
                              hipStream_t s);
-hipError_t launch_decode(const DecodeArgs &a, uint32_t n_spans, uint32_t block_threads, hipStream_t s,
-                         hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_decode(const DecodeArgs &a, const StepPages *sp, uint32_t grid, uint32_t block_threads,
+                         uint32_t kinds, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many, uint32_t max_heads, uint32_t max_units,
                          const float *partials, float *out, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_reduce_counted(const ReduceRec *many, const uint32_t *n_many_dev, uint32_t many_bound,
@@ -191,6 +230,8 @@ struct Tunables {
     int64_t taper = 1;
     int64_t gqa_cost_pct = 150; // planner weight of a matrix-core (grouped-query) KV byte, percent
     int64_t prefill_xcd = 1;
+    int64_t merge_acq_rel = 0;
+    int64_t replan_every = 64; // a kept plan is remade after its requests have grown by this many tokens
     bool slots_auto = true;
 };
 
@@ -207,6 +248,9 @@ struct ukv_pool {
     ukv_service_t services[UKV_MAX_SERVICES];
     ukv::ClassTable classes;
     ukv::Tunables tun;
+
+    uint64_t tun_epoch = 0; // bumped by every ukv_set_param that changes how a launch is planned
+    uint32_t kinds = 0; // bit k: a service of kind k exists (chooses the decode kernel instantiation)
 
     // LIFO free list
     std::vector<int32_t> free_stack;

@@ -73,6 +73,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
             s.ctx_len = (uint32_t)ctx;
             s.cls = cls;
             s.head0 = h0;
+            s.req = i;
             s.part_stride = part_stride_of(c);
             plan.seqs.push_back(s);
             plan.seq_req.push_back(i);

@@ -54,6 +54,7 @@ static void choose_slicing(uint32_t n_kv, uint32_t d, uint32_t block_threads, in
 }
 
 int derive_classes(ukv_pool *p) {
+    p->kinds = 0;
     for (uint32_t s = 0; s < p->n_services; ++s) {
         const ukv_service_t &sv = p->services[s];
         ClassRec &c = p->classes.c[s];
@@ -72,6 +73,7 @@ int derive_classes(ukv_pool *p) {
             c.kind = c.g == 1 ? kD64G1 : kD64G2;
         else
             return fail(UKV_EINVAL, "unsupported shape: head_dim 128 with group 1/2/4/8, or head_dim 64 with group 1/2");
+        p->kinds |= 1u << c.kind;
         if (c.kind == kD128GQA) {
             // matrix-core path: one wave per kv head of the slice, all waves on the same tokens
             const uint32_t waves = (uint32_t)p->tun.block_threads / 64;
@@ -243,7 +245,17 @@ int ukv_pages_free(ukv_pool_t *p, uint32_t n, const int32_t *ids) {
 int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
     if (!p)
         return fail(UKV_EINVAL, "null pool");
+    if (key != UKV_PARAM_PROFILE)
+        ++p->tun_epoch; // kept plans are remade
     switch (key) {
+    case UKV_PARAM_MERGE_ACQ_REL:
+        p->tun.merge_acq_rel = value ? 1 : 0;
+        return UKV_OK;
+    case UKV_PARAM_REPLAN_EVERY:
+        if (value < 0 || value > (1 << 20))
+            return fail(UKV_EINVAL, "replan_every out of range");
+        p->tun.replan_every = value;
+        return UKV_OK;
     case UKV_PARAM_MAX_SPANS:
         if (value < 1 || value > (1 << 20))
             return fail(UKV_EINVAL, "max_spans out of range");
@@ -313,6 +325,8 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_TAPER: *value = p->tun.taper; return UKV_OK;
     case UKV_PARAM_GQA_COST_PCT: *value = p->tun.gqa_cost_pct; return UKV_OK;
     case UKV_PARAM_PREFILL_XCD: *value = p->tun.prefill_xcd; return UKV_OK;
+    case UKV_PARAM_REPLAN_EVERY: *value = p->tun.replan_every; return UKV_OK;
+    case UKV_PARAM_MERGE_ACQ_REL: *value = p->tun.merge_acq_rel; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

@@ -25,14 +25,13 @@ static constexpr uint32_t kPlanThreads = 1024;
 
 constexpr size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 // layout of the array (byte offsets)
-static constexpr size_t kOffClasses = 0;
-static constexpr size_t kOffSeqs = up256(kOffClasses + sizeof(ClassTable));
+static constexpr size_t kOffSeqs = 0;
 static constexpr size_t kOffItems = up256(kOffSeqs + kStaticMaxSeqs * sizeof(SeqRec));
-static constexpr size_t kOffSpans = up256(kOffItems + (kStaticMaxSeqs + kStaticMaxSpans) * sizeof(Item));
+static constexpr size_t kOffSpans = up256(kOffItems + (kStaticMaxSeqs + kStaticMaxSpans) * sizeof(ItemRec));
 static constexpr size_t kOffMany = up256(kOffSpans + (kStaticMaxSpans + 1) * sizeof(uint32_t));
 static constexpr size_t kOffFew = up256(kOffMany + kStaticMaxSpans * sizeof(ReduceRec));
 static constexpr size_t kOffCounts = up256(kOffFew + kStaticMaxSpans * sizeof(ReduceRec));
-static constexpr size_t kOffStart = up256(kOffCounts + 2 * sizeof(uint32_t));
+static constexpr size_t kOffStart = up256(kOffCounts + 4 * sizeof(uint32_t)); // two list lengths, the span queue, the span count
 static constexpr size_t kOffPartials = up256(kOffStart + (kStaticMaxSeqs + 1) * sizeof(uint64_t));
 static_assert(kOffPartials + (1u << 20) < kStaticScratchBytes, "scratch too small for its plan area");
 
@@ -90,17 +89,14 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
     __shared__ uint64_t s_tmp[kPlanThreads / 64 + 1];
     const uint32_t tid = threadIdx.x;
     unsigned char *w = a.scratch;
-    ClassRec *classes = reinterpret_cast<ClassRec *>(w + kOffClasses);
     SeqRec *seqs = reinterpret_cast<SeqRec *>(w + kOffSeqs);
-    Item *items = reinterpret_cast<Item *>(w + kOffItems);
+    ItemRec *items = reinterpret_cast<ItemRec *>(w + kOffItems); // one record per work item, in span order
     uint32_t *span_first = reinterpret_cast<uint32_t *>(w + kOffSpans);
     ReduceRec *many = reinterpret_cast<ReduceRec *>(w + kOffMany);
     ReduceRec *few = reinterpret_cast<ReduceRec *>(w + kOffFew);
     uint32_t *counts = reinterpret_cast<uint32_t *>(w + kOffCounts);
     uint64_t *start = reinterpret_cast<uint64_t *>(w + kOffStart); // start[k] = first cost unit of sequence k
 
-    if (tid < UKV_MAX_SERVICES)
-        classes[tid] = a.classes.c[tid];
     auto token_cost = [&](const ClassRec &c) -> uint64_t {
         const uint64_t bytes = (uint64_t)c.hs * c.row_bytes;
         return c.kind == kD128GQA ? bytes * a.gqa_cost_pct / 100 : bytes;
@@ -124,6 +120,7 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
         s.out_off = a.out_off[tid];
         s.ctx_len = a.ctx_len[tid];
         s.cls = cls;
+        s.req = tid;
         s.part_stride = part_stride_of(c);
         const uint64_t wk = kItemOverheadBytes + (uint64_t)s.ctx_len * token_cost(c);
         for (uint32_t sl = 0; sl < n_sl; ++sl) {
@@ -208,6 +205,8 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
     if (tid == 0) {
         counts[0] = (uint32_t)t_many;
         counts[1] = (uint32_t)t_few;
+        counts[2] = 0; // the decode launch's span queue starts at zero
+        counts[3] = n_spans;
     }
 
     // per span (one thread each): the sequences it meets, then its items
@@ -251,7 +250,10 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
             return t < n_tok ? (uint32_t)t : n_tok;
         };
         const uint32_t f_k = (uint32_t)(sk / span), np = (uint32_t)((ek - 1) / span) - f_k + 1;
-        items[i0 + e] = Item{k, cut(lo), cut(hi), np > 1 ? tid - f_k : kDirect};
+        ItemRec &r = items[i0 + e];
+        r.it = Item{k, cut(lo), cut(hi), np > 1 ? tid - f_k : kDirect};
+        r.s = seqs[k]; // complete: n_parts and part_off were written before the last workgroup barrier
+        r.c = a.classes.c[seqs[k].cls];
     }
 }
 
@@ -364,15 +366,20 @@ extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch
     a.page_table = b->page_table;
     a.q = b->q;
     a.out = (float *)b->out;
-    a.classes = (const ClassRec *)(sp + kOffClasses);
-    a.seqs = (const SeqRec *)(sp + kOffSeqs);
-    a.items = (const Item *)(sp + kOffItems);
+    a.recs = (const ItemRec *)(sp + kOffItems);
     a.span_first = (const uint32_t *)(sp + kOffSpans);
     a.partials = (float *)(sp + kOffPartials);
     a.counters = nullptr; // cut sequences are merged by the two launches below
+    a.merge_acq_rel = 0;
     a.new_k = nullptr;
     a.new_v = nullptr;
-    e = launch_decode(a, kStaticMaxSpans, (uint32_t)p->tun.block_threads, s, nullptr, nullptr);
+    a.delta = 0;
+    a.queue = (uint32_t *)(sp + kOffCounts) + 2;
+    a.queue_base = 0;
+    a.n_spans = kStaticMaxSpans;
+    a.n_spans_dev = (const uint32_t *)(sp + kOffCounts) + 3; // what the plan kernel made of the batch
+    e = launch_decode(a, nullptr, decode_grid(kStaticMaxSpans, (uint32_t)p->tun.block_threads, p->kinds),
+                      (uint32_t)p->tun.block_threads, p->kinds, s, nullptr, nullptr);
     if (e != hipSuccess) {
         set_error(std::string("launch decode kernel: ") + hipGetErrorString(e));
         return UKV_EHIP;

@@ -47,8 +47,22 @@ class DeviceBatch:
     def close(self):
         if self.pool:
             self.torch.cuda.synchronize()
+            if getattr(self, "plan", 0):
+                U.ukv_plan_destroy(self.plan)
+                self.plan = 0
             U.ukv_pool_destroy(self.pool)
             self.pool = 0
+
+    def make_plan(self):
+        """A plan kept across steps for the batch as it is now (it owns the workspace from here on)."""
+        if getattr(self, "plan", 0):
+            U.ukv_plan_destroy(self.plan)
+        self.plan = U.ukv_plan_create(self.pool, self.desc(), self.ws_t.data_ptr(), self.ws_bytes)
+        return self.plan
+
+    def plan_step(self, new_pages, advance=True):
+        """One decode step of the kept plan: every request grows by one token (append + attention, one launch)."""
+        U.ukv_plan_step(self.plan, new_pages, advance, None, self.stream())
 
     def resize_workspace(self):
         self.ws_bytes = U.ukv_decode_workspace_bytes(self.pool, self.b.n_requests)

@@ -90,6 +90,9 @@ def test_mini_configs_match_oracle(cfg, block):
         U.ukv_set_param(db.pool, U.UKV_PARAM_MIN_SPAN_BYTES, 48 * 1024)      # many cuts -> merge of partials
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)                 # (the default except for all-GQA pools)
         _check_attention(db, b, "cut into many items, merge fused into the decode launch")
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MERGE_ACQ_REL, 1)               # items counted with acquire-release
+        _check_attention(db, b, "cut into many items, merge fused, acquire-release count")
+        U.ukv_set_param(db.pool, U.UKV_PARAM_MERGE_ACQ_REL, 0)
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
         _check_attention(db, b, "cut into many items, merge in a second launch")
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)
