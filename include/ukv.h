@@ -91,9 +91,9 @@ typedef struct {
     uint64_t free_pages;
 } ukv_service_info_t;
 
-/* Unified block manager (section 5: "calculate proper block shape, and manage the cache
- * blocks"): validates the services against the page size and builds a LIFO free list that
- * first hands out pages 0, 1, 2, ...  No device work. */
+/* Unified block manager (section 5: the component that derives the block shape from the services' layer shapes
+ * and hands out the pool's blocks): validates the services against the page size and builds a LIFO free list
+ * that first hands out pages 0, 1, 2, ...  No device work. */
 int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out);
 int ukv_pool_destroy(ukv_pool_t *pool);
 int ukv_pool_info(const ukv_pool_t *pool, uint32_t service, ukv_service_info_t *out);

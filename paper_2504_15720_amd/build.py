@@ -61,16 +61,15 @@ def build_library(verbose: bool = False) -> str:
 
 
 CALIB_DIR = os.path.join(HERE, "calib")
-CALIB_PROGRAMS = [("hbm_calib", []), ("mfma_valu_overlap", []), ("mfma_valu_overlap_vgpr", ["-DVGPR_SOURCES"])]
+CALIB_PROGRAMS = [("hbm_calib", [])]
 CALIB_BIN = os.path.join(CALIB_DIR, "hbm_calib")
 
 
 def build_calib() -> str:
-    """The stand-alone measuring programs: the streaming copy/read program that calibrates the profiler's HBM
-    byte counters, and the matrix/vector instruction overlap probe."""
+    """The stand-alone streaming copy/read program that calibrates the profiler's HBM byte counters."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     for name, extra in CALIB_PROGRAMS:
-        src = name[:-len("_vgpr")] if name.endswith("_vgpr") else name
+        src = name
         cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument"] + \
             DEVICE_FLAGS + extra + [os.path.join(CALIB_DIR, src + ".hip"), "-o", os.path.join(CALIB_DIR, name)]
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -6,7 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
-#include <unordered_map>
+#include <utility>
 #include <vector>
 
 #include "ukv_internal.h"
@@ -58,6 +58,27 @@ int stage_release_after(ukv_pool::Stage *st, hipStream_t s) {
     st->pending = true;
     return UKV_OK;
 }
+
+// Once a kernel that reads a staging slot has been enqueued, the slot must not be rewritten before that kernel has
+// run, whatever way the call ends: leaving the scope with `launched` set records the slot's event (if even that
+// fails, the stream is drained).  The normal path calls done(), which reports errors.
+struct StageUse {
+    ukv_pool::Stage *st;
+    hipStream_t s;
+    bool launched = false;
+    int done() {
+        launched = false;
+        return stage_release_after(st, s);
+    }
+    ~StageUse() {
+        if (!launched)
+            return;
+        if (hipEventRecord(st->ev, s) == hipSuccess)
+            st->pending = true;
+        else
+            (void)hipStreamSynchronize(s);
+    }
+};
 
 // Profiling: the kernel's own start/stop timestamps, attached to its dispatch (no extra
 // barriers on the stream).  get() hands out a pair when profiling is on, else nulls.
@@ -512,7 +533,8 @@ int ukv_plan_step(ukv_plan_t *pl, const ukv_plan_io_t *io_in, int advance, const
     // The resident plan serves: one launch, the new page ids in its arguments.
     pl->sp.n_req = n;
     pl->sp.first[n] = (uint16_t)total;
-    std::memcpy(pl->sp.page, new_pages, (size_t)n_new_pages * sizeof(int32_t));
+    if (n_new_pages)
+        std::memcpy(pl->sp.page, new_pages, (size_t)n_new_pages * sizeof(int32_t));
     DecodeArgs a = pl->args;
     a.page_table = io.page_table;
     a.q = io.q;
@@ -602,9 +624,12 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
     std::memcpy(h + off_cls, &p->classes, sizeof(ClassTable));
     // Entries patched by this call are handed to the append workgroups directly, so that patching
     // and appending can share one launch; a token touching more than four pages takes two launches.
-    std::unordered_map<uint64_t, int32_t> patched;
+    std::vector<std::pair<uint64_t, int32_t>> &patched = p->patch_scratch; // (entry, page) by entry; storage reused
+    patched.clear();
     for (uint32_t i = 0; i < b->n_patches; ++i)
-        patched[b->patch_entry[i]] = b->patch_page[i];
+        patched.emplace_back(b->patch_entry[i], b->patch_page[i]);
+    std::stable_sort(patched.begin(), patched.end(),
+                     [](const std::pair<uint64_t, int32_t> &x, const std::pair<uint64_t, int32_t> &y) { return x.first < y.first; });
     bool one_launch = true;
     AppendRec *recs = (AppendRec *)(h + off_recs);
     for (uint32_t i = 0; i < n; ++i) {
@@ -617,9 +642,12 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
         if (last - first >= 4)
             one_launch = false;
         for (uint64_t k = 0; k <= last - first && k < 4; ++k) {
-            auto it = patched.find(b->table_off[i] + first + k);
-            if (it != patched.end())
-                recs[i].page[k] = it->second;
+            const uint64_t e = b->table_off[i] + first + k;
+            // the last patch of an entry wins, as it would if the patches were applied in order
+            auto it = std::upper_bound(patched.begin(), patched.end(), e,
+                                       [](uint64_t v, const std::pair<uint64_t, int32_t> &x) { return v < x.first; });
+            if (it != patched.begin() && (it - 1)->first == e)
+                recs[i].page[k] = (it - 1)->second;
         }
     }
     if (b->n_patches) {
@@ -629,10 +657,12 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
     // the records are small: the kernels read them straight from the pinned, device-mapped slot
     unsigned char *d = (unsigned char *)st->mapped;
     uint32_t patches_in_append = b->n_patches;
+    StageUse use{st, s};
     if (!one_launch) {
         HIP_TRY(launch_patch(b->page_table, (const uint64_t *)(d + off_pe), (const int32_t *)(d + off_pp),
                              b->n_patches, s),
                 "launch patch kernel");
+        use.launched = true;
         patches_in_append = 0;
     }
     ProfPair pp{p, 2};
@@ -643,7 +673,8 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
                           (const int32_t *)(d + off_pp), patches_in_append, s, pp.ev.a, pp.ev.b),
             "launch append kernel");
     pp.done();
-    return stage_release_after(st, s);
+    use.launched = true;
+    return use.done();
 }
 
 // n_last: null = whole requests; else only the n_last[i] last tokens of request i, which is then all
@@ -677,7 +708,8 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const 
     }
     hipStream_t s = (hipStream_t)stream;
     // one record (= one workgroup) per chunk of about 1 MiB of a request's stream
-    std::vector<GatherRec> chunks;
+    std::vector<GatherRec> &chunks = p->chunk_scratch; // storage reused from call to call
+    chunks.clear();
     for (uint32_t i = 0; i < n; ++i) {
         const uint32_t T = p->classes.c[b->service_id[i]].token_bytes;
         const uint32_t step = std::max<uint32_t>(1, (1u << 20) / T);

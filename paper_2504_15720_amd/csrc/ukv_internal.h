@@ -6,6 +6,7 @@
 #include <cstddef>
 #include <cstdint>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "ukv.h"
@@ -269,6 +270,8 @@ struct ukv_pool {
     int next_stage = 0;
 
     ukv::Plan plan_scratch;
+    std::vector<std::pair<uint64_t, int32_t>> patch_scratch; // ukv_append: the call's table patches, sorted by entry
+    std::vector<ukv::GatherRec> chunk_scratch;               // gather / scatter: the call's chunk records
 
     // profiling
     struct EvPair {
