@@ -297,6 +297,7 @@ def main():
                     help="ukv_decode_step in every step (host plan + upload) instead of the plan kept across steps")
     ap.add_argument("--replan-every", type=int, default=-1, help="UKV_PARAM_REPLAN_EVERY")
     ap.add_argument("--merge-acq-rel", action="store_true", help="UKV_PARAM_MERGE_ACQ_REL = 1")
+    ap.add_argument("--validate", action="store_true", help="UKV_PARAM_VALIDATE = 1 (page tables checked before every call)")
     ap.add_argument("--phase", choices=["decode", "prefill", "serve", "grid"], default="decode")
     ap.add_argument("--serve-requests", type=int, default=64, help="requests per service of the serving loop")
     ap.add_argument("--serve-clock", choices=["wall", "model"], default="wall",
@@ -367,6 +368,8 @@ def main():
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 0)
     if args.fused_merge:
         U.ukv_set_param(db.pool, U.UKV_PARAM_FUSED_MERGE, 1)
+    if args.validate:
+        U.ukv_set_param(db.pool, U.UKV_PARAM_VALIDATE, 1)
     if args.merge_acq_rel:
         U.ukv_set_param(db.pool, U.UKV_PARAM_MERGE_ACQ_REL, 1)
     if args.replan_every >= 0:

@@ -30,12 +30,14 @@
  *     per-call records into a staging slot), so a call recorded into a HIP graph would replay the batch it
  *     was recorded with; they are meant to be called, not captured.
  *   - The library never allocates or frees the pool memory itself.  It owns its host
- *     object, the free list and pinned, device-mapped staging buffers (per-call records).
+ *     object, the free list and pinned, device-mapped staging buffers (per-call records); with
+ *     UKV_PARAM_VALIDATE also one 256-byte device allocation per pool.
  *   - What lives in host memory is checked during the call (service ids, lengths against the
  *     pool size, page ids of patches, alignment of offsets).  What lives in device memory is
  *     not: every page id the kernels find in page_table for a request's ceil(n*T/page_bytes)
- *     pages must be below the pool's page count, and the offset arrays must stay inside the
- *     caller's q / out / new_k / new_v / page_table allocations.
+ *     pages must be below the pool's page count (UKV_PARAM_VALIDATE turns on a check on the device),
+ *     and the offset arrays must stay inside the caller's q / out / new_k / new_v / page_table
+ *     allocations.
  *   - There is no CPU fallback: without a usable HIP device the compute calls fail with
  *     UKV_EHIP.
  */
@@ -302,6 +304,13 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
                                         barrier before they count the item; 1 = the count is an agent-scope
                                         acquire-release, the ordering the language's memory model promises (4 to 8 % of
                                         the launch).  UKV_PARAM_FUSED_MERGE = 0 needs neither. */
+#define UKV_PARAM_VALIDATE 13        /* 1 = before the kernels of a compute call run, a small kernel checks that every
+                                        page-table entry the call will use names a page of the pool.  If one does not,
+                                        the call's kernels do nothing (no read or write through the table), and the next
+                                        compute call on the pool returns UKV_EINVAL, naming the entry (ukv_last_error).
+                                        One extra launch per call (and 256 bytes of device memory per pool, allocated
+                                        at the first checked call); default 0.  Not covered:
+                                        ukv_decode_attention_static. */
 #define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
                                         workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);

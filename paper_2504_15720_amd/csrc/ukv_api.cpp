@@ -121,6 +121,61 @@ struct ProfPair {
     }
 };
 
+// Opt-in check of the page tables (UKV_PARAM_VALIDATE).  report_bad_tables: at the start of every compute call,
+// turns what an earlier call's check found into UKV_EINVAL.  validate_tables: enqueues the check of entries
+// [0, ceil((ctx_len + adjust) T / P)) of every request (after the call's patches, before its kernels) and hands back
+// the device address of the flag that makes those kernels leave at once; null while the check is off.
+int report_bad_tables(ukv_pool *p, hipStream_t s) {
+    if (!p->tun.validate || !p->val_host)
+        return UKV_OK;
+    volatile ValReport *r = p->val_host;
+    if (!r->bad)
+        return UKV_OK;
+    HIP_TRY(hipMemsetAsync(p->val_flag, 0, sizeof(uint32_t), s), "hipMemsetAsync(check flag)");
+    set_error("an earlier checked call found page id " + std::to_string((long long)r->page) + " in page_table[" +
+              std::to_string((unsigned long long)r->entry) + "] (request " + std::to_string(r->req) +
+              " of that call); the pool has " + std::to_string((unsigned long long)p->n_pages) +
+              " pages.  The kernels of that call did nothing.");
+    r->bad = 0;
+    ++p->tun_epoch; // launches that left early did not advance their plan's span queue: kept plans are remade
+    return UKV_EINVAL;
+}
+
+int validate_tables(ukv_pool *p, uint32_t n, const uint32_t *service_id, const uint32_t *ctx_len,
+                    const uint64_t *table_off, const int32_t *page_table, int adjust, hipStream_t s,
+                    const uint32_t **bad_out) {
+    *bad_out = nullptr;
+    if (!p->tun.validate || n == 0)
+        return UKV_OK;
+    if (!p->val_host) {
+        void *h = nullptr, *d = nullptr;
+        HIP_TRY(hipHostMalloc(&h, sizeof(ValReport), hipHostMallocMapped), "hipHostMalloc");
+        std::memset(h, 0, sizeof(ValReport));
+        HIP_TRY(hipHostGetDevicePointer(&d, h, 0), "hipHostGetDevicePointer");
+        p->val_host = (ValReport *)h;
+        p->val_dev = (ValReport *)d;
+        void *f = nullptr;
+        HIP_TRY(hipMalloc(&f, 256), "hipMalloc(check flag)");
+        p->val_flag = (uint32_t *)f;
+        HIP_TRY(hipMemsetAsync(f, 0, 256, s), "hipMemsetAsync(check flag)");
+    }
+    ukv_pool::Stage *st = nullptr;
+    int rc = stage_acquire(p, align_up((size_t)n * sizeof(ValRec)), &st);
+    if (rc != UKV_OK)
+        return rc;
+    ValRec *recs = (ValRec *)st->host;
+    for (uint32_t i = 0; i < n; ++i) {
+        const int64_t c = (int64_t)ctx_len[i] + adjust;
+        recs[i] = ValRec{table_off[i], c > 0 ? ukv_pages_for_tokens(p, service_id[i], (uint64_t)c) : 0, i, 0};
+    }
+    HIP_TRY(launch_validate(page_table, (const ValRec *)st->mapped, n, p->n_pages, p->val_dev, p->val_flag, s),
+            "launch page-table check");
+    if ((rc = stage_release_after(st, s)) != UKV_OK)
+        return rc;
+    *bad_out = p->val_flag;
+    return UKV_OK;
+}
+
 struct BlobLayout {
     size_t recs, spans, reduce, counters, queue, total;
 };
@@ -267,6 +322,9 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
         return UKV_EINVAL;
     }
     hipStream_t s = (hipStream_t)stream;
+    int rc = report_bad_tables(p, s);
+    if (rc != UKV_OK)
+        return rc;
     if (p->tun.slots_auto) { // once per pool (and after a block-size change): what the device keeps resident
         const int r = decode_resident_workgroups((uint32_t)p->tun.block_threads);
         if (r > 0)
@@ -274,7 +332,7 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
         p->tun.slots_auto = false;
     }
     Plan &plan = p->plan_scratch; // storage reused from call to call
-    int rc = build_plan(p, b, plan);
+    rc = build_plan(p, b, plan);
     if (rc != UKV_OK)
         return rc;
     if (with_append)
@@ -333,6 +391,9 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
     a.new_k = with_append ? (const uint16_t *)b->new_k : nullptr;
     a.new_v = with_append ? (const uint16_t *)b->new_v : nullptr;
     a.delta = 0;
+    if ((rc = validate_tables(p, b->n_requests, b->service_id, b->ctx_len, b->table_off, b->page_table, 0, s,
+                              &a.bad)) != UKV_OK)
+        return rc;
     a.queue = (uint32_t *)(w + L.queue);
     a.queue_base = 0; // the upload has just zeroed the counter
     a.n_spans = n_spans;
@@ -531,6 +592,9 @@ int ukv_plan_step(ukv_plan_t *pl, const ukv_plan_io_t *io_in, int advance, const
         return UKV_OK;
     }
     // The resident plan serves: one launch, the new page ids in its arguments.
+    int rc = report_bad_tables(p, s);
+    if (rc != UKV_OK)
+        return rc;
     pl->sp.n_req = n;
     pl->sp.first[n] = (uint16_t)total;
     if (n_new_pages)
@@ -543,7 +607,10 @@ int ukv_plan_step(ukv_plan_t *pl, const ukv_plan_io_t *io_in, int advance, const
     a.new_v = (const uint16_t *)io.new_v;
     a.delta = pl->delta + grow;
     a.queue_base = pl->queue_at;
-    int rc;
+    // (the entries this step adds are not in the table yet: they were checked on the host above)
+    if ((rc = validate_tables(p, n, pl->service_id.data(), pl->ctx_len.data(), pl->table_off.data(), io.page_table,
+                              (int)grow - 1, s, &a.bad)) != UKV_OK)
+        return rc;
     if (pl->n_spans) {
         ProfPair pp{p, 0};
         if ((rc = pp.get()) != UKV_OK)
@@ -606,6 +673,9 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
         }
     }
     hipStream_t s = (hipStream_t)stream;
+    int rc = report_bad_tables(p, s);
+    if (rc != UKV_OK)
+        return rc;
     size_t o = 0;
     const size_t off_cls = o;
     o = align_up(o + sizeof(ClassTable));
@@ -616,7 +686,6 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
     const size_t off_pp = o;
     o = align_up(o + (size_t)b->n_patches * sizeof(int32_t));
     const size_t total = o;
-    int rc;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -630,7 +699,7 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
         patched.emplace_back(b->patch_entry[i], b->patch_page[i]);
     std::stable_sort(patched.begin(), patched.end(),
                      [](const std::pair<uint64_t, int32_t> &x, const std::pair<uint64_t, int32_t> &y) { return x.first < y.first; });
-    bool one_launch = true;
+    bool one_launch = !p->tun.validate; // a checked call writes its patches first, so that the check sees them
     AppendRec *recs = (AppendRec *)(h + off_recs);
     for (uint32_t i = 0; i < n; ++i) {
         recs[i] = AppendRec{b->table_off[i], b->new_off[i], b->ctx_len[i], b->service_id[i], {-1, -1, -1, -1}};
@@ -665,12 +734,15 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
         use.launched = true;
         patches_in_append = 0;
     }
+    const uint32_t *bad = nullptr;
+    if ((rc = validate_tables(p, n, b->service_id, b->ctx_len, b->table_off, b->page_table, 0, s, &bad)) != UKV_OK)
+        return rc;
     ProfPair pp{p, 2};
     if ((rc = pp.get()) != UKV_OK)
         return rc;
     HIP_TRY(launch_append(p->base, p->log2_page, b->page_table, (const AppendRec *)(d + off_recs), n,
                           (const ClassRec *)(d + off_cls), b->new_k, b->new_v, (const uint64_t *)(d + off_pe),
-                          (const int32_t *)(d + off_pp), patches_in_append, s, pp.ev.a, pp.ev.b),
+                          (const int32_t *)(d + off_pp), patches_in_append, bad, s, pp.ev.a, pp.ev.b),
             "launch append kernel");
     pp.done();
     use.launched = true;
@@ -707,6 +779,9 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const 
         }
     }
     hipStream_t s = (hipStream_t)stream;
+    int rc = report_bad_tables(p, s);
+    if (rc != UKV_OK)
+        return rc;
     // one record (= one workgroup) per chunk of about 1 MiB of a request's stream
     std::vector<GatherRec> &chunks = p->chunk_scratch; // storage reused from call to call
     chunks.clear();
@@ -722,7 +797,9 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const 
         return UKV_OK;
     const size_t off_recs = align_up(sizeof(ClassTable));
     const size_t total = align_up(off_recs + chunks.size() * sizeof(GatherRec));
-    int rc;
+    const uint32_t *bad = nullptr;
+    if ((rc = validate_tables(p, n, b->service_id, b->ctx_len, b->table_off, b->page_table, 0, s, &bad)) != UKV_OK)
+        return rc;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -731,7 +808,7 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const 
     std::memcpy(h + off_recs, chunks.data(), chunks.size() * sizeof(GatherRec));
     unsigned char *d = (unsigned char *)st->mapped;
     HIP_TRY(launch_copy_tokens(to_pool, p->base, p->log2_page, b->page_table, (const GatherRec *)(d + off_recs),
-                               (uint32_t)chunks.size(), (const ClassRec *)d, k_io, v_io, s),
+                               (uint32_t)chunks.size(), (const ClassRec *)d, k_io, v_io, bad, s),
             "launch token copy kernel");
     return stage_release_after(st, s);
 }
@@ -798,6 +875,10 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         set_error("workspace must be non-null and 256-byte aligned");
         return UKV_EINVAL;
     }
+    hipStream_t s = (hipStream_t)stream;
+    int rc = report_bad_tables(p, s);
+    if (rc != UKV_OK)
+        return rc;
     struct Group {
         uint64_t cost;
         uint32_t req, kvh;
@@ -886,7 +967,6 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         set_error("workspace too small for this batch");
         return UKV_ENOSPC;
     }
-    int rc;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -896,7 +976,6 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         std::memcpy(recs, list[0].data(), list[0].size() * sizeof(PrefillRec));
     if (!list[1].empty())
         std::memcpy(recs + list[0].size(), list[1].data(), list[1].size() * sizeof(PrefillRec));
-    hipStream_t s = (hipStream_t)stream;
     HIP_TRY(launch_stage_copy(workspace, st->mapped, total, nullptr, nullptr, nullptr, 0, s), "launch plan upload");
     if ((rc = stage_release_after(st, s)) != UKV_OK)
         return rc;
@@ -907,6 +986,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     a.page_table = b->page_table;
     a.q = (const uint16_t *)b->q;
     a.out = (float *)b->out;
+    if ((rc = validate_tables(p, n, b->service_id, b->ctx_len, b->table_off, b->page_table, 0, s, &a.bad)) != UKV_OK)
+        return rc;
     size_t first = 0;
     for (int di = 0; di < 2; ++di) {
         if (list[di].empty())

@@ -14,6 +14,30 @@ __global__ void patch_kernel(int32_t *page_table, const uint64_t *entry, const i
         page_table[entry[i]] = page[i];
 }
 
+// Opt-in check (UKV_PARAM_VALIDATE): every table entry a call is about to use must name a page of the pool.  One
+// workgroup per request; the first bad entry found is reported in pinned host memory, and its flag makes the call's
+// compute kernels leave at once.  The check only reads the table.
+__global__ void __launch_bounds__(256) validate_kernel(const int32_t *page_table, const ValRec *recs, uint64_t n_pages,
+                                                       ValReport *report, uint32_t *flag_dev) {
+    const ValRec r = recs[blockIdx.x];
+    for (uint64_t e = threadIdx.x; e < r.n_entries; e += blockDim.x) {
+        const int64_t pg = page_table[r.table_off + e];
+        if (pg < 0 || (uint64_t)pg >= n_pages) {
+            *flag_dev = 1u; // what the kernels of this and later calls read, until the host has reported
+            if (atomicCAS_system(&report->bad, 0u, 1u) == 0u) { // the first one to find something describes it
+                report->req = r.req;
+                report->entry = r.table_off + e;
+                report->page = pg;
+            }
+        }
+    }
+}
+
+// The flag of that check (device memory), read by the kernels of the checked call: one load per workgroup.
+__device__ __forceinline__ bool tables_bad(const uint32_t *bad) {
+    return bad != nullptr && *reinterpret_cast<const volatile uint32_t *>(bad) != 0;
+}
+
 // Workgroups [0, n_requests): one per request; each lane moves 16-byte pieces of the new token
 // row.  Page ids of table entries that are being patched in the same call come with the record
 // (r.page[k] >= 0 for the k-th page the token touches), so no workgroup reads an entry another one
@@ -22,7 +46,10 @@ __global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, u
                                                      const AppendRec *recs, uint32_t n_requests,
                                                      const ClassRec *classes, const uint16_t *new_k,
                                                      const uint16_t *new_v, const uint64_t *patch_entry,
-                                                     const int32_t *patch_page, uint32_t n_patches) {
+                                                     const int32_t *patch_page, uint32_t n_patches,
+                                                     const uint32_t *bad) {
+    if (tables_bad(bad))
+        return;
     if (blockIdx.x >= n_requests) {
         const uint32_t i = (blockIdx.x - n_requests) * blockDim.x + threadIdx.x;
         if (i < n_patches)
@@ -59,7 +86,10 @@ __global__ void __launch_bounds__(256) append_kernel(unsigned char *pool_base, u
 template <bool TO_POOL>
 __global__ void __launch_bounds__(256) copy_tokens_kernel(unsigned char *pool_base, uint32_t lg,
                                                           const int32_t *page_table, const GatherRec *recs,
-                                                          const ClassRec *classes, uint16_t *k_io, uint16_t *v_io) {
+                                                          const ClassRec *classes, uint16_t *k_io, uint16_t *v_io,
+                                                          const uint32_t *bad) {
+    if (tables_bad(bad))
+        return;
     const GatherRec r = recs[blockIdx.x];
     const ClassRec c = classes[r.cls];
     const uint32_t pieces_per_row = c.row_bytes / 16, half = pieces_per_row / 2;
@@ -129,6 +159,14 @@ hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, in
     return hipGetLastError();
 }
 
+hipError_t launch_validate(const int32_t *page_table, const ValRec *recs, uint32_t n, uint64_t n_pages,
+                           ValReport *report, uint32_t *flag_dev, hipStream_t s) {
+    if (n == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(validate_kernel, dim3(n), dim3(256), 0, s, page_table, recs, n_pages, report, flag_dev);
+    return hipGetLastError();
+}
+
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s) {
     if (n == 0)
@@ -139,28 +177,28 @@ hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_
 
 hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,
                          uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
-                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
-                         hipEvent_t ev0, hipEvent_t ev1) {
+                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
+                         const uint32_t *bad, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     const uint32_t blocks = n + (n_patches + 255) / 256;
     if (blocks == 0)
         return hipSuccess;
     hipExtLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, s, ev0, ev1, 0, pool_base, log2_page, page_table,
                           recs, n, classes, static_cast<const uint16_t *>(new_k),
-                          static_cast<const uint16_t *>(new_v), patch_entry, patch_page, n_patches);
+                          static_cast<const uint16_t *>(new_v), patch_entry, patch_page, n_patches, bad);
     return hipGetLastError();
 }
 
 hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                               const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
-                              hipStream_t s) {
+                              const uint32_t *bad, hipStream_t s) {
     if (n == 0)
         return hipSuccess;
     if (to_pool)
         hipLaunchKernelGGL(copy_tokens_kernel<true>, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table,
-                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
+                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io), bad);
     else
         hipLaunchKernelGGL(copy_tokens_kernel<false>, dim3(n), dim3(256), 0, s, pool_base, log2_page, page_table,
-                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io));
+                           recs, classes, static_cast<uint16_t *>(k_io), static_cast<uint16_t *>(v_io), bad);
     return hipGetLastError();
 }
 

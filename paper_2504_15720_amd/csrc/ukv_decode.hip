@@ -60,6 +60,7 @@ __device__ __forceinline__ DecodeArgs ctx_args() {
     a.new_k = nullptr; // the fused-append inputs are fetched where they are used (new_token_rows)
     a.new_v = nullptr;
     a.delta = 0;       // already applied to the item and the sequence in LDS
+    a.bad = nullptr;
     return a;
 }
 __device__ __forceinline__ SeqRec ctx_seq() {
@@ -838,6 +839,9 @@ __device__ __forceinline__ uint32_t take_span(const DecodeArgs &a) {
 
 template <int NT, uint32_t KINDS>
 __device__ __forceinline__ void decode_body(const DecodeArgs &a, const StepPages &sp) {
+    // a checked call (UKV_PARAM_VALIDATE) whose page tables hold an id outside the pool does nothing
+    if (a.bad != nullptr && uni(*reinterpret_cast<const volatile uint32_t *>(a.bad)) != 0)
+        return;
     if (threadIdx.x == 0)
         s_ctx.a = a;
     const uint32_t grid = gridDim.x;

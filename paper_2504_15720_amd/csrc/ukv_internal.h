@@ -99,6 +99,7 @@ struct DecodeArgs {
     // A plan that outlives its step: every sequence has grown by `delta` tokens since the plan was made; the growth
     // goes to the sequence's last item (the one whose t1 equals the planned ctx_len).  0 for a plan made for this call.
     uint32_t delta;
+    const uint32_t *bad; // null, or the flag of the page-table check: set = leave at once
     // Spans are handed out through a queue in device memory: the launch has one workgroup per place the device
     // offers (grid <= n_spans); workgroup w starts with span w, and a workgroup that has finished a span takes the
     // next one, whichever XCD it runs on.  (The hardware deals the workgroups of a grid out to the XCDs in turn, and
@@ -123,6 +124,23 @@ struct StepPages {
     int32_t page[kStepMaxPages];
 };
 static_assert(sizeof(DecodeArgs) + sizeof(StepPages) <= 4096, "decode kernel arguments exceed 4 KiB");
+
+// Opt-in check of the page tables a call is about to use (UKV_PARAM_VALIDATE): one record per request.
+struct ValRec {
+    uint64_t table_off;
+    uint64_t n_entries; // entries [0, n_entries) of the request's table are checked
+    uint32_t req;
+    uint32_t pad_;
+};
+// What the check reports, in pinned host memory that the device writes: the first bad entry found.  (The kernels
+// of a checked call read a flag in device memory instead, set together with `bad`: a read of host memory at the
+// start of every workgroup was measured at a third of the decode launch.)
+struct ValReport {
+    uint32_t bad; // 0 = nothing found
+    uint32_t req;
+    uint64_t entry; // index into page_table
+    int64_t page;
+};
 
 struct ReduceRec {
     uint64_t part_off;
@@ -165,6 +183,7 @@ struct PrefillArgs {
     const uint16_t *q; // bf16
     float *out;
     const PrefillRec *recs;
+    const uint32_t *bad; // null, or the flag of the page-table check: set = leave at once
 };
 static constexpr uint32_t kPrefillBlocks = 2; // 16-column blocks per wave
 static constexpr uint32_t kPrefillWaves = 4;  // waves per workgroup (8 was measured: slower, one workgroup per CU)
@@ -192,17 +211,19 @@ hipError_t launch_reduce(const ReduceRec *recs, uint32_t n_recs, uint32_t n_many
 hipError_t launch_reduce_counted(const ReduceRec *many, const uint32_t *n_many_dev, uint32_t many_bound,
                                  const ReduceRec *few, const uint32_t *n_few_dev, uint32_t few_bound, uint32_t max_heads,
                                  uint32_t max_units, const float *partials, float *out, hipStream_t s);
+hipError_t launch_validate(const int32_t *page_table, const ValRec *recs, uint32_t n, uint64_t n_pages,
+                           ValReport *report, uint32_t *flag_dev, hipStream_t s);
 hipError_t launch_patch(int32_t *page_table, const uint64_t *entry, const int32_t *page, uint32_t n,
                         hipStream_t s);
 hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *page_table, const AppendRec *recs,
                          uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
-                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches, hipStream_t s,
-                         hipEvent_t ev0, hipEvent_t ev1);
+                         const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
+                         const uint32_t *bad, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, hipStream_t s, hipEvent_t ev0,
                           hipEvent_t ev1);
 hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                               const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
-                              hipStream_t s);
+                              const uint32_t *bad, hipStream_t s);
 
 // ---- host planner (ukv_planner.cpp) ----
 struct Plan {
@@ -232,6 +253,7 @@ struct Tunables {
     int64_t gqa_cost_pct = 150; // planner weight of a matrix-core (grouped-query) KV byte, percent
     int64_t prefill_xcd = 1;
     int64_t merge_acq_rel = 0;
+    int64_t validate = 0; // check the page tables a call uses before its kernels run
     int64_t replan_every = 64; // a kept plan is remade after its requests have grown by this many tokens
     bool slots_auto = true;
 };
@@ -270,6 +292,9 @@ struct ukv_pool {
     int next_stage = 0;
 
     ukv::Plan plan_scratch;
+    ukv::ValReport *val_host = nullptr; // pinned; val_dev is the device's address of the same memory
+    ukv::ValReport *val_dev = nullptr;
+    uint32_t *val_flag = nullptr; // device memory (256 bytes, allocated when the check is first used): set = leave
     std::vector<std::pair<uint64_t, int32_t>> patch_scratch; // ukv_append: the call's table patches, sorted by entry
     std::vector<ukv::GatherRec> chunk_scratch;               // gather / scatter: the call's chunk records
 

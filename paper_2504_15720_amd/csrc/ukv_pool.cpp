@@ -168,6 +168,10 @@ int ukv_pool_destroy(ukv_pool_t *p) {
         if (st.host && hipHostFree(st.host) != hipSuccess)
             rc = UKV_EHIP;
     }
+    if (p->val_host && hipHostFree(p->val_host) != hipSuccess)
+        rc = UKV_EHIP;
+    if (p->val_flag && hipFree(p->val_flag) != hipSuccess)
+        rc = UKV_EHIP;
     for (auto *v : {&p->ev_used, &p->ev_free})
         for (auto &e : *v) {
             (void)hipEventDestroy(e.a);
@@ -245,11 +249,14 @@ int ukv_pages_free(ukv_pool_t *p, uint32_t n, const int32_t *ids) {
 int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
     if (!p)
         return fail(UKV_EINVAL, "null pool");
-    if (key != UKV_PARAM_PROFILE)
+    if (key != UKV_PARAM_PROFILE && key != UKV_PARAM_VALIDATE)
         ++p->tun_epoch; // kept plans are remade
     switch (key) {
     case UKV_PARAM_MERGE_ACQ_REL:
         p->tun.merge_acq_rel = value ? 1 : 0;
+        return UKV_OK;
+    case UKV_PARAM_VALIDATE:
+        p->tun.validate = value ? 1 : 0;
         return UKV_OK;
     case UKV_PARAM_REPLAN_EVERY:
         if (value < 0 || value > (1 << 20))
@@ -327,6 +334,7 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_PREFILL_XCD: *value = p->tun.prefill_xcd; return UKV_OK;
     case UKV_PARAM_REPLAN_EVERY: *value = p->tun.replan_every; return UKV_OK;
     case UKV_PARAM_MERGE_ACQ_REL: *value = p->tun.merge_acq_rel; return UKV_OK;
+    case UKV_PARAM_VALIDATE: *value = p->tun.validate; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

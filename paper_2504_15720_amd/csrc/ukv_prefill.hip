@@ -38,6 +38,9 @@ typedef const __attribute__((address_space(1))) void *global_ptr_t;
 
 template <int NB, int NW, int D>
 __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
+    // a checked call (UKV_PARAM_VALIDATE) whose page tables hold an id outside the pool does nothing
+    if (a.bad != nullptr && uni(*reinterpret_cast<const volatile uint32_t *>(a.bad)) != 0)
+        return;
     constexpr int NT = 64 * NW;             // NW = 4 or 8 waves; D = 128 or 64
     constexpr uint32_t KB = 2 * D;          // bytes of the K (or V) part of a head-row
     constexpr uint32_t PIECES = KB / 16;    // 16-byte pieces of it

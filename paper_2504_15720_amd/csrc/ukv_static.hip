@@ -374,6 +374,7 @@ extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch
     a.new_k = nullptr;
     a.new_v = nullptr;
     a.delta = 0;
+    a.bad = nullptr; // (UKV_PARAM_VALIDATE does not cover this entry point: its check needs staging memory)
     a.queue = (uint32_t *)(sp + kOffCounts) + 2;
     a.queue_base = 0;
     a.n_spans = kStaticMaxSpans;

@@ -40,6 +40,18 @@ hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) {
     return hipSuccess;
 }
 hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
+hipError_t hipMalloc(void **p, size_t n) {
+    *p = std::malloc(n ? n : 1);
+    return *p ? hipSuccess : hipErrorOutOfMemory;
+}
+hipError_t hipFree(void *p) {
+    std::free(p);
+    return hipSuccess;
+}
+hipError_t hipMemsetAsync(void *p, int v, size_t n, hipStream_t) {
+    std::memset(p, v, n);
+    return hipSuccess;
+}
 const char *hipGetErrorString(hipError_t) { return "fake hip error"; }
 }
 
@@ -65,6 +77,23 @@ hipError_t launch_stage_copy(void *dst, const void *src, size_t bytes, int32_t *
     std::memcpy(dst, src, (bytes + 15) / 16 * 16); // the kernel moves whole 16-byte pieces
     for (uint32_t i = 0; i < n_patches; ++i)
         page_table[pe[i]] = pp[i];
+    return hipSuccess;
+}
+
+hipError_t launch_validate(const int32_t *page_table, const ValRec *recs, uint32_t n, uint64_t n_pages,
+                           ValReport *report, uint32_t *flag_dev, hipStream_t) {
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint64_t e = 0; e < recs[i].n_entries; ++e) {
+            const int64_t pg = page_table[recs[i].table_off + e];
+            if (pg < 0 || (uint64_t)pg >= n_pages)
+                *flag_dev = 1;
+            if ((pg < 0 || (uint64_t)pg >= n_pages) && !report->bad) {
+                report->bad = 1;
+                report->req = recs[i].req;
+                report->entry = recs[i].table_off + e;
+                report->page = pg;
+            }
+        }
     return hipSuccess;
 }
 
@@ -112,6 +141,8 @@ hipError_t launch_decode(const DecodeArgs &a, const StepPages *sp_in, uint32_t g
                          hipEvent_t, hipEvent_t) {
     static const StepPages none{};
     const StepPages &sp = sp_in ? *sp_in : none;
+    if (a.bad && *a.bad)
+        return hipSuccess;
     if (grid == 0 || grid > a.n_spans)
         die("grid must be in [1, n_spans]");
     if (a.log2_page != g_fake.log2_page)
@@ -144,7 +175,9 @@ hipError_t launch_reduce_counted(const ReduceRec *, const uint32_t *, uint32_t, 
 
 hipError_t launch_append(unsigned char *, uint32_t lg, int32_t *page_table, const AppendRec *recs, uint32_t n,
                          const ClassRec *classes, const void *, const void *, const uint64_t *pe, const int32_t *pp,
-                         uint32_t n_patches, hipStream_t, hipEvent_t, hipEvent_t) {
+                         uint32_t n_patches, const uint32_t *bad, hipStream_t, hipEvent_t, hipEvent_t) {
+    if (bad && *bad)
+        return hipSuccess;
     for (uint32_t i = 0; i < n; ++i) {
         const AppendRec &r = recs[i];
         if (r.ctx_len == 0)
@@ -166,6 +199,8 @@ hipError_t launch_append(unsigned char *, uint32_t lg, int32_t *page_table, cons
 }
 
 hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t, hipStream_t, hipEvent_t, hipEvent_t) {
+    if (a.bad && *a.bad)
+        return hipSuccess;
     for (uint32_t i = 0; i < n_recs; ++i) {
         const PrefillRec &r = a.recs[i];
         if (r.q_len == 0)
@@ -181,7 +216,9 @@ hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t, hipSt
 }
 
 hipError_t launch_copy_tokens(bool, unsigned char *, uint32_t lg, const int32_t *page_table, const GatherRec *recs,
-                              uint32_t n, const ClassRec *classes, void *, void *, hipStream_t) {
+                              uint32_t n, const ClassRec *classes, void *, void *, const uint32_t *bad, hipStream_t) {
+    if (bad && *bad)
+        return hipSuccess;
     for (uint32_t i = 0; i < n; ++i) {
         const GatherRec &r = recs[i];
         if (r.t0 >= r.t1 || r.flat_t0 > r.t0)

@@ -142,6 +142,7 @@ static void run_scenario(uint32_t round) {
     if (rnd_below(4) == 0)
         EXPECT(ukv_set_param(sc.pool, UKV_PARAM_PROFILE, 1 + rnd_below(3)) == UKV_OK);
     EXPECT(ukv_set_param(sc.pool, UKV_PARAM_REPLAN_EVERY, rnd_below(12)) == UKV_OK);
+    EXPECT(ukv_set_param(sc.pool, UKV_PARAM_VALIDATE, rnd_below(2)) == UKV_OK);
     sc.resize_ws();
 
     ukv_batch_t b = sc.batch();
@@ -271,6 +272,20 @@ static void bad_arguments() {
     EXPECT(ukv_decode_step(pool, &b, ws, wsb, nullptr) == UKV_EINVAL);
     EXPECT(ukv_append(pool, &b, nullptr) == UKV_EINVAL);
     b.n_patches = 0;
+    // the opt-in check: a table entry outside the pool stops the call's kernels and the next call says so
+    EXPECT(ukv_set_param(pool, UKV_PARAM_VALIDATE, 1) == UKV_OK);
+    EXPECT(ukv_decode_attention(pool, &b, ws, wsb, nullptr) == UKV_OK);
+    table[1] = 64;
+    EXPECT(ukv_decode_attention(pool, &b, ws, wsb, nullptr) == UKV_OK); // enqueued; its kernels leave at once
+    EXPECT(ukv_gather(pool, &b, dummy, dummy, &zero, nullptr) == UKV_EINVAL);
+    EXPECT(std::strstr(ukv_last_error(), "page id 64") != nullptr);
+    table[1] = -3;
+    EXPECT(ukv_append(pool, &b, nullptr) == UKV_OK);
+    EXPECT(ukv_decode_attention(pool, &b, ws, wsb, nullptr) == UKV_EINVAL);
+    table[1] = 1;
+    EXPECT(ukv_decode_attention(pool, &b, ws, wsb, nullptr) == UKV_OK);
+    EXPECT(ukv_decode_attention(pool, &b, ws, wsb, nullptr) == UKV_OK);
+    EXPECT(ukv_set_param(pool, UKV_PARAM_VALIDATE, 0) == UKV_OK);
     uint32_t q_len = 9;
     EXPECT(ukv_prefill_attention(pool, &b, &q_len, ws, wsb, nullptr) == UKV_EINVAL);
     EXPECT(ukv_scatter_tokens(pool, &b, &q_len, dummy, dummy, &zero, nullptr) == UKV_EINVAL);
