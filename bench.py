@@ -39,15 +39,18 @@ WORKLOAD_NAMES = {
 
 
 def read_traffic(cfg: int):
-    """HBM bytes per decode launch from the committed rocprofv3 --pmc summary, if there is one
-    (bytes of the profiled run, and their ratio to that run's algorithmic bytes)."""
-    path = os.path.join(ROOT, "profiles", f"decode_kernel_cfg{cfg}_pmc.txt")
+    """HBM bytes per decode launch as the hardware counters gave them.  They cannot be read inside this run (they
+    need two rocprofv3 --pmc passes), so they come from the committed summary of such passes over this command,
+    together with the algorithmic bytes of THAT run (a few steps earlier in the same batch's life, so a fraction of
+    a per cent smaller than this run's) and their ratio: (traffic, source) or (None, None)."""
+    name = f"decode_kernel_cfg{cfg}_pmc.txt"
     try:
-        text = open(path).read()
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
-        r = re.search(r"^traffic_over_algorithmic:\s*([0-9.eE+]+)", text, re.M)
-        return (float(m.group(1)) if m else None), (float(r.group(1)) if r else None)
-    except OSError:
+        text = open(os.path.join(ROOT, "profiles", name)).read()
+        get = lambda key: float(re.search(rf"^{key}:\s*([0-9.eE+]+)", text, re.M).group(1))
+        return get("traffic_bytes_per_launch"), {
+            "file": "profiles/" + name, "algorithmic_bytes_per_launch_in_that_run": int(get("algorithmic_bytes_per_launch")),
+            "traffic_over_algorithmic": get("traffic_over_algorithmic")}
+    except (OSError, AttributeError):
         return None, None
 
 
@@ -325,6 +328,8 @@ def main():
               "collectives. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    if args.steps < 3 * args.time_every:      # short runs (profiler passes): time every launch
+        args.time_every = 1
     if args.phase == "prefill":
         return main_prefill(args)
     if args.phase == "serve":
@@ -455,8 +460,8 @@ def main():
         "attention_kernels_gbs": round(kv_per_step / ((dec_ms + red_ms) * 1e-3) / 1e9, 2),
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": read_traffic(args.config)[0],
-                     "traffic_over_algorithmic": read_traffic(args.config)[1]},
+                     "traffic": read_traffic(args.config)[0] if not args.as_stated_pool and args.layout == "merged" else None,
+                     "traffic_source": read_traffic(args.config)[1]},
         "setup_s": round(t_gen, 1),
     }
     if kv_per_step < 256e6:  # smaller than the 256 MB of last-level cache: the launch never goes to HBM
