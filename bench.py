@@ -121,8 +121,10 @@ def main_prefill(args):
     db = DeviceBatch(b, profile=True)
     if args.prefill_no_xcd:
         U.ukv_set_param(db.pool, U.UKV_PARAM_PREFILL_XCD, 0)
+    U.ukv_set_param(db.pool, U.UKV_PARAM_PREFILL_WEIGHTS, args.prefill_weights)
     q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, ctx, rng)
     _, run = db.prefill(ctx, q_bits, q_off, out_off, n_el)
+    form = U.ukv_get_param(db.pool, U.UKV_PARAM_PREFILL_FORM_USED)
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
@@ -142,9 +144,10 @@ def main_prefill(args):
         "metric": "prefill-attention TFLOP/s (causal, paged KV), 1 GPU", "value": round(flops * args.steps / wall / 1e12, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16" if form == 2 else "bf16 scores, fp16 weights x fp16 V", "data": "synthetic",
         "config": {"workload": f"prefill/{args.prefill_workload}: {n} whole prompts, services {names}, lengths {law}",
-                   "prompt_tokens": tokens, "flops_per_step": flops, "page_bytes": b.page_bytes},
+                   "prompt_tokens": tokens, "flops_per_step": flops, "page_bytes": b.page_bytes,
+                   "softmax_weights": "two bf16 parts" if form == 2 else "one fp16 part (step includes the fp16 copy of V)"},
         "prompt_tokens_per_s": round(tokens * args.steps / wall, 1),
         "kernel_ms": {"prefill": round(k_ms, 4)},
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
@@ -307,6 +310,8 @@ def main():
                     help="time charged to the scheduler's budgets: measured wall time, or a model of the batch (reproducible)")
     ap.add_argument("--prefill-workload", choices=list(PREFILL_WORKLOADS), default="chat")
     ap.add_argument("--prefill-no-xcd", action="store_true")
+    ap.add_argument("--prefill-weights", type=int, choices=[0, 1, 2], default=0,
+                    help="form of the softmax weights: 0 = the library's choice, 1 = one fp16 part, 2 = two bf16 parts")
     ap.add_argument("--taper", type=int, default=0)
     ap.add_argument("--gqa-cost-pct", type=int, default=0)
     ap.add_argument("--unfused-merge", action="store_true", help="merge split partials in a second launch")

@@ -237,8 +237,21 @@ int ukv_decode_attention_static(ukv_pool_t *pool, const ukv_device_batch_t *batc
  * fp32 accumulation as in ukv_decode_attention.  Every shape ukv_pool_create accepts is supported
  * (requests of head_dim 128 and of head_dim 64 run as two launches).  workspace: DEVICE, 256-byte aligned, at least
  * ukv_prefill_workspace_bytes(pool, n_requests, sum of q_len) bytes; else UKV_ENOSPC.
- * Uses service_id, ctx_len, table_off, page_table, q, q_off, out, out_off. */
+ * Uses service_id, ctx_len, table_off, page_table, q, q_off, out, out_off.
+ *
+ * The softmax weights reach the matrix cores in one of two forms (UKV_PARAM_PREFILL_WEIGHTS):
+ *   two bf16 parts (16 significant bits; results within about 1e-5 of exact arithmetic on unit-scale values), or
+ *   one fp16 part (11 bits: a result is off by at most 2^-12 times the largest distance of a V element of its row
+ *   from it -- about 1e-4 on unit-scale values -- and 1.3 times faster).  The one-part form multiplies fp16 by
+ *   fp16, so a first pass copies the V rows the call needs, as fp16, into the workspace (V elements beyond
+ *   +-65504 saturate, elements below 2^-24 in magnitude become 0), which then has to hold
+ *   ukv_prefill_workspace_bytes_one_part(pool, n_requests, sum of q_len, sum of ctx_len over the requests
+ *   with q_len > 0) bytes.  By default the call takes the one-part form when the workspace is that large and the
+ *   batch has at least 2000 flop of attention per byte of that copy (whole prompts of a few hundred tokens and more;
+ *   below that the copy costs more than it saves), and the two-part form otherwise. */
 size_t ukv_prefill_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests, uint64_t total_q_rows);
+size_t ukv_prefill_workspace_bytes_one_part(const ukv_pool_t *pool, uint32_t n_requests, uint64_t total_q_rows,
+                                            uint64_t total_ctx_tokens);
 int ukv_prefill_attention(ukv_pool_t *pool, const ukv_batch_t *batch, const uint32_t *q_len, void *workspace,
                           size_t ws_bytes, void *stream);
 
@@ -311,6 +324,12 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
                                         One extra launch per call (and 256 bytes of device memory per pool, allocated
                                         at the first checked call); default 0.  Not covered:
                                         ukv_decode_attention_static. */
+#define UKV_PARAM_PREFILL_WEIGHTS 14 /* form of the softmax weights in ukv_prefill_attention: 0 (default) = one fp16 part
+                                        where the workspace has room for the fp16 copy of V and the batch is large
+                                        enough to pay for it, else two bf16 parts; 1 = always one part (UKV_ENOSPC if
+                                        the workspace is too small); 2 = always two parts */
+#define UKV_PARAM_PREFILL_FORM_USED 15 /* read only: the form the pool's last ukv_prefill_attention call took (1 or 2;
+                                        0 before the first call) */
 #define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
                                         workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);

@@ -21,13 +21,15 @@ UKV_MAX_SERVICES = 16
 UKV_PARAM_MAX_SPANS, UKV_PARAM_MIN_SPAN_BYTES, UKV_PARAM_BLOCK_THREADS = 1, 2, 3
 UKV_PARAM_HEADS_PER_SLICE, UKV_PARAM_PROFILE, UKV_PARAM_FUSED_MERGE = 4, 5, 6
 UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT, UKV_PARAM_PREFILL_XCD = 7, 8, 9, 10
-UKV_PARAM_REPLAN_EVERY, UKV_PARAM_MERGE_ACQ_REL, UKV_PARAM_VALIDATE = 11, 12, 13
+UKV_PARAM_REPLAN_EVERY, UKV_PARAM_MERGE_ACQ_REL, UKV_PARAM_VALIDATE, UKV_PARAM_PREFILL_WEIGHTS = 11, 12, 13, 14
+UKV_PARAM_PREFILL_FORM_USED = 15
 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",
     "ukv_pages_free", "ukv_append", "ukv_decode_workspace_bytes", "ukv_decode_attention", "ukv_decode_step",
     "ukv_plan_create", "ukv_plan_step", "ukv_plan_lengths", "ukv_plan_destroy",
-    "ukv_decode_attention_static", "ukv_prefill_workspace_bytes", "ukv_prefill_attention",
+    "ukv_decode_attention_static", "ukv_prefill_workspace_bytes", "ukv_prefill_workspace_bytes_one_part",
+    "ukv_prefill_attention",
     "ukv_gather",
     "ukv_scatter",
     "ukv_scatter_tokens",
@@ -136,6 +138,8 @@ def lib():
         L.ukv_decode_attention_static.argtypes = [vp, C.POINTER(ukv_device_batch_t), vp]
         L.ukv_prefill_workspace_bytes.argtypes = [vp, C.c_uint32, C.c_uint64]
         L.ukv_prefill_workspace_bytes.restype = C.c_size_t
+        L.ukv_prefill_workspace_bytes_one_part.argtypes = [vp, C.c_uint32, C.c_uint64, C.c_uint64]
+        L.ukv_prefill_workspace_bytes_one_part.restype = C.c_size_t
         L.ukv_prefill_attention.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, C.c_size_t, vp]
         L.ukv_gather.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
         L.ukv_scatter.argtypes = [vp, C.POINTER(ukv_batch_t), vp, vp, vp, vp]
@@ -296,6 +300,10 @@ def ukv_decode_attention_static(pool: int, n_requests: int, service_id_ptr: int,
 
 def ukv_prefill_workspace_bytes(pool: int, n_requests: int, total_q_rows: int) -> int:
     return int(lib().ukv_prefill_workspace_bytes(pool, n_requests, total_q_rows))
+
+
+def ukv_prefill_workspace_bytes_one_part(pool: int, n_requests: int, total_q_rows: int, total_ctx_tokens: int) -> int:
+    return int(lib().ukv_prefill_workspace_bytes_one_part(pool, n_requests, total_q_rows, total_ctx_tokens))
 
 
 def ukv_prefill_attention(pool: int, batch: BatchDesc, q_len, workspace_ptr: int, ws_bytes: int,

@@ -854,6 +854,29 @@ size_t ukv_prefill_workspace_bytes(const ukv_pool_t *p, uint32_t n_requests, uin
     return align_up(prefill_rec_bound(p, n_requests, total_q_rows) * sizeof(PrefillRec));
 }
 
+// One-part weights: the copy pass takes a request's tokens in chunks of about kV16ChunkBytes of V (all kv heads).
+static constexpr uint64_t kV16ChunkBytes = 64 * 1024; // small enough that a few prompts already give every SIMD several waves
+static constexpr uint64_t kOnePartFlopPerByte = 2000; // below this the copy pass costs more than the products it saves
+static uint32_t v16_chunk_tokens(const ClassRec &c) {
+    const uint64_t per_token = (uint64_t)c.n_kv * 2 * c.d;
+    return (uint32_t)std::min<uint64_t>(4096, std::max<uint64_t>(8, kV16ChunkBytes / per_token));
+}
+
+size_t ukv_prefill_workspace_bytes_one_part(const ukv_pool_t *p, uint32_t n_requests, uint64_t total_q_rows,
+                                            uint64_t total_ctx_tokens) {
+    if (!p)
+        return 0;
+    uint64_t max_row = 1, min_chunk = 4096;
+    for (uint32_t s = 0; s < p->n_services; ++s) {
+        const ClassRec &c = p->classes.c[s];
+        max_row = std::max<uint64_t>(max_row, (uint64_t)c.n_kv * 2 * c.d);
+        min_chunk = std::min<uint64_t>(min_chunk, v16_chunk_tokens(c));
+    }
+    const uint64_t n_chunks = total_ctx_tokens / min_chunk + n_requests;
+    return ukv_prefill_workspace_bytes(p, n_requests, total_q_rows) + align_up((size_t)(n_chunks * sizeof(V16Rec))) +
+           (size_t)(total_ctx_tokens * max_row) + 256 * (size_t)n_requests;
+}
+
 int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q_len, void *workspace,
                           size_t ws_bytes, void *stream) {
     if (!p || !b) {
@@ -885,6 +908,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     };
     std::vector<Group> groups;
     uint64_t total_rows = 0;
+    std::vector<uint64_t> v16_base(n, 0); // one-part weights: where request i's fp16 V rows start, relative to the copy's start
+    uint64_t v16_bytes = 0, n_chunks = 0, flops = 0;
     for (uint32_t i = 0; i < n; ++i) {
         if (b->service_id[i] >= p->n_services) {
             set_error("service_id out of range");
@@ -915,6 +940,10 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         const uint64_t cost = (first + last) * q_len[i] / 2 * c.g;
         for (uint32_t h = 0; h < c.n_kv; ++h)
             groups.push_back(Group{cost, i, h});
+        v16_base[i] = v16_bytes;
+        v16_bytes += align_up((size_t)((uint64_t)b->ctx_len[i] * c.n_kv * 2 * c.d));
+        n_chunks += ((uint64_t)b->ctx_len[i] + v16_chunk_tokens(c) - 1) / v16_chunk_tokens(c);
+        flops += 4 * (uint64_t)c.d * c.n_kv * cost;
     }
     if (groups.empty())
         return UKV_OK;
@@ -943,8 +972,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 r.out_off = b->out_off[i];
                 r.ctx_len = b->ctx_len[i];
                 r.q_len = q_len[i];
-                r.cls = b->service_id[i];
                 r.kvh = g.kvh;
+                r.v16_off = v16_base[i] + (uint64_t)g.kvh * b->ctx_len[i] * 2 * c.d; // made absolute below
                 r.r0 = t * rows;
                 r.g = c.g;
                 r.n_q = c.n_q;
@@ -962,11 +991,27 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 list[di][e * n_queues + k] = queue[k][e];
     }
     const size_t n_recs = list[0].size() + list[1].size();
-    const size_t total = align_up(n_recs * sizeof(PrefillRec)); // the records carry what they need of their class
-    if (total > ws_bytes) {
+    const size_t rec_bytes = align_up(n_recs * sizeof(PrefillRec)); // the records carry what they need of their class
+    if (rec_bytes > ws_bytes) {
         set_error("workspace too small for this batch");
         return UKV_ENOSPC;
     }
+    // Form of the weights: one fp16 part needs the fp16 copy of V in the workspace, behind the records and the copy
+    // pass's own work list.
+    const size_t chunk_bytes = align_up((size_t)(n_chunks * sizeof(V16Rec)));
+    const size_t one_part_total = rec_bytes + chunk_bytes + (size_t)v16_bytes;
+    uint32_t parts = 2;
+    if (p->tun.prefill_weights == 1) {
+        if (one_part_total > ws_bytes) {
+            set_error("workspace too small for one-part weights (see ukv_prefill_workspace_bytes_one_part)");
+            return UKV_ENOSPC;
+        }
+        parts = 1;
+    } else if (p->tun.prefill_weights == 0 && one_part_total <= ws_bytes && flops >= kOnePartFlopPerByte * v16_bytes) {
+        parts = 1;
+    }
+    p->tun.prefill_form_used = parts;
+    const size_t total = parts == 1 ? rec_bytes + chunk_bytes : rec_bytes;
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -976,6 +1021,31 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         std::memcpy(recs, list[0].data(), list[0].size() * sizeof(PrefillRec));
     if (!list[1].empty())
         std::memcpy(recs + list[0].size(), list[1].data(), list[1].size() * sizeof(PrefillRec));
+    if (parts == 1) {
+        const uint64_t v16_start = rec_bytes + chunk_bytes;
+        for (size_t e = 0; e < n_recs; ++e)
+            recs[e].v16_off += v16_start;
+        V16Rec *ch = (V16Rec *)(h + rec_bytes);
+        size_t k = 0;
+        for (uint32_t i = 0; i < n; ++i) {
+            if (q_len[i] == 0)
+                continue;
+            const ClassRec &c = p->classes.c[b->service_id[i]];
+            const uint32_t step = v16_chunk_tokens(c);
+            for (uint64_t t0 = 0; t0 < b->ctx_len[i]; t0 += step) {
+                V16Rec r{};
+                r.table_off = b->table_off[i];
+                r.v16_off = v16_start + v16_base[i];
+                r.t0 = (uint32_t)t0;
+                r.t1 = (uint32_t)std::min<uint64_t>(t0 + step, b->ctx_len[i]);
+                r.ctx_len = b->ctx_len[i];
+                r.token_bytes = c.token_bytes;
+                r.n_kv = c.n_kv;
+                r.d = c.d;
+                ch[k++] = r;
+            }
+        }
+    }
     HIP_TRY(launch_stage_copy(workspace, st->mapped, total, nullptr, nullptr, nullptr, 0, s), "launch plan upload");
     if ((rc = stage_release_after(st, s)) != UKV_OK)
         return rc;
@@ -986,8 +1056,13 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     a.page_table = b->page_table;
     a.q = (const uint16_t *)b->q;
     a.out = (float *)b->out;
+    a.v16 = w;
     if ((rc = validate_tables(p, n, b->service_id, b->ctx_len, b->table_off, b->page_table, 0, s, &a.bad)) != UKV_OK)
         return rc;
+    if (parts == 1)
+        HIP_TRY(launch_v16(p->base, p->log2_page, b->page_table, (const V16Rec *)(w + rec_bytes), (uint32_t)n_chunks, w,
+                           a.bad, s),
+                "launch fp16 copy of V");
     size_t first = 0;
     for (int di = 0; di < 2; ++di) {
         if (list[di].empty())
@@ -996,7 +1071,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         ProfPair pp{p, 3};
         if ((rc = pp.get()) != UKV_OK)
             return rc;
-        HIP_TRY(launch_prefill(a, (uint32_t)list[di].size(), kDims[di], s, pp.ev.a, pp.ev.b), "launch prefill kernel");
+        HIP_TRY(launch_prefill(a, (uint32_t)list[di].size(), kDims[di], parts, s, pp.ev.a, pp.ev.b),
+                "launch prefill kernel");
         pp.done();
         first += list[di].size();
     }

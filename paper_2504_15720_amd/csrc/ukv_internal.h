@@ -165,14 +165,14 @@ struct PrefillRec {
     uint64_t q_off;   // element offset of the request's first query row
     uint64_t out_off; // element offset of the request's first output row
     uint32_t ctx_len; // tokens in the cache, the chunk's own included
-    uint32_t q_len;   // query rows of the request; row r is the token at position ctx_len - q_len + r
-    uint32_t cls;
-    uint32_t kvh;
+    uint32_t q_len;   // query rows of the request; row r is the token at position ctx_len - q_len + r;
+                      // q_len == 0: filler workgroup (keeps the XCD interleave regular)
+    uint64_t v16_off; // one-part weights only: byte offset, in the workspace, of this (request, kv head)'s V rows as fp16
     uint32_t r0;      // first query row of the tile
     // what the kernel needs of the service's class, copied here so that a workgroup starts with one load
     uint32_t g, n_q, token_bytes;
     float scale_log2e;
-    uint32_t pad_[1]; // q_len == 0: filler workgroup (keeps the XCD interleave regular)
+    uint32_t kvh;
 };
 static_assert(sizeof(PrefillRec) == 64, "PrefillRec layout");
 
@@ -184,7 +184,21 @@ struct PrefillArgs {
     float *out;
     const PrefillRec *recs;
     const uint32_t *bad; // null, or the flag of the page-table check: set = leave at once
+    const unsigned char *v16; // one-part weights only: the workspace that holds the V rows as fp16
 };
+
+// Work item of the pass that copies V rows out of the pool as fp16 (one-part weights): tokens [t0, t1) of one
+// request, all kv heads; head h's row of token t goes to v16_off + (h ctx_len + t) * 2 head_dim.
+struct V16Rec {
+    uint64_t table_off;
+    uint64_t v16_off;
+    uint32_t t0, t1;
+    uint32_t ctx_len;
+    uint32_t token_bytes;
+    uint32_t n_kv, d;
+    uint32_t pad_[2];
+};
+static_assert(sizeof(V16Rec) == 48, "V16Rec layout");
 static constexpr uint32_t kPrefillBlocks = 2; // 16-column blocks per wave
 static constexpr uint32_t kPrefillWaves = 4;  // waves per workgroup (8 was measured: slower, one workgroup per CU)
 static constexpr uint32_t kPrefillCols = 16 * kPrefillBlocks * kPrefillWaves; // (query row, query head) pairs per workgroup
@@ -219,7 +233,10 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
                          uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
                          const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
                          const uint32_t *bad, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
-hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, hipStream_t s, hipEvent_t ev0,
+hipError_t launch_v16(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table, const V16Rec *recs,
+                      uint32_t n_recs, unsigned char *v16, const uint32_t *bad, hipStream_t s);
+// parts: 2 = weights as two bf16 parts, 1 = as one fp16 part (a.v16 and the records' v16_off are then set)
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, uint32_t parts, hipStream_t s, hipEvent_t ev0,
                           hipEvent_t ev1);
 hipError_t launch_copy_tokens(bool to_pool, unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table,
                               const GatherRec *recs, uint32_t n, const ClassRec *classes, void *k_io, void *v_io,
@@ -254,6 +271,8 @@ struct Tunables {
     int64_t prefill_xcd = 1;
     int64_t merge_acq_rel = 0;
     int64_t validate = 0; // check the page tables a call uses before its kernels run
+    int64_t prefill_weights = 0; // 0 = chosen per call, 1 = one fp16 part, 2 = two bf16 parts
+    int64_t prefill_form_used = 0; // what the last prefill call took
     int64_t replan_every = 64; // a kept plan is remade after its requests have grown by this many tokens
     bool slots_auto = true;
 };

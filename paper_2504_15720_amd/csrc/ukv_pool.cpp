@@ -249,7 +249,7 @@ int ukv_pages_free(ukv_pool_t *p, uint32_t n, const int32_t *ids) {
 int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
     if (!p)
         return fail(UKV_EINVAL, "null pool");
-    if (key != UKV_PARAM_PROFILE && key != UKV_PARAM_VALIDATE)
+    if (key != UKV_PARAM_PROFILE && key != UKV_PARAM_VALIDATE && key != UKV_PARAM_PREFILL_WEIGHTS)
         ++p->tun_epoch; // kept plans are remade
     switch (key) {
     case UKV_PARAM_MERGE_ACQ_REL:
@@ -257,6 +257,11 @@ int ukv_set_param(ukv_pool_t *p, int key, int64_t value) {
         return UKV_OK;
     case UKV_PARAM_VALIDATE:
         p->tun.validate = value ? 1 : 0;
+        return UKV_OK;
+    case UKV_PARAM_PREFILL_WEIGHTS:
+        if (value < 0 || value > 2)
+            return fail(UKV_EINVAL, "prefill_weights must be 0, 1 or 2");
+        p->tun.prefill_weights = value;
         return UKV_OK;
     case UKV_PARAM_REPLAN_EVERY:
         if (value < 0 || value > (1 << 20))
@@ -335,6 +340,8 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_REPLAN_EVERY: *value = p->tun.replan_every; return UKV_OK;
     case UKV_PARAM_MERGE_ACQ_REL: *value = p->tun.merge_acq_rel; return UKV_OK;
     case UKV_PARAM_VALIDATE: *value = p->tun.validate; return UKV_OK;
+    case UKV_PARAM_PREFILL_WEIGHTS: *value = p->tun.prefill_weights; return UKV_OK;
+    case UKV_PARAM_PREFILL_FORM_USED: *value = p->tun.prefill_form_used; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

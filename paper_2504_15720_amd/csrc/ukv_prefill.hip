@@ -17,8 +17,16 @@ namespace ukv {
 //   O^T[d][column]    += V^T[d][token] . P^T[token][column]
 // The S^T results leave lane (j, q) with the scores of column j for the tokens 4q..4q+3 and
 // 16+4q..16+4q+3 of the tile, which is the k-block the second product wants from that lane; V^T
-// operands come straight from the row-major V tile by transposing LDS reads.  P is split into bf16
-// high and low parts (two products), so the weights keep 16 mantissa bits.  Column j of a block is
+// operands come straight from the row-major V tile by transposing LDS reads.  The weights P enter the
+// second product in one of two forms (template parameter PARTS):
+//   2: split into bf16 high and low parts (two products against the pool's bf16 V rows): 16 mantissa bits;
+//   1: rounded to fp16 (one product, v_mfma_f32_16x16x32_f16), 11 mantissa bits: every weight is off by at most
+//      2^-12 of itself, the same rounded weights are summed for the denominator, so a result is off by at most
+//      2^-12 times the largest distance of a V element from that result.  The matrix instruction wants both
+//      operands in one format, so the V rows are read as fp16 from a copy that v16_kernel has made in the
+//      workspace (bf16's 8 significant bits fit fp16; values beyond +-65504 saturate, below 2^-24 vanish).
+//      The exponentials are taken 2^8 higher, which keeps small weights out of fp16's subnormal range.
+// Column j of a block is
 // row r0 + blk*(16/G) + j/G, head j%G; the score of (token t, column) counts if t <= position(column)
 // -- only the last tiles of a block are partly masked, tiles wholly behind a block's rows are
 // skipped.  The tiles are pipelined: while the vector units do the softmax of one tile, the matrix
@@ -26,6 +34,7 @@ namespace ukv {
 // number, so that a column none of whose tokens has been seen yet stays at weight 0 without inf - inf.
 static constexpr float kMinusBig = -1.0e30f;
 static constexpr float kLazy = 6.0f; // log2 of the largest weight tolerated before the reference moves
+static constexpr float kShiftOnePart = 8.0f; // one-part weights are 2^8 x the two-part ones: at most 2^14, fp16 holds 2^15
 // Staged tiles in LDS: the 32 K rows of a tile in one array, its 32 V rows in another, 2 head_dim bytes
 // per row, written by global-to-LDS loads (no registers in between; lane L of a wave instruction fills
 // bytes [16 L, 16 L + 16) of a 1 KiB stretch, from any global address).  Rows keep their 16-byte pieces
@@ -33,10 +42,13 @@ static constexpr float kLazy = 6.0f; // log2 of the largest weight tolerated bef
 // adjacent lanes fall on different banks.  Two arrays each for K and V: one is read while the other
 // is written.
 static constexpr int kPfTabWindow = 1024;
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef const __attribute__((address_space(1))) void *global_ptr_t;
 
-template <int NB, int NW, int D>
+template <int NB, int NW, int D, int PARTS>
 __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     // a checked call (UKV_PARAM_VALIDATE) whose page tables hold an id outside the pool does nothing
     if (a.bad != nullptr && uni(*reinterpret_cast<const volatile uint32_t *>(a.bad)) != 0)
@@ -50,6 +62,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     constexpr uint32_t KI = 32 / RPI / NW;  // staging instructions per wave, tile and part (K, V)
     static_assert(KI >= 1, "too many waves for this head_dim");
     constexpr uint32_t kPartBytes = 32 * KB; // the K rows (or the V rows) of a 32-token tile
+    constexpr float kShift = PARTS == 2 ? 0.f : kShiftOnePart;
     __shared__ PrefillRec s_rec;
     // Two staged tiles, one array each: with distinct arrays the compiler can tell that reading one tile
     // does not depend on the global-to-LDS loads that fill the other, and lets those loads stay in flight.
@@ -65,6 +78,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         return; // filler
     const uint64_t table_off = uni(s_rec.table_off), q_off = uni(s_rec.q_off), out_off = uni(s_rec.out_off);
     const uint32_t ctx_len = uni(s_rec.ctx_len), kvh = uni(s_rec.kvh), r0 = uni(s_rec.r0);
+    const unsigned char *v16 = PARTS == 1 ? a.v16 + uni(s_rec.v16_off) : nullptr; // this (request, kv head)'s V rows as fp16
     const uint32_t G = uni(s_rec.g), n_q = uni(s_rec.n_q);
     const uint64_t T = uni(s_rec.token_bytes);
     const float scale_log2e = uni(s_rec.scale_log2e);
@@ -96,7 +110,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         } w;
         w.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
         w.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 16 * KB));
-        return __builtin_bit_cast(bf16x8_t, w);
+        return __builtin_bit_cast(uint4, w);
     };
     const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
     const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
@@ -188,11 +202,16 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                                                      (lds_ptr_t)(kt + (KI * wave + x) * 1024), 16, 0, 0);
                 }
             };
-            auto issue_v = [&](const RowPtrs &r, unsigned char *vt) {
+            // V rows of the tile at tb: from the pool (r: the row addresses worked out for the tile's K), or, with
+            // one-part weights, from the fp16 copy, whose rows of one kv head follow each other.
+            auto issue_v = [&](const RowPtrs &r, uint32_t tb, unsigned char *vt) {
 #pragma unroll
-                for (uint32_t x = 0; x < KI; ++x)
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x] + KB + (ld_pos ^ vswz(ld_tok + RPI * x)) * 16),
+                for (uint32_t x = 0; x < KI; ++x) {
+                    const uint32_t tok = ld_tok + RPI * x;
+                    const unsigned char *src = PARTS == 1 ? v16 + (uint64_t)min(tb + tok, last) * KB : r.p[x] + KB;
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(src + (ld_pos ^ vswz(tok)) * 16),
                                                      (lds_ptr_t)(vt + (KI * wave + x) * 1024), 16, 0, 0);
+                }
             };
             // Raw scores S^T = K Q^T of one staged K tile against all NB blocks of the wave.
             auto scores = [&](const unsigned char *kt, f32x4_t (&s0)[NB], f32x4_t (&s1)[NB]) {
@@ -219,8 +238,8 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             // some column's position (or past the window); otherwise every score counts and the compares
             // are skipped.  A block that lies wholly before the tile just sees every score masked.
             // Returns whether some accumulator has to be rescaled before the tile is added: by 2^(-grow[b]).
-            auto softmax = [&](uint32_t tb, const f32x4_t (&s0)[NB], const f32x4_t (&s1)[NB], bf16x8_t (&Ph)[NB],
-                               bf16x8_t (&Pl)[NB], float (&grow)[NB], auto masked) -> bool {
+            auto softmax = [&](uint32_t tb, const f32x4_t (&s0)[NB], const f32x4_t (&s1)[NB], uint4 (&Ph)[NB],
+                               uint4 (&Pl)[NB], float (&grow)[NB], auto masked) -> bool {
                 constexpr bool MASKED = decltype(masked)::value;
                 // Raw scores; the scale (times log2 e, positive) is applied to the maximum and folded into
                 // the multiply-add under the exponential.
@@ -258,38 +277,52 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     grow[b] = mn - m[b]; // how far the reference point moved: 0 almost always
                     rescale |= grow[b] != 0.f;
                     m[b] = mn;
-                    // P as two bf16 parts by truncation (see process_item_gqa)
-                    uint32_t ph[4], pl[4];
+                    uint32_t ph[4], pl[4] = {0, 0, 0, 0};
+                    const float neg_ref = kShift - mn;
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
-                        const float p0 = fast_exp2(fmaf(sr[b][e], scale_log2e, -mn));
-                        const float p1 = fast_exp2(fmaf(sr[b][e + 1], scale_log2e, -mn));
-                        const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
-                        const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
-                        const float x1 = p1 - __uint_as_float(u1 & 0xffff0000u);
-                        ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
-                        pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
+                        const float p0 = fast_exp2(fmaf(sr[b][e], scale_log2e, neg_ref));
+                        const float p1 = fast_exp2(fmaf(sr[b][e + 1], scale_log2e, neg_ref));
+                        if constexpr (PARTS == 2) {
+                            // P as two bf16 parts by truncation (see process_item_gqa)
+                            const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+                            const float x0 = p0 - __uint_as_float(u0 & 0xffff0000u);
+                            const float x1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+                            ph[e / 2] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+                            pl[e / 2] = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
+                        } else {
+                            ph[e / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{p0, p1}, f16x2_t));
+                        }
                     }
-                    Ph[b] = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
-                    Pl[b] = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
+                    Ph[b] = make_uint4(ph[0], ph[1], ph[2], ph[3]);
+                    Pl[b] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
                 }
                 return __builtin_amdgcn_ballot_w64(rescale) != 0;
             };
             // O^T += V^T P^T for one staged V tile, one group of 16 output rows at a time, multiplied into every
             // block.  The weights' running sums ride along as one more product with an all-ones left operand: every row
             // of its result is the column sum of the (two-part) weights, over all four k-blocks at once.
-            auto pv = [&](const unsigned char *vt, const bf16x8_t (&Ph)[NB], const bf16x8_t (&Pl)[NB]) {
-                const bf16x8_t ones = as_bf16x8(make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u));
+            auto pv = [&](const unsigned char *vt, const uint4 (&Ph)[NB], const uint4 (&Pl)[NB]) {
+                constexpr uint32_t kOne = PARTS == 2 ? 0x3f803f80u : 0x3c003c00u; // 1.0 twice, bf16 or fp16
+                const uint4 ones = make_uint4(kOne, kOne, kOne, kOne);
+                auto mac = [](const uint4 &x, const uint4 &y, const f32x4_t &c) {
+                    if constexpr (PARTS == 2)
+                        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(x), as_bf16x8(y), c, 0, 0, 0);
+                    else
+                        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, x),
+                                                                      __builtin_bit_cast(f16x8_t, y), c, 0, 0, 0);
+                };
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    lacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, Ph[b], lacc[b], 0, 0, 0);
-                    lacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, Pl[b], lacc[b], 0, 0, 0);
+                    lacc[b] = mac(ones, Ph[b], lacc[b]);
+                    if constexpr (PARTS == 2)
+                        lacc[b] = mac(ones, Pl[b], lacc[b]);
                 }
                 // Left operand of the product for output rows d = 16 mm + i (lane i of 16): V[token][d] for the
                 // lane's 8 tokens, fetched by two transposing LDS reads (tokens 4q..4q+3 and 16+4q..16+4q+3).
                 // The reads run two groups ahead of the products that use them (the order is pinned below):
                 // issued only when needed, every group of products would wait out a whole LDS round trip.
-                bf16x8_t Vt[MM];
+                uint4 Vt[MM];
 #pragma unroll
                 for (int mm = 0; mm < MM; ++mm)
                     Vt[mm] = vt_operand(vt + voff[mm]);
@@ -297,18 +330,19 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 for (int mm = 0; mm < MM; ++mm) {
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Ph[b], oacc[b][mm], 0, 0, 0);
-                        oacc[b][mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vt[mm], Pl[b], oacc[b][mm], 0, 0, 0);
+                        oacc[b][mm] = mac(Vt[mm], Ph[b], oacc[b][mm]);
+                        if constexpr (PARTS == 2)
+                            oacc[b][mm] = mac(Vt[mm], Pl[b], oacc[b][mm]);
                     }
                 }
                 constexpr int kAhead = 2; // groups of 16 output rows whose operands are in flight
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0); // LDS reads of the first groups
-                __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);     // the sums of the weights
+                __builtin_amdgcn_sched_group_barrier(0x008, PARTS * NB, 0); // the sums of the weights
 #pragma unroll
                 for (int mm = 0; mm < MM; ++mm) {
                     if (mm + kAhead < MM)
                         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, PARTS * NB, 0);
                 }
             };
             RowPtrs rows; // row addresses of the tile whose K was requested last
@@ -323,13 +357,13 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                             unsigned char *v_fill, const f32x4_t (&c0s)[NB], const f32x4_t (&c1s)[NB],
                             f32x4_t (&n0s)[NB], f32x4_t (&n1s)[NB]) {
                 if (tb + 32 < w1)
-                    issue_v(rows, v_fill); // rows: those of the tile at tb + 32, from the previous step
+                    issue_v(rows, tb + 32, v_fill); // rows: those of the tile at tb + 32, from the previous step
                 if (tb + 64 < w1) {
                     rows = rows_of(tb + 64);
                     issue_k(rows, k_fill);
                 }
                 if (tb < r1) {
-                    bf16x8_t Ph[NB], Pl[NB];
+                    uint4 Ph[NB], Pl[NB];
                     float grow[NB];
                     bool rescale;
                     // The next tile's scores are taken whether or not this wave (or the window) has a next
@@ -368,7 +402,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             f32x4_t sa0[NB], sa1[NB], sb0[NB], sb1[NB];
             rows = rows_of(w0);
             issue_k(rows, s_k0);
-            issue_v(rows, s_v0);
+            issue_v(rows, w0, s_v0);
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads(); // the first tile is staged
             if (w0 + 32 < w1) {
@@ -404,18 +438,90 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     }
 }
 
+// The pool's V rows of one chunk of tokens (all kv heads of one request), as fp16, into the workspace: the
+// right-hand side of the one-part product.  Pure copy-and-convert, bound by memory; 16 bytes per lane and pass.
+struct V16Args {
+    const unsigned char *pool_base;
+    uint32_t log2_page;
+    const int32_t *page_table;
+    const V16Rec *recs;
+    unsigned char *v16;
+    const uint32_t *bad;
+};
+
+__global__ void __launch_bounds__(256) v16_kernel(V16Args a) {
+    if (a.bad != nullptr && uni(*reinterpret_cast<const volatile uint32_t *>(a.bad)) != 0)
+        return;
+    __shared__ V16Rec s_rec;
+    if (threadIdx.x == 0)
+        s_rec = a.recs[blockIdx.x];
+    __syncthreads();
+    const uint64_t table_off = uni(s_rec.table_off), T = uni(s_rec.token_bytes);
+    const uint32_t t0 = uni(s_rec.t0), t1 = uni(s_rec.t1), ctx_len = uni(s_rec.ctx_len);
+    const uint32_t d = uni(s_rec.d), n_kv = uni(s_rec.n_kv);
+    unsigned char *dst = a.v16 + uni(s_rec.v16_off);
+    const uint32_t lg = a.log2_page;
+    const uint64_t page_mask = (1ull << lg) - 1;
+    const uint32_t lp = d == 128 ? 4 : 3; // a head's V row has 2^lp 16-byte pieces
+    const uint32_t pieces = 1u << lp;
+    const uint32_t upt = n_kv * pieces;   // pieces per token
+    // the 256 lanes cover whole tokens: several tokens per pass where a token has fewer than 256 pieces
+    const uint32_t tid = threadIdx.x;
+    uint32_t tstep = 1, tl = 0, r0 = tid, rstep = 256;
+    if (upt < 256) {
+        tstep = 256 / upt;
+        tl = tid / upt;
+        r0 = tid % upt;
+        rstep = upt;
+        if (tl >= tstep)
+            return;
+    }
+    for (uint32_t tok = t0 + tl; tok < t1; tok += tstep) {
+        for (uint32_t r = r0; r < upt; r += rstep) {
+            const uint32_t h = r >> lp, pc = r & (pieces - 1);
+            const uint64_t off = (uint64_t)tok * T + (uint64_t)h * (4 * d) + 2 * d + pc * 16;
+            const int32_t pg = as_global(a.page_table)[table_off + (off >> lg)];
+            // read once by this pass (the attention kernel takes V from the copy): streaming load; the copy itself
+            // is stored plainly, it is read again soon
+            const uint4 w = ld_kv(reinterpret_cast<const uint4 *>(a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & page_mask))));
+            float f[8];
+            unpack8(w, f);
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const float x0 = __builtin_amdgcn_fmed3f(f[e], -65504.f, 65504.f);
+                const float x1 = __builtin_amdgcn_fmed3f(f[e + 1], -65504.f, 65504.f);
+                o[e / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{x0, x1}, f16x2_t));
+            }
+            *as_global(reinterpret_cast<u32x4 *>(dst + ((uint64_t)h * ctx_len + tok) * (2 * d) + pc * 16)) = (u32x4){o[0], o[1], o[2], o[3]};
+        }
+    }
+}
+
+hipError_t launch_v16(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table, const V16Rec *recs,
+                      uint32_t n_recs, unsigned char *v16, const uint32_t *bad, hipStream_t s) {
+    if (n_recs == 0)
+        return hipSuccess;
+    V16Args a{pool_base, log2_page, page_table, recs, v16, bad};
+    hipLaunchKernelGGL(v16_kernel, dim3(n_recs), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps.
-hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, hipStream_t s, hipEvent_t ev0,
-                          hipEvent_t ev1) {
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, uint32_t parts, hipStream_t s,
+                          hipEvent_t ev0, hipEvent_t ev1) {
     if (n_recs == 0)
         return hipSuccess;
     static_assert(kPrefillCols == kPrefillWaves * kPrefillBlocks * 16, "NW waves x NB blocks of 16 columns");
-    if (head_dim == 128)
-        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 128>), dim3(n_recs),
-                              dim3(64 * kPrefillWaves), 0, s, ev0, ev1, 0, a);
+    const dim3 grid(n_recs), block(64 * kPrefillWaves);
+    if (head_dim == 128 && parts == 1)
+        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 128, 1>), grid, block, 0, s, ev0, ev1, 0, a);
+    else if (head_dim == 128)
+        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 128, 2>), grid, block, 0, s, ev0, ev1, 0, a);
+    else if (parts == 1)
+        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 64, 1>), grid, block, 0, s, ev0, ev1, 0, a);
     else
-        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 64>), dim3(n_recs),
-                              dim3(64 * kPrefillWaves), 0, s, ev0, ev1, 0, a);
+        hipExtLaunchKernelGGL((prefill_kernel<kPrefillBlocks, kPrefillWaves, 64, 2>), grid, block, 0, s, ev0, ev1, 0, a);
     return hipGetLastError();
 }
 

@@ -101,7 +101,9 @@ class DeviceBatch:
         q_len = np.ascontiguousarray(q_len, np.uint32)
         q_t = torch.from_numpy(q_bits.view(np.int16).copy()).to(self.dev)
         out_t = torch.full((n_elems,), float("nan"), dtype=torch.float32, device=self.dev)
-        ws = U.ukv_prefill_workspace_bytes(self.pool, b.n_requests, int(q_len.sum()))
+        # room for the fp16 copy of V as well, so that the call may take the one-part weights
+        ws = U.ukv_prefill_workspace_bytes_one_part(self.pool, b.n_requests, int(q_len.sum()),
+                                                    int(b.ctx_len[q_len > 0].astype(np.int64).sum()))
         if getattr(self, "pf_ws_t", None) is None or self.pf_ws_t.numel() < ws:
             self.pf_ws_t = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         desc = U.BatchDesc(b.service_id, b.ctx_len, b.table_off, self.table_t.data_ptr(), q_t.data_ptr(), q_off,

@@ -65,7 +65,8 @@ class ServingLoop:
         scheds = self.scheds = ([U.ukv_sched_create(pool, wl.profiles, wl.max_batch)] if policy == "db"
                                 else [U.ukv_sched_create(pool, wl.profiles, wl.max_batch) for _ in range(ns)])
         ws_bytes = max(U.ukv_decode_workspace_bytes(pool, n),
-                       U.ukv_prefill_workspace_bytes(pool, wl.max_batch, wl.max_batch * self.max_prompt))
+                       U.ukv_prefill_workspace_bytes_one_part(pool, wl.max_batch, wl.max_batch * self.max_prompt,
+                                                              wl.max_batch * self.max_prompt))
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.dev)
         self.ctx = ctx = np.zeros(n, np.int64)
         owned = [[] for _ in range(n)]

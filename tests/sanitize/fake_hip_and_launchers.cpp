@@ -198,15 +198,43 @@ hipError_t launch_append(unsigned char *, uint32_t lg, int32_t *page_table, cons
     return hipSuccess;
 }
 
-hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t, hipStream_t, hipEvent_t, hipEvent_t) {
+// The copy pass of the one-part weights: writes (zeros) exactly the bytes the kernel would write, so that the
+// sanitizer sees a record that reaches past the workspace.
+hipError_t launch_v16(const unsigned char *, uint32_t lg, const int32_t *page_table, const V16Rec *recs, uint32_t n_recs,
+                      unsigned char *v16, const uint32_t *bad, hipStream_t) {
+    if (bad && *bad)
+        return hipSuccess;
+    for (uint32_t i = 0; i < n_recs; ++i) {
+        const V16Rec &r = recs[i];
+        if (r.t0 >= r.t1 || r.t1 > r.ctx_len || (r.d != 64 && r.d != 128) || r.n_kv == 0)
+            die("fp16 copy record");
+        const uint64_t last = ((uint64_t)r.t1 * r.token_bytes - 1) >> lg;
+        for (uint64_t e = ((uint64_t)r.t0 * r.token_bytes) >> lg; e <= last; ++e)
+            if (page_table[r.table_off + e] < 0 || (uint64_t)page_table[r.table_off + e] >= g_fake.n_pages)
+                die("fp16 copy through a page id out of range");
+        for (uint32_t h = 0; h < r.n_kv; ++h)
+            std::memset(v16 + r.v16_off + ((uint64_t)h * r.ctx_len + r.t0) * 2 * r.d, 0, (size_t)(r.t1 - r.t0) * 2 * r.d);
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_dim, uint32_t parts, hipStream_t,
+                          hipEvent_t, hipEvent_t) {
     if (a.bad && *a.bad)
         return hipSuccess;
+    if (parts != 1 && parts != 2)
+        die("prefill parts");
     for (uint32_t i = 0; i < n_recs; ++i) {
         const PrefillRec &r = a.recs[i];
         if (r.q_len == 0)
             continue; // filler
         if (r.q_len > r.ctx_len || r.r0 >= r.q_len)
             die("prefill record");
+        if (parts == 1) { // the rows this record reads from the fp16 copy: first and last byte
+            const volatile unsigned char *v = a.v16 + r.v16_off;
+            (void)v[0];
+            (void)v[(uint64_t)r.ctx_len * 2 * head_dim - 1];
+        }
         const uint64_t last = ((uint64_t)r.ctx_len * r.token_bytes - 1) >> a.log2_page;
         for (uint64_t e = 0; e <= last; ++e)
             if (a.page_table[r.table_off + e] < 0 || (uint64_t)a.page_table[r.table_off + e] >= g_fake.n_pages)

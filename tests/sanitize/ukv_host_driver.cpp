@@ -186,6 +186,23 @@ static void run_scenario(uint32_t round) {
     const size_t pws = ukv_prefill_workspace_bytes(sc.pool, n_req, rows);
     void *pw = std::aligned_alloc(256, (pws + 255) / 256 * 256 + 256);
     EXPECT(ukv_prefill_attention(sc.pool, &b, q_len.data(), pw, pws, nullptr) == UKV_OK);
+    // one-part weights: the fp16 copy of V lives in the workspace too
+    EXPECT(ukv_set_param(sc.pool, UKV_PARAM_PREFILL_WEIGHTS, 1) == UKV_OK);
+    {   // the two-part workspace is a bound, so a tiny batch's copy may fit it: either answer, nothing out of bounds
+        const int r1 = ukv_prefill_attention(sc.pool, &b, q_len.data(), pw, pws, nullptr);
+        EXPECT(r1 == UKV_OK || r1 == UKV_ENOSPC);
+    }
+    std::free(pw);
+    uint64_t ctx_tokens = 0;
+    for (uint32_t i = 0; i < n_req; ++i)
+        ctx_tokens += q_len[i] ? sc.ctx[i] : 0;
+    const size_t pws1 = ukv_prefill_workspace_bytes_one_part(sc.pool, n_req, rows, ctx_tokens);
+    EXPECT(pws1 >= pws);
+    pw = std::aligned_alloc(256, (pws1 + 255) / 256 * 256);
+    EXPECT(ukv_prefill_attention(sc.pool, &b, q_len.data(), pw, pws1, nullptr) == UKV_OK);
+    EXPECT(ukv_set_param(sc.pool, UKV_PARAM_PREFILL_WEIGHTS, 0) == UKV_OK);
+    EXPECT(ukv_prefill_attention(sc.pool, &b, q_len.data(), pw, pws1, nullptr) == UKV_OK);
+    EXPECT(ukv_set_param(sc.pool, UKV_PARAM_PREFILL_WEIGHTS, 3) == UKV_EINVAL);
     std::free(pw);
 
     // a plan kept across steps

@@ -113,19 +113,24 @@ def test_million_token_context_in_one_mebibyte_pages():
         n_el = int((q_len * row_el).sum())
         pq_t = torch.from_numpy(normal_bf16(n_el, rng).view(np.int16)).to(dev)
         pout_t = torch.full((n_el,), float("nan"), dtype=torch.float32, device=dev)
-        pws = U.ukv_prefill_workspace_bytes(pool, 2, int(q_len.sum()))
+        # both forms of the softmax weights; the one-part form keeps an fp16 copy of every V row in the workspace
+        pws = U.ukv_prefill_workspace_bytes_one_part(pool, 2, int(q_len.sum()), int(ctx.sum()))
         pws_t = torch.empty(pws, dtype=torch.uint8, device=dev)
         pdesc = U.BatchDesc(sid, ctx, table_off, table_t.data_ptr(), pq_t.data_ptr(), pq_off, pout_t.data_ptr(), pq_off)
-        U.ukv_prefill_attention(pool, pdesc, q_len, pws_t.data_ptr(), pws, stream_h)
-        got = pout_t.cpu().numpy().astype(np.float64)
-        for i in range(2):
-            sv = services[sid[i]]
-            g = got[int(pq_off[i]):int(pq_off[i]) + 64 * int(row_el[i])].reshape(64, sv.n_q_heads, sv.head_dim)
-            worst = 0.0
-            for r in (0, 1, 31, 62, 63):
-                worst = max(worst, float(np.max(np.abs(g[r] - expected(i, int(ctx[i]) - 64 + r + 1)))))
-            print(f"  prefill, request {i}: max|err| = {worst:.3e}", flush=True)
-            assert np.all(np.isfinite(g)) and worst <= ATOL
+        for form in (2, 1):
+            U.ukv_set_param(pool, U.UKV_PARAM_PREFILL_WEIGHTS, form)
+            pout_t.fill_(float("nan"))
+            U.ukv_prefill_attention(pool, pdesc, q_len, pws_t.data_ptr(), pws, stream_h)
+            assert U.ukv_get_param(pool, U.UKV_PARAM_PREFILL_FORM_USED) == form
+            got = pout_t.cpu().numpy().astype(np.float64)
+            for i in range(2):
+                sv = services[sid[i]]
+                g = got[int(pq_off[i]):int(pq_off[i]) + 64 * int(row_el[i])].reshape(64, sv.n_q_heads, sv.head_dim)
+                worst = 0.0
+                for r in (0, 1, 31, 62, 63):
+                    worst = max(worst, float(np.max(np.abs(g[r] - expected(i, int(ctx[i]) - 64 + r + 1)))))
+                print(f"  prefill, weights in {form} part(s), request {i}: max|err| = {worst:.3e}", flush=True)
+                assert np.all(np.isfinite(g)) and worst <= ATOL
         torch.cuda.synchronize()
     finally:
         torch.cuda.synchronize()
