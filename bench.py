@@ -236,7 +236,7 @@ def main_grid(args):
                 U.ukv_set_param(pool, U.UKV_PARAM_PROFILE, 1)
                 q_t = noise.repeat(-(-n * ctx * row // noise.numel()))[:n * ctx * row].contiguous()
                 out_t = torch.empty(n * ctx * row, dtype=torch.float32, device=dev)
-                ws = U.ukv_prefill_workspace_bytes(pool, n, n * ctx)
+                ws = U.ukv_prefill_workspace_bytes_one_part(pool, n, n * ctx, n * ctx)   # room for either form of the weights
                 ws_t = torch.empty(ws, dtype=torch.uint8, device=dev)
                 off = (np.arange(n) * ctx * row).astype(np.uint64)
                 desc = U.BatchDesc([0] * n, [ctx] * n, (np.arange(n) * n_pg).astype(np.uint64), table_t.data_ptr(),
@@ -246,19 +246,23 @@ def main_grid(args):
                     U.ukv_prefill_attention(pool, desc, q_len, ws_t.data_ptr(), ws, stream)
                 torch.cuda.synchronize()
                 U.ukv_profile_read(pool)
-                for _ in range(5):
+                n_calls = max(5, args.steps)
+                t0 = time.perf_counter()
+                for _ in range(n_calls):
                     U.ukv_prefill_attention(pool, desc, q_len, ws_t.data_ptr(), ws, stream)
                 torch.cuda.synchronize()
+                call_us = (time.perf_counter() - t0) / n_calls * 1e6    # whole call: upload, fp16 copy of V if any, kernel
                 pr = U.ukv_profile_read(pool)
                 us = 1e3 * pr.prefill_ms / pr.n_prefill
                 flops = n * 4.0 * row * ctx * (ctx + 1) / 2            # causal, counted once
                 cells.append({"service": f"{sv.n_q_heads}/{sv.n_kv_heads} d={sv.head_dim}", "prompts": n, "tokens": ctx,
-                              "kernel_us": round(us, 1), "tflops": round(flops / us / 1e6, 1)})
+                              "weights_parts": U.ukv_get_param(pool, U.UKV_PARAM_PREFILL_FORM_USED),
+                              "kernel_us": round(us, 1), "call_us": round(call_us, 1), "tflops": round(flops / us / 1e6, 1)})
                 torch.cuda.synchronize()
                 U.ukv_pool_destroy(pool)
                 del raw, pool_t, q_t, out_t
     print(json.dumps({"metric": "prefill attention on uniform batches of whole prompts: prefill kernel time, 1 GPU",
-                      "unit": "us", "steps": 5, "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
+                      "unit": "us", "steps": max(5, args.steps), "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
 
 
 def main_serve(args):
