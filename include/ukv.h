@@ -241,9 +241,10 @@ int ukv_decode_attention_static(ukv_pool_t *pool, const ukv_device_batch_t *batc
  *
  * The softmax weights reach the matrix cores in one of two forms (UKV_PARAM_PREFILL_WEIGHTS):
  *   two bf16 parts (16 significant bits; results within 3e-5 of exact arithmetic on unit-normal K, V and q), or
- *   one fp16 part (11 bits: every weight is off by at most 2^-12 of itself, so a result is off by at most 2^-11 times
- *   the largest distance of a V element of its row from it -- measured: within 5e-4 on unit-normal values -- and the
- *   kernel is 1.3 times faster).  The one-part form multiplies fp16 by
+ *   one fp16 part (11 bits: every weight is off by at most 2^-11 of itself and the same rounded weights are summed
+ *   for the denominator, so a result moves by at most 2^-10 times the largest distance of a V element of its row from
+ *   it, and by that much only if every rounding error lined up with its V element; measured: within 5e-4 on
+ *   unit-normal values -- and the kernel is 1.3 times faster).  The one-part form multiplies fp16 by
  *   fp16, so a first pass copies the V rows the call needs, as fp16, into the workspace (V elements beyond
  *   +-65504 saturate, elements below 2^-24 in magnitude become 0), which then has to hold
  *   ukv_prefill_workspace_bytes_one_part(pool, n_requests, sum of q_len, sum of ctx_len over the requests

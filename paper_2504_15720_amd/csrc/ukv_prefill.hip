@@ -20,9 +20,10 @@ namespace ukv {
 // operands come straight from the row-major V tile by transposing LDS reads.  The weights P enter the
 // second product in one of two forms (template parameter PARTS):
 //   2: split into bf16 high and low parts (two products against the pool's bf16 V rows): 16 mantissa bits;
-//   1: rounded to fp16 (one product, v_mfma_f32_16x16x32_f16), 11 mantissa bits: every weight is off by at most
-//      2^-12 of itself, the same rounded weights are summed for the denominator, so a result is off by at most
-//      2^-12 times the largest distance of a V element from that result.  The matrix instruction wants both
+//   1: rounded to fp16 (one product, v_mfma_f32_16x16x32_f16), 11 significant bits: every weight is off by at most
+//      2^-11 of itself, the same rounded weights are summed for the denominator, so a result moves by at most
+//      2^-10 times the largest distance of a V element from that result (and by far less unless the rounding
+//      errors line up with the V elements).  The matrix instruction wants both
 //      operands in one format, so the V rows are read as fp16 from a copy that v16_kernel has made in the
 //      workspace (bf16's 8 significant bits fit fp16; values beyond +-65504 saturate, below 2^-24 vanish).
 //      The exponentials are taken 2^8 higher, which keeps small weights out of fp16's subnormal range.
