@@ -934,6 +934,10 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
             set_error("prefill attention supports head_dim 128 or 64 with group 1, 2, 4, 8 or 16");
             return UKV_EINVAL;
         }
+        if (c.token_bytes >= (1u << 24)) { // the kernel's row offsets are products of 24-bit factors
+            set_error("prefill attention supports token rows below 16 MiB");
+            return UKV_EINVAL;
+        }
         total_rows += q_len[i];
         // causal: row r looks at ctx_len - q_len + r + 1 tokens
         const uint64_t first = (uint64_t)b->ctx_len[i] - q_len[i] + 1, last = b->ctx_len[i];

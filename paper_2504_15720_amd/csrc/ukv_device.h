@@ -105,4 +105,18 @@ __device__ __forceinline__ float max_over_kblocks(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])); // odd and even rows of 16 exchanged
 }
 
+// The same for two values at once (x[0], x[1]: two blocks of columns): the first swap pairs the two values, so that the
+// lower half of the wave goes on with x[0] and the upper half with x[1]; the last swap hands every lane both results.
+// Three swaps and two maxima instead of four and four.
+__device__ __forceinline__ void max_over_kblocks_pair(float (&x)[2]) {
+    const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[0]), __float_as_uint(x[1]), false, false);
+    // a[0] = (x0 of lanes < 32 | x1 of lanes < 32), a[1] = (x0 of lanes >= 32 | x1 of lanes >= 32)
+    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])); // lanes < 32: x0 over (l, l^32); lanes >= 32: x1
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    const float w = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])); // over (l, l^16) as well
+    const auto d = __builtin_amdgcn_permlane32_swap(__float_as_uint(w), __float_as_uint(w), false, false);
+    x[0] = __uint_as_float(d[0]); // (w of lanes < 32 | w of lanes < 32)
+    x[1] = __uint_as_float(d[1]); // (w of lanes >= 32 | w of lanes >= 32)
+}
+
 } // namespace ukv

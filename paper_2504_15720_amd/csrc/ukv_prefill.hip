@@ -97,6 +97,15 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     // 16 the element i%4 of what the lanes 4x + i/4 (x = 0..3) of the group addressed: with lane s pointing
     // at elements 16 mm + 4 (s%4) .. +3 of token 4q + s/4, lane i receives V[4q + x][16 mm + i], x = 0..3.
     auto vswz = [](uint32_t tok) { return 2 * ((tok / (256 / KB)) % (KB / 32)); };
+    // where, inside a head-row (K) or a row of the fp16 copy (V), the pieces lie that this lane's loads fetch
+    uint32_t k_piece[KI], v_piece[KI], kv_delta[KI];
+#pragma unroll
+    for (uint32_t x = 0; x < KI; ++x) {
+        const uint32_t tok = ld_tok + RPI * x;
+        k_piece[x] = (ld_pos ^ (tok % PIECES)) * 16;
+        v_piece[x] = (ld_pos ^ vswz(tok)) * 16;
+        kv_delta[x] = KB + v_piece[x] - k_piece[x]; // from the lane's K piece to its V piece of the same head-row
+    }
     uint32_t voff[MM]; // this lane's read offsets into a staged V tile, one per group of 16 output rows
     {
         const uint32_t tok = 4 * q + j / 4, h = j % 4;
@@ -122,7 +131,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     bool col_ok[NB];
     bf16x8_t qreg[NB][KSTEPS]; // the q operands stay in registers: re-reading them from LDS for every tile cost 3 %
     f32x4_t oacc[NB][MM];
-    float m[NB];
+    float m[NB], m_lazy[NB]; // reference point of the exponentials, and the maximum above which it moves (m + kLazy)
     f32x4_t lacc[NB]; // running sums of the weights, every element the same (see pv)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -142,6 +151,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         for (int mm = 0; mm < MM; ++mm)
             oacc[b][mm] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         m[b] = kMinusBig;
+        m_lazy[b] = kMinusBig + kLazy;
         lacc[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     }
     // tokens this wave / this workgroup has to look at: up to the position of the last valid row
@@ -176,42 +186,41 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             // Window-relative byte offsets fit 32 bits (a window spans at most kPfTabWindow pages).
             const uint32_t c0 = (uint32_t)(((uint64_t)w0 * T + row_off) - (s_lo << lg));
             const uint32_t T32 = (uint32_t)T, mask32 = (uint32_t)page_mask;
-            auto row_ptr = [&](uint32_t t) -> const unsigned char * {
-                const uint32_t off = (t - w0) * T32 + c0;
+            // Address of token t's head-row, `add` bytes into it.  The offset inside the window is a product of
+            // 24-bit factors (a window holds fewer than 2^24 tokens, a token row is shorter than 2^24 bytes: the
+            // full-rate multiply); what is added to the page's address is formed in 32 bits first.
+            auto row_ptr = [&](uint32_t t, uint32_t add) -> const unsigned char * {
+                const uint32_t off = __umul24(t - w0, T32) + c0;
                 const int32_t pg = tab[off >> lg];
-                return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + (off & mask32));
+                return a.pool_base + (((uint64_t)(uint32_t)pg << lg) + ((off & mask32) + add));
             };
             // Tile staging: each wave fetches RPI KI of the tile's 32 K rows (or V rows), RPI rows per
             // global-to-LDS load.  Tokens past the window's end are copies of its last token (masked in the
             // scores).  A tile's K is requested one step before its V, so the row addresses are worked out
             // once, for K, and kept for V.
-            struct RowPtrs {
+            struct RowPtrs { // of this lane's K pieces of a tile (its V pieces: kv_delta[x] further, two-part weights only)
                 const unsigned char *p[KI];
             };
             auto rows_of = [&](uint32_t tb) {
                 RowPtrs r;
 #pragma unroll
                 for (uint32_t x = 0; x < KI; ++x)
-                    r.p[x] = row_ptr(min(tb + ld_tok + RPI * x, last));
+                    r.p[x] = row_ptr(min(tb + ld_tok + RPI * x, last), k_piece[x]);
                 return r;
             };
             auto issue_k = [&](const RowPtrs &r, unsigned char *kt) {
 #pragma unroll
-                for (uint32_t x = 0; x < KI; ++x) {
-                    const uint32_t tok = ld_tok + RPI * x;
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x] + ((ld_pos ^ (tok % PIECES)) * 16)),
-                                                     (lds_ptr_t)(kt + (KI * wave + x) * 1024), 16, 0, 0);
-                }
+                for (uint32_t x = 0; x < KI; ++x)
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(r.p[x]), (lds_ptr_t)(kt + (KI * wave + x) * 1024), 16, 0, 0);
             };
             // V rows of the tile at tb: from the pool (r: the row addresses worked out for the tile's K), or, with
             // one-part weights, from the fp16 copy, whose rows of one kv head follow each other.
             auto issue_v = [&](const RowPtrs &r, uint32_t tb, unsigned char *vt) {
 #pragma unroll
                 for (uint32_t x = 0; x < KI; ++x) {
-                    const uint32_t tok = ld_tok + RPI * x;
-                    const unsigned char *src = PARTS == 1 ? v16 + (uint64_t)min(tb + tok, last) * KB : r.p[x] + KB;
-                    __builtin_amdgcn_global_load_lds((global_ptr_t)(src + (ld_pos ^ vswz(tok)) * 16),
-                                                     (lds_ptr_t)(vt + (KI * wave + x) * 1024), 16, 0, 0);
+                    const unsigned char *src = PARTS == 1 ? v16 + ((uint64_t)min(tb + ld_tok + RPI * x, last) * KB + v_piece[x])
+                                                          : r.p[x] + kv_delta[x];
+                    __builtin_amdgcn_global_load_lds((global_ptr_t)(src), (lds_ptr_t)(vt + (KI * wave + x) * 1024), 16, 0, 0);
                 }
             };
             // Raw scores S^T = K Q^T of one staged K tile against all NB blocks of the wave.
@@ -238,9 +247,9 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             // that the blocks' independent instruction chains can overlap.  MASKED: the tile reaches past
             // some column's position (or past the window); otherwise every score counts and the compares
             // are skipped.  A block that lies wholly before the tile just sees every score masked.
-            // Returns whether some accumulator has to be rescaled before the tile is added: by 2^(-grow[b]).
+            // Returns whether some accumulator has to be rescaled before the tile is added: by 2^(m_old[b] - m[b]).
             auto softmax = [&](uint32_t tb, const f32x4_t (&s0)[NB], const f32x4_t (&s1)[NB], uint4 (&Ph)[NB],
-                               uint4 (&Pl)[NB], float (&grow)[NB], auto masked) -> bool {
+                               uint4 (&Pl)[NB], float (&m_old)[NB], auto masked) -> bool {
                 constexpr bool MASKED = decltype(masked)::value;
                 // Raw scores; the scale (times log2 e, positive) is applied to the maximum and folded into
                 // the multiply-add under the exponential.
@@ -265,18 +274,18 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     mt[b] = fmaxf(fmaxf(fmaxf(sr[b][0], sr[b][1]), fmaxf(sr[b][2], sr[b][3])),
                                   fmaxf(fmaxf(sr[b][4], sr[b][5]), fmaxf(sr[b][6], sr[b][7])));
                 }
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    mt[b] = max_over_kblocks(mt[b]) * scale_log2e;
-                bool rescale = false;
+                max_over_kblocks_pair(mt);
+                uint64_t rescale = 0; // lanes one of whose columns moves its reference (kept as a mask: no round trip through a register)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     // The reference point of the exponentials only moves when the maximum has grown by
                     // more than 2^kLazy: weights then stay below 2^kLazy, and the accumulators are rescaled
-                    // rarely.
-                    const float mn = mt[b] > m[b] + kLazy ? mt[b] : m[b]; // finite: m starts at kMinusBig
-                    grow[b] = mn - m[b]; // how far the reference point moved: 0 almost always
-                    rescale |= grow[b] != 0.f;
+                    // rarely (by 2^-grow, worked out only then: see step).
+                    mt[b] *= scale_log2e;
+                    const bool moves = mt[b] > m_lazy[b];
+                    const float mn = moves ? mt[b] : m[b]; // finite: m starts at kMinusBig
+                    rescale |= __builtin_amdgcn_ballot_w64(moves);
+                    m_old[b] = m[b];
                     m[b] = mn;
                     uint32_t ph[4], pl[4] = {0, 0, 0, 0};
                     const float neg_ref = kShift - mn;
@@ -298,7 +307,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     Ph[b] = make_uint4(ph[0], ph[1], ph[2], ph[3]);
                     Pl[b] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
                 }
-                return __builtin_amdgcn_ballot_w64(rescale) != 0;
+                return rescale != 0;
             };
             // O^T += V^T P^T for one staged V tile, one group of 16 output rows at a time, multiplied into every
             // block.  The weights' running sums ride along as one more product with an all-ones left operand: every row
@@ -365,7 +374,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                 }
                 if (tb < r1) {
                     uint4 Ph[NB], Pl[NB];
-                    float grow[NB];
+                    float m_old[NB];
                     bool rescale;
                     // The next tile's scores are taken whether or not this wave (or the window) has a next
                     // tile: without one they are computed from stale LDS contents and never used.
@@ -374,15 +383,16 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
                     // and every column of the wave is a valid row
                     if (tb + 32 <= r1 && tb + 32 <= wave_lo + 1 && wave_full) {
                         scores(k_next, n0s, n1s);
-                        rescale = softmax(tb, c0s, c1s, Ph, Pl, grow, std::false_type{});
+                        rescale = softmax(tb, c0s, c1s, Ph, Pl, m_old, std::false_type{});
                     } else {
                         scores(k_next, n0s, n1s);
-                        rescale = softmax(tb, c0s, c1s, Ph, Pl, grow, std::true_type{});
+                        rescale = softmax(tb, c0s, c1s, Ph, Pl, m_old, std::true_type{});
                     }
                     if (rescale) {
 #pragma unroll
                         for (int b = 0; b < NB; ++b) {
-                            const float alpha = fast_exp2(-grow[b]);
+                            const float alpha = fast_exp2(m_old[b] - m[b]); // 1 for a column whose reference stayed
+                            m_lazy[b] = m[b] + kLazy;
                             lacc[b] *= alpha;
 #pragma unroll
                             for (int mm = 0; mm < MM; ++mm)
