@@ -841,7 +841,7 @@ static size_t prefill_rec_bound(const ukv_pool *p, uint32_t n_requests, uint64_t
     uint64_t max_kv = 1, max_g = 1;
     for (uint32_t s = 0; s < p->n_services; ++s) {
         max_kv = std::max<uint64_t>(max_kv, p->classes.c[s].n_kv);
-        max_g = std::max<uint64_t>(max_g, p->classes.c[s].g);
+        max_g = std::max<uint64_t>(max_g, prefill_group_columns(p->classes.c[s].g));
     }
     const uint64_t min_rows = std::max<uint64_t>(1, kPrefillCols / max_g);
     const uint64_t tiles = max_kv * (total_q_rows / min_rows + n_requests);
@@ -930,8 +930,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         }
         if (q_len[i] == 0)
             continue;
-        if ((c.d != 128 && c.d != 64) || 16 % c.g != 0) {
-            set_error("prefill attention supports head_dim 128 or 64 with group 1, 2, 4, 8 or 16");
+        if ((c.d != 128 && c.d != 64) || c.g > 16) {
+            set_error("prefill attention supports head_dim 128 or 64 with groups of up to 16 query heads");
             return UKV_EINVAL;
         }
         if (c.token_bytes >= (1u << 24)) { // the kernel's row offsets are products of 24-bit factors
@@ -967,7 +967,8 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 continue;
             const uint32_t k = (uint32_t)(std::min_element(load.begin(), load.end()) - load.begin());
             load[k] += g.cost;
-            const uint32_t rows = kPrefillCols / c.g;
+            const uint32_t gl = prefill_group_columns(c.g);
+            const uint32_t rows = kPrefillCols / gl;
             const uint32_t n_tiles = (q_len[i] + rows - 1) / rows;
             for (uint32_t t = n_tiles; t-- > 0;) { // the last rows look at the most tokens: they go first
                 PrefillRec r{};
@@ -979,7 +980,7 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 r.kvh = g.kvh;
                 r.v16_off = v16_base[i] + (uint64_t)g.kvh * b->ctx_len[i] * 2 * c.d; // made absolute below
                 r.r0 = t * rows;
-                r.g = c.g;
+                r.g = c.g | (gl << 16);
                 r.n_q = c.n_q;
                 r.token_bytes = c.token_bytes;
                 r.scale_log2e = c.scale_log2e;

@@ -553,7 +553,8 @@ __device__ __forceinline__ void process_item(const StepPages &sp) {
 
 
 // ---------------------------------------------------------------------------------------------
-// Grouped-query path (head_dim 128, G = 2, 4 or 8 query heads per kv head) on the matrix cores.
+// Grouped-query path (head_dim 128, G = 2 .. 16 query heads per kv head: whatever fits the 16 columns of a
+// product) on the matrix cores.
 //
 // With G query heads sharing one kv head the path does G flop per KV byte and the plain-ALU
 // formulation above becomes ALU-bound.  Here one wave owns one kv head and walks the item's

@@ -47,6 +47,11 @@ __host__ __device__ inline bool merges_in_launch(uint32_t n_parts, uint32_t part
 // The second launch takes sequences of up to this many parts with one wave per (sequence, query head), part
 // after part, and longer ones with four waves that share the parts.
 static constexpr uint32_t kReduceFewParts = 24;
+// reduce_few_kernel gives a lane 64-float strides of one partial and one query head's (m, l): in the matrix-core layout
+// that needs the group size to divide 32 and 2 G <= 16 elements per lane.  Other group sizes go to reduce_many_kernel.
+__host__ __device__ inline bool reduce_few_takes(uint32_t layout_g) {
+    return layout_g == 0 || layout_g == 2 || layout_g == 4 || layout_g == 8;
+}
 
 // Per-service constants used by the kernels.
 struct ClassRec {
@@ -170,10 +175,18 @@ struct PrefillRec {
     uint64_t v16_off; // one-part weights only: byte offset, in the workspace, of this (request, kv head)'s V rows as fp16
     uint32_t r0;      // first query row of the tile
     // what the kernel needs of the service's class, copied here so that a workgroup starts with one load
-    uint32_t g, n_q, token_bytes;
+    uint32_t g; // low half: query heads per kv head; high half: that number rounded up to a power of two, the number
+                // of columns a query row takes up in a block of 16 (columns past the group stay empty)
+    uint32_t n_q, token_bytes;
     float scale_log2e;
     uint32_t kvh;
 };
+inline uint32_t prefill_group_columns(uint32_t g) { // 1, 2, 4, 8 or 16
+    uint32_t gl = 1;
+    while (gl < g)
+        gl *= 2;
+    return gl;
+}
 static_assert(sizeof(PrefillRec) == 64, "PrefillRec layout");
 
 struct PrefillArgs {

@@ -234,7 +234,9 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         plan.max_reduce_units = std::max(plan.max_reduce_units, r.layout_g ? r.n_heads / r.layout_g : r.n_heads);
     }
     const auto many = std::stable_partition(plan.reduce.begin(), plan.reduce.end(),
-                                            [](const ReduceRec &r) { return r.n_parts > kReduceFewParts; });
+                                            [](const ReduceRec &r) {
+                                                return r.n_parts > kReduceFewParts || !reduce_few_takes(r.layout_g);
+                                            });
     plan.n_reduce_many = (uint32_t)(many - plan.reduce.begin());
     return UKV_OK;
 }

@@ -80,7 +80,8 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     const uint64_t table_off = uni(s_rec.table_off), q_off = uni(s_rec.q_off), out_off = uni(s_rec.out_off);
     const uint32_t ctx_len = uni(s_rec.ctx_len), kvh = uni(s_rec.kvh), r0 = uni(s_rec.r0);
     const unsigned char *v16 = PARTS == 1 ? a.v16 + uni(s_rec.v16_off) : nullptr; // this (request, kv head)'s V rows as fp16
-    const uint32_t G = uni(s_rec.g), n_q = uni(s_rec.n_q);
+    // G query heads share the kv head; a query row takes GL columns of a block (G rounded up to a power of two)
+    const uint32_t G = uni(s_rec.g) & 0xffffu, GL = uni(s_rec.g) >> 16, n_q = uni(s_rec.n_q);
     const uint64_t T = uni(s_rec.token_bytes);
     const float scale_log2e = uni(s_rec.scale_log2e);
     int32_t *tab = s_ptab;
@@ -122,7 +123,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         w.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 16 * KB));
         return __builtin_bit_cast(uint4, w);
     };
-    const uint32_t rpb = 16 / G;                   // query rows per block of 16 columns
+    const uint32_t rpb = 16 / GL;                  // query rows per block of 16 columns
     const uint32_t pos0 = ctx_len - q_len;         // position of query row 0
     const uint32_t row_w = r0 + wave * NB * rpb;   // first row of this wave
 
@@ -135,11 +136,11 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     f32x4_t lacc[NB]; // running sums of the weights, every element the same (see pv)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        const uint32_t row = row_w + b * rpb + j / G;
-        col_ok[b] = row < q_len;
+        const uint32_t row = row_w + b * rpb + j / GL;
+        col_ok[b] = row < q_len && j % GL < G;
         col_pos[b] = pos0 + row;
         const uint4 *qp = reinterpret_cast<const uint4 *>(a.q + q_off + ((uint64_t)(col_ok[b] ? row : 0) * n_q + kvh * G +
-                                                                         j % G) * D) + q;
+                                                                         (col_ok[b] ? j % GL : 0)) * D) + q;
 #pragma unroll
         for (int st = 0; st < KSTEPS; ++st) {
             uint4 w = ld_g16(qp + st * 4);
@@ -441,7 +442,7 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             continue;
         const float inv = lb > 0.f ? 1.f / lb : 0.f;
         const uint32_t row = col_pos[b] - pos0;
-        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % G) * D + 4 * q;
+        float *dst = a.out + out_off + ((uint64_t)row * n_q + kvh * G + j % GL) * D + 4 * q;
 #pragma unroll
         for (int mm = 0; mm < MM; ++mm)
             st_g16(dst + 16 * mm, oacc[b][mm][0] * inv, oacc[b][mm][1] * inv, oacc[b][mm][2] * inv,

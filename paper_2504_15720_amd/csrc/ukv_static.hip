@@ -170,7 +170,8 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
         const uint32_t np = parts_of(k);
         if (np > 1) {
             floats_mine += (uint64_t)np * seqs[k].part_stride;
-            if (np > kReduceFewParts)
+            const ClassRec &c = a.classes.c[seqs[k].cls];
+            if (np > kReduceFewParts || !reduce_few_takes(c.kind == kD128GQA ? c.g : 0))
                 ++many_mine;
             else
                 ++few_mine;
@@ -197,7 +198,7 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
         r.n_heads = c.hs * c.g;
         r.d = c.d;
         r.layout_g = c.kind == kD128GQA ? c.g : 0;
-        if (np > kReduceFewParts)
+        if (np > kReduceFewParts || !reduce_few_takes(r.layout_g))
             many[m_run++] = r;
         else
             few[w_run++] = r;
@@ -311,12 +312,14 @@ extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch
     }
     // sizes against the fixed scratch array
     uint32_t max_sl = 1, max_stride = 32, max_heads = 1, max_units = 1;
+    bool all_few = true; // no service whose cut sequences all go to the many-parts merge kernel (see reduce_few_takes)
     for (uint32_t s = 0; s < p->n_services; ++s) {
         const ClassRec &c = p->classes.c[s];
         max_sl = std::max(max_sl, c.n_kv / c.hs);
         max_stride = std::max(max_stride, part_stride_of(c));
         max_heads = std::max(max_heads, c.hs * c.g);
         max_units = std::max(max_units, c.kind == kD128GQA ? c.hs : c.hs * c.g);
+        all_few = all_few && reduce_few_takes(c.kind == kD128GQA ? c.g : 0);
     }
     if (n > kStaticMaxRequests || (uint64_t)n * max_sl > kStaticMaxSeqs) {
         set_error("batch too large for the static scratch array: at most " + std::to_string(kStaticMaxRequests) +
@@ -386,7 +389,7 @@ extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch
         return UKV_EHIP;
     }
     // At most max_spans - 1 sequences are cut; one of more than kReduceFewParts parts uses up that many boundaries.
-    const uint32_t few_bound = max_spans - 1, many_bound = (max_spans - 1) / kReduceFewParts;
+    const uint32_t few_bound = max_spans - 1, many_bound = all_few ? (max_spans - 1) / kReduceFewParts : max_spans - 1;
     const uint32_t *counts = (const uint32_t *)(sp + kOffCounts);
     e = launch_reduce_counted((const ReduceRec *)(sp + kOffMany), counts, many_bound, (const ReduceRec *)(sp + kOffFew),
                               counts + 1, few_bound, max_heads, max_units, a.partials, a.out, s);
