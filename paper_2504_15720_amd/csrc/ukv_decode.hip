@@ -368,7 +368,7 @@ __device__ __forceinline__ void process_item(const StepPages &sp) {
     float *mbuf = s_mbuf;
     constexpr int LPR = D / 8;   // lanes per row
     constexpr int NG = NT / LPR; // row groups in the workgroup
-    constexpr int U = 4;
+    constexpr int U = G >= 8 ? 1 : G >= 4 ? 2 : 4; // tokens per lane and round trip: what the registers hold next to G accumulator rows
     const int tid = threadIdx.x;
     const int lir = tid % LPR, grp = tid / LPR;
     const uint32_t HS = c.hs, TI = c.ti;
@@ -888,6 +888,10 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const StepPages
                 process_item<128, 1, NT>(sp);
             else if ((KINDS & (1u << kD128GQA)) && kind == kD128GQA)
                 process_item_gqa<NT>(sp);
+            else if ((KINDS & (1u << kD64G4)) && kind == kD64G4)
+                process_item<64, 4, NT>(sp);
+            else if ((KINDS & (1u << kD64G8)) && kind == kD64G8)
+                process_item<64, 8, NT>(sp);
             rec = rec_next;
         }
         __syncthreads(); // every wave has read the previous s_span
@@ -1076,8 +1080,8 @@ int decode_resident_workgroups(uint32_t block_threads) {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return 0;
     hipError_t e = block_threads == 512
-                       ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<512, kAllKinds>, 512, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<256, kAllKinds>, 256, 0);
+                       ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<512, kWorkloadKinds>, 512, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<256, kWorkloadKinds>, 256, 0);
     if (e != hipSuccess || per_cu <= 0 || cus <= 0) // (a kernel that does not fit a CU at all)
         return 0;
     return cus;
@@ -1085,8 +1089,9 @@ int decode_resident_workgroups(uint32_t block_threads) {
 
 // The compiled sets of kinds, smallest first; a launch takes the first one that covers the pool's kinds.
 static constexpr uint32_t kKindSets[] = {1u << kD128G1, (1u << kD64G1) | (1u << kD64G2),
-                                         (1u << kD64G1) | (1u << kD64G2) | (1u << kD128G1), 1u << kD128GQA, kAllKinds};
-static constexpr int kNumKindSets = 5;
+                                         (1u << kD64G1) | (1u << kD64G2) | (1u << kD128G1), 1u << kD128GQA,
+                                         kWorkloadKinds, kAllKinds};
+static constexpr int kNumKindSets = 6;
 
 static int kind_set_of(uint32_t kinds) {
     if (kinds == 0 || (kinds & ~kAllKinds))
@@ -1104,6 +1109,7 @@ static DecodeKernelFn decode_kernel_fn(int set, bool big) {
     case 1: return big ? decode_kernel<512, kKindSets[1]> : decode_kernel<256, kKindSets[1]>;
     case 2: return big ? decode_kernel<512, kKindSets[2]> : decode_kernel<256, kKindSets[2]>;
     case 3: return big ? decode_kernel<512, kKindSets[3]> : decode_kernel<256, kKindSets[3]>;
+    case 4: return big ? decode_kernel<512, kKindSets[4]> : decode_kernel<256, kKindSets[4]>;
     default: return big ? decode_kernel<512, kAllKinds> : decode_kernel<256, kAllKinds>;
     }
 }

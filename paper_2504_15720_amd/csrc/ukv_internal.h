@@ -76,7 +76,10 @@ struct ItemRec {
 static_assert(sizeof(ItemRec) == 128 && offsetof(ItemRec, it.t1) == 8 && offsetof(ItemRec, s.ctx_len) == 56,
               "ItemRec layout (the kernel patches t1 and ctx_len by position)");
 
-enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kNumKinds };
+// kD64G4 / kD64G8: grouped queries at head_dim 64 on the plain path (there is no matrix-core path at this head_dim);
+// arithmetic-bound, kept out of the kernels that the workloads' pools use (kWorkloadKinds).
+enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kD64G4, kD64G8, kNumKinds };
+static constexpr uint32_t kWorkloadKinds = (1u << kD64G1) | (1u << kD64G2) | (1u << kD128G1) | (1u << kD128GQA);
 static constexpr uint32_t kAllKinds = (1u << kNumKinds) - 1;
 
 // floats of one split partial of a (request, head-slice) sequence: accumulators and (m, l) pairs of its query heads,

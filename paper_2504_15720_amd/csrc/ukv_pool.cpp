@@ -68,10 +68,10 @@ int derive_classes(ukv_pool *p) {
         c.scale_log2e = (float)(scale * 1.4426950408889634);
         if (c.d == 128 && c.g >= 1 && c.g <= 16) // the matrix-core path pads a group to the 16 columns of a product
             c.kind = c.g == 1 ? kD128G1 : kD128GQA;
-        else if (c.d == 64 && (c.g == 1 || c.g == 2))
-            c.kind = c.g == 1 ? kD64G1 : kD64G2;
+        else if (c.d == 64 && (c.g == 1 || c.g == 2 || c.g == 4 || c.g == 8))
+            c.kind = c.g == 1 ? kD64G1 : c.g == 2 ? kD64G2 : c.g == 4 ? kD64G4 : kD64G8;
         else
-            return fail(UKV_EINVAL, "unsupported shape: head_dim 128 with group 1..16, or head_dim 64 with group 1/2");
+            return fail(UKV_EINVAL, "unsupported shape: head_dim 128 with group 1..16, or head_dim 64 with group 1/2/4/8");
         p->kinds |= 1u << c.kind;
         if (c.kind == kD128GQA) {
             // matrix-core path: one wave per kv head of the slice, all waves on the same tokens
