@@ -251,7 +251,12 @@ int ukv_decode_attention_static(ukv_pool_t *pool, const ukv_device_batch_t *batc
  *   ukv_prefill_workspace_bytes_one_part(pool, n_requests, sum of q_len, sum of ctx_len over the requests
  *   with q_len > 0) bytes.  By default the call takes the one-part form when the workspace is that large and the
  *   batch has at least 2000 flop of attention per byte of that copy (whole prompts of a few hundred tokens and more;
- *   below that the copy costs more than it saves), and the two-part form otherwise. */
+ *   below that the copy costs more than it saves), and the two-part form otherwise.
+ *
+ * A workgroup takes 128 / G query rows of one (request, kv head) and walks the tokens they can see.  Where that gives few
+ * workgroups with long walks (a chunk of a long prompt), the walks are cut into stretches of 1024 tokens or more, each a
+ * workgroup that leaves a partial result in the workspace, merged by one more launch -- if the workspace has the room
+ * that ukv_prefill_workspace_bytes_one_part includes for it (about 140 MB); else one workgroup per tile. */
 size_t ukv_prefill_workspace_bytes(const ukv_pool_t *pool, uint32_t n_requests, uint64_t total_q_rows);
 size_t ukv_prefill_workspace_bytes_one_part(const ukv_pool_t *pool, uint32_t n_requests, uint64_t total_q_rows,
                                             uint64_t total_ctx_tokens);
@@ -333,6 +338,8 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
                                         the workspace is too small); 2 = always two parts */
 #define UKV_PARAM_PREFILL_FORM_USED 15 /* read only: the form the pool's last ukv_prefill_attention call took (1 or 2;
                                         0 before the first call) */
+#define UKV_PARAM_PREFILL_PARTIALS_USED 16 /* read only: partial results the pool's last ukv_prefill_attention call made
+                                        (0 = every tile of query rows was walked by one workgroup) */
 #define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
                                         workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);

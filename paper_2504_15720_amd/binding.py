@@ -22,7 +22,7 @@ UKV_PARAM_MAX_SPANS, UKV_PARAM_MIN_SPAN_BYTES, UKV_PARAM_BLOCK_THREADS = 1, 2, 3
 UKV_PARAM_HEADS_PER_SLICE, UKV_PARAM_PROFILE, UKV_PARAM_FUSED_MERGE = 4, 5, 6
 UKV_PARAM_SLOTS, UKV_PARAM_TAPER, UKV_PARAM_GQA_COST_PCT, UKV_PARAM_PREFILL_XCD = 7, 8, 9, 10
 UKV_PARAM_REPLAN_EVERY, UKV_PARAM_MERGE_ACQ_REL, UKV_PARAM_VALIDATE, UKV_PARAM_PREFILL_WEIGHTS = 11, 12, 13, 14
-UKV_PARAM_PREFILL_FORM_USED = 15
+UKV_PARAM_PREFILL_FORM_USED, UKV_PARAM_PREFILL_PARTIALS_USED = 15, 16
 
 EXPORTS = [
     "ukv_pool_create", "ukv_pool_destroy", "ukv_pool_info", "ukv_pages_for_tokens", "ukv_pages_alloc",

@@ -873,8 +873,12 @@ size_t ukv_prefill_workspace_bytes_one_part(const ukv_pool_t *p, uint32_t n_requ
         min_chunk = std::min<uint64_t>(min_chunk, v16_chunk_tokens(c));
     }
     const uint64_t n_chunks = total_ctx_tokens / min_chunk + n_requests;
+    // ... and room for the walks of few, long tiles to be cut into stretches: their records, merge list and partials
+    const size_t split = align_up((size_t)kPrefillMaxParts * kXcds * sizeof(PrefillRec)) +
+                         align_up((size_t)kPrefillMaxParts * sizeof(PrefillMergeRec)) +
+                         align_up((size_t)kPrefillMaxParts * kPrefillPartFloats * sizeof(float));
     return ukv_prefill_workspace_bytes(p, n_requests, total_q_rows) + align_up((size_t)(n_chunks * sizeof(V16Rec))) +
-           (size_t)(total_ctx_tokens * max_row) + 256 * (size_t)n_requests;
+           (size_t)(total_ctx_tokens * max_row) + 256 * (size_t)n_requests + split;
 }
 
 int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q_len, void *workspace,
@@ -956,7 +960,34 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     // loaded of the XCD queues, then the queues interleaved (padded with fillers to the longest).
     const uint32_t n_queues = p->tun.prefill_xcd ? kXcds : 1;
     static const uint32_t kDims[2] = {128, 64};
+    // Few workgroups that each walk a long context (a chunk of one long prompt) leave most of the device idle and take
+    // as long as the walk: where the longest walk is more than 5/4 of what an even spread over the resident
+    // workgroups would give, the tiles' walks are cut into stretches of about that even share (at least 1024 tokens),
+    // each a workgroup of its own that leaves a partial result, merged by a second launch.
+    uint64_t total_walk = 0, longest_walk = 0; // in tokens, summed over every (request, kv head, tile of rows)
+    for (const Group &g : groups) {
+        const uint32_t i = g.req;
+        const ClassRec &c = p->classes.c[b->service_id[i]];
+        const uint32_t rows = kPrefillCols / prefill_group_columns(c.g);
+        for (uint32_t r0 = 0; r0 < q_len[i]; r0 += rows) {
+            const uint64_t walk = (uint64_t)b->ctx_len[i] - q_len[i] + std::min<uint32_t>(r0 + rows, q_len[i]);
+            total_walk += walk;
+            longest_walk = std::max(longest_walk, walk);
+        }
+    }
+    const int cus = decode_resident_workgroups(256);
+    const uint64_t places = 2ull * (cus > 0 ? (uint64_t)cus : 256); // two workgroups of this kernel per compute unit
+    uint32_t stretch = 0; // 0: every tile is walked by one workgroup
+    if (4 * longest_walk > 5 * (total_walk / places) && longest_walk >= 2 * kPrefillMinStretch)
+        stretch = (uint32_t)std::max<uint64_t>(kPrefillMinStretch, (total_walk / (2 * places) + 31) / 32 * 32);
     std::vector<PrefillRec> list[2];
+    std::vector<PrefillMergeRec> merges;
+    uint32_t n_parts = 0;
+    size_t part_floats_total = 0;
+    auto build_lists = [&](uint32_t stretch_tokens) {
+    merges.clear();
+    n_parts = 0;
+    part_floats_total = 0;
     for (int di = 0; di < 2; ++di) {
         std::vector<std::vector<PrefillRec>> queue(n_queues);
         std::vector<uint64_t> load(n_queues, 0);
@@ -984,7 +1015,34 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
                 r.n_q = c.n_q;
                 r.token_bytes = c.token_bytes;
                 r.scale_log2e = c.scale_log2e;
-                queue[k].push_back(r);
+                const uint32_t walk = b->ctx_len[i] - q_len[i] + std::min<uint32_t>(r.r0 + rows, q_len[i]);
+                const uint32_t n_seg = stretch_tokens && walk > stretch_tokens + stretch_tokens / 2
+                                           ? (walk + stretch_tokens - 1) / stretch_tokens : 1;
+                if (n_seg == 1) {
+                    r.t0 = 0;
+                    r.t1 = walk;
+                    r.part = kPrefillDirect;
+                    queue[k].push_back(r);
+                    continue;
+                }
+                const uint32_t seg = ((walk + n_seg - 1) / n_seg + 31) / 32 * 32; // stretches start at multiples of 32
+                PrefillMergeRec m{};
+                m.out_off = r.out_off;
+                m.part0 = n_parts;
+                m.q_len = r.q_len;
+                m.r0 = r.r0;
+                m.g = r.g;
+                m.n_q = r.n_q;
+                m.kvh = r.kvh;
+                m.d = c.d;
+                for (uint32_t t0 = 0; t0 < walk; t0 += seg) {
+                    r.t0 = t0;
+                    r.t1 = std::min(t0 + seg, walk);
+                    r.part = n_parts++;
+                    ++m.n_parts;
+                    queue[k].push_back(r);
+                }
+                merges.push_back(m);
             }
         }
         size_t longest = 0;
@@ -995,8 +1053,21 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
             for (size_t e = 0; e < queue[k].size(); ++e)
                 list[di][e * n_queues + k] = queue[k][e];
     }
+    part_floats_total = (size_t)n_parts * kPrefillPartFloats;
+    };
+    build_lists(stretch);
+    auto fixed_bytes = [&]() { // records, merge list and partials: what the call needs whichever form the weights take
+        return align_up((list[0].size() + list[1].size()) * sizeof(PrefillRec)) +
+               align_up(merges.size() * sizeof(PrefillMergeRec)) + align_up(part_floats_total * sizeof(float));
+    };
+    if (stretch && (fixed_bytes() > ws_bytes || n_parts > kPrefillMaxParts)) {
+        stretch = 0; // no room for the partial results: one workgroup per tile, as the smaller workspace size promises
+        build_lists(0);
+    }
     const size_t n_recs = list[0].size() + list[1].size();
     const size_t rec_bytes = align_up(n_recs * sizeof(PrefillRec)); // the records carry what they need of their class
+    const size_t merge_bytes = align_up(merges.size() * sizeof(PrefillMergeRec));
+    const size_t partial_bytes = align_up(part_floats_total * sizeof(float));
     if (rec_bytes > ws_bytes) {
         set_error("workspace too small for this batch");
         return UKV_ENOSPC;
@@ -1004,7 +1075,7 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     // Form of the weights: one fp16 part needs the fp16 copy of V in the workspace, behind the records and the copy
     // pass's own work list.
     const size_t chunk_bytes = align_up((size_t)(n_chunks * sizeof(V16Rec)));
-    const size_t one_part_total = rec_bytes + chunk_bytes + (size_t)v16_bytes;
+    const size_t one_part_total = rec_bytes + merge_bytes + chunk_bytes + (size_t)v16_bytes + partial_bytes;
     uint32_t parts = 2;
     if (p->tun.prefill_weights == 1) {
         if (one_part_total > ws_bytes) {
@@ -1016,7 +1087,10 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         parts = 1;
     }
     p->tun.prefill_form_used = parts;
-    const size_t total = parts == 1 ? rec_bytes + chunk_bytes : rec_bytes;
+    p->tun.prefill_partials_used = n_parts;
+    const size_t total = rec_bytes + merge_bytes + (parts == 1 ? chunk_bytes : 0); // what is uploaded
+    const size_t v16_start = total;
+    const size_t partial_start = v16_start + (parts == 1 ? (size_t)v16_bytes : 0);
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
@@ -1026,11 +1100,12 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         std::memcpy(recs, list[0].data(), list[0].size() * sizeof(PrefillRec));
     if (!list[1].empty())
         std::memcpy(recs + list[0].size(), list[1].data(), list[1].size() * sizeof(PrefillRec));
+    if (!merges.empty())
+        std::memcpy(h + rec_bytes, merges.data(), merges.size() * sizeof(PrefillMergeRec));
     if (parts == 1) {
-        const uint64_t v16_start = rec_bytes + chunk_bytes;
         for (size_t e = 0; e < n_recs; ++e)
             recs[e].v16_off += v16_start;
-        V16Rec *ch = (V16Rec *)(h + rec_bytes);
+        V16Rec *ch = (V16Rec *)(h + rec_bytes + merge_bytes);
         size_t k = 0;
         for (uint32_t i = 0; i < n; ++i) {
             if (q_len[i] == 0)
@@ -1062,11 +1137,12 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     a.q = (const uint16_t *)b->q;
     a.out = (float *)b->out;
     a.v16 = w;
+    a.partials = (float *)(w + partial_start);
     if ((rc = validate_tables(p, n, b->service_id, b->ctx_len, b->table_off, b->page_table, 0, s, &a.bad)) != UKV_OK)
         return rc;
     if (parts == 1)
-        HIP_TRY(launch_v16(p->base, p->log2_page, b->page_table, (const V16Rec *)(w + rec_bytes), (uint32_t)n_chunks, w,
-                           a.bad, s),
+        HIP_TRY(launch_v16(p->base, p->log2_page, b->page_table, (const V16Rec *)(w + rec_bytes + merge_bytes),
+                           (uint32_t)n_chunks, w, a.bad, s),
                 "launch fp16 copy of V");
     size_t first = 0;
     for (int di = 0; di < 2; ++di) {
@@ -1081,6 +1157,9 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
         pp.done();
         first += list[di].size();
     }
+    HIP_TRY(launch_prefill_merge((const PrefillMergeRec *)(w + rec_bytes), (uint32_t)merges.size(), a.partials, a.out, a.bad,
+                                 s),
+            "launch merge of the prefill partials");
     (void)total_rows;
     return UKV_OK;
 }

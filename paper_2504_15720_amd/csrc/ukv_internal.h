@@ -183,14 +183,21 @@ struct PrefillRec {
     uint32_t n_q, token_bytes;
     float scale_log2e;
     uint32_t kvh;
+    // The tokens this workgroup walks: all its rows can see (0 .. position of its last row), or, where few
+    // workgroups would each walk a long context, one stretch [t0, t1) of them (multiples of 32 but for the end), the
+    // result then going to partial `part` of the workspace (kPrefillDirect: straight to the output).
+    uint32_t t0, t1;
+    uint32_t part;
+    uint32_t pad_;
 };
+static constexpr uint32_t kPrefillDirect = 0xffffffffu;
 inline uint32_t prefill_group_columns(uint32_t g) { // 1, 2, 4, 8 or 16
     uint32_t gl = 1;
     while (gl < g)
         gl *= 2;
     return gl;
 }
-static_assert(sizeof(PrefillRec) == 64, "PrefillRec layout");
+static_assert(sizeof(PrefillRec) == 80, "PrefillRec layout");
 
 struct PrefillArgs {
     const unsigned char *pool_base;
@@ -201,7 +208,24 @@ struct PrefillArgs {
     const PrefillRec *recs;
     const uint32_t *bad; // null, or the flag of the page-table check: set = leave at once
     const unsigned char *v16; // one-part weights only: the workspace that holds the V rows as fp16
+    float *partials;          // results of workgroups that walk a stretch of their tokens (see prefill_part_floats)
 };
+// One partial: kPrefillCols columns x head_dim accumulators (not yet divided by the sum of weights), then the columns'
+// (reference point, sum of weights) pairs; every slot has the size the larger head_dim needs.
+static constexpr uint32_t kPrefillPartFloats = 128u * (128u + 2u);
+static constexpr uint32_t kPrefillMinStretch = 1024; // tokens: a shorter stretch is not worth a partial and a merge
+static constexpr uint32_t kPrefillMaxParts = 2048;   // partial slots a call may use (about 136 MB of workspace)
+
+// Merge of the partials of one tile of query rows that was walked in stretches: n_parts partials from slot part0 on.
+struct PrefillMergeRec {
+    uint64_t out_off;
+    uint32_t part0, n_parts;
+    uint32_t q_len, r0;
+    uint32_t g; // as PrefillRec::g
+    uint32_t n_q, kvh, d;
+    uint32_t pad_[2];
+};
+static_assert(sizeof(PrefillMergeRec) == 48, "PrefillMergeRec layout");
 
 // Work item of the pass that copies V rows out of the pool as fp16 (one-part weights): tokens [t0, t1) of one
 // request, all kv heads; head h's row of token t goes to v16_off + (h ctx_len + t) * 2 head_dim.
@@ -249,6 +273,8 @@ hipError_t launch_append(unsigned char *pool_base, uint32_t log2_page, int32_t *
                          uint32_t n, const ClassRec *classes, const void *new_k, const void *new_v,
                          const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
                          const uint32_t *bad, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_prefill_merge(const PrefillMergeRec *recs, uint32_t n_recs, const float *partials, float *out,
+                                const uint32_t *bad, hipStream_t s);
 hipError_t launch_v16(const unsigned char *pool_base, uint32_t log2_page, const int32_t *page_table, const V16Rec *recs,
                       uint32_t n_recs, unsigned char *v16, const uint32_t *bad, hipStream_t s);
 // parts: 2 = weights as two bf16 parts, 1 = as one fp16 part (a.v16 and the records' v16_off are then set)
@@ -289,6 +315,7 @@ struct Tunables {
     int64_t validate = 0; // check the page tables a call uses before its kernels run
     int64_t prefill_weights = 0; // 0 = chosen per call, 1 = one fp16 part, 2 = two bf16 parts
     int64_t prefill_form_used = 0; // what the last prefill call took
+    int64_t prefill_partials_used = 0;
     int64_t replan_every = 64; // a kept plan is remade after its requests have grown by this many tokens
     bool slots_auto = true;
 };

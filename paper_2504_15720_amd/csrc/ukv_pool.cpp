@@ -341,6 +341,7 @@ int ukv_get_param(const ukv_pool_t *p, int key, int64_t *value) {
     case UKV_PARAM_VALIDATE: *value = p->tun.validate; return UKV_OK;
     case UKV_PARAM_PREFILL_WEIGHTS: *value = p->tun.prefill_weights; return UKV_OK;
     case UKV_PARAM_PREFILL_FORM_USED: *value = p->tun.prefill_form_used; return UKV_OK;
+    case UKV_PARAM_PREFILL_PARTIALS_USED: *value = p->tun.prefill_partials_used; return UKV_OK;
     default: return fail(UKV_EINVAL, "unknown parameter");
     }
 }

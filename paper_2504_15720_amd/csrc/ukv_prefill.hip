@@ -162,13 +162,15 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
         const uint32_t last_row = min(first_row + n_rows, q_len) - 1;
         return pos0 + last_row + 1;
     };
-    const uint32_t wave_hi = hi_of(row_w, NB * rpb);
-    const uint32_t wg_hi = hi_of(r0, NW * NB * rpb);
+    // ... cut to the stretch [t0, t1) this workgroup was given (the whole of it unless the tile's walk was split)
+    const uint32_t t0 = uni(s_rec.t0), t1 = uni(s_rec.t1), part = uni(s_rec.part);
+    const uint32_t wave_hi = min(hi_of(row_w, NB * rpb), t1);
+    const uint32_t wg_hi = min(hi_of(r0, NW * NB * rpb), t1);
     const uint32_t wave_lo = pos0 + row_w;                     // position of the wave's first row
     const bool wave_full = row_w + NB * rpb <= q_len;          // all the wave's columns are valid rows
 
     const uint64_t row_off = (uint64_t)kvh * (4 * D);
-    uint32_t w0 = 0;
+    uint32_t w0 = t0;
     while (w0 < wg_hi) { // workgroup-uniform: one pass per page-table window
         const uint64_t s_lo = ((uint64_t)w0 * T + row_off) >> lg;
         const uint64_t lim = (s_lo + kPfTabWindow) << lg;
@@ -435,6 +437,22 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
     }
 
     // lane (j, q) holds O[column j][d = 16 mm + 4q + r] in oacc[b][mm][r] and the column's sum of weights in lacc[b]
+    if (part != kPrefillDirect) { // one stretch of the tile's tokens: accumulators, reference point and sum as they are
+        float *pb = a.partials + (uint64_t)part * kPrefillPartFloats;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (!col_ok[b])
+                continue;
+            const uint32_t col = (wave * NB + b) * 16 + j;
+            float *dst = pb + col * D + 4 * q;
+#pragma unroll
+            for (int mm = 0; mm < MM; ++mm)
+                st_g16(dst + 16 * mm, oacc[b][mm][0], oacc[b][mm][1], oacc[b][mm][2], oacc[b][mm][3]);
+            if (q == 0)
+                st_g8(pb + kPrefillCols * D + col * 2, m[b], lacc[b][0]);
+        }
+        return;
+    }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const float lb = lacc[b][0];
@@ -448,6 +466,64 @@ __global__ void __launch_bounds__(64 * NW, 2) prefill_kernel(PrefillArgs a) {
             st_g16(dst + 16 * mm, oacc[b][mm][0] * inv, oacc[b][mm][1] * inv, oacc[b][mm][2] * inv,
                    oacc[b][mm][3] * inv);
     }
+}
+
+// Merge of the partials of a tile of query rows whose tokens were walked in stretches by several workgroups:
+//   out = sum_c O_c 2^(m_c - M) / sum_c l_c 2^(m_c - M),  M = max_c m_c
+// (a stretch that lies past a column's position left that column at (m, l) = (very negative, 0): weight 0).
+// One workgroup per (tile, block of 16 columns); a thread takes four head_dim elements of one column: first the
+// largest reference point over the parts (the (m, l) pairs are few and stay in cache), then the weighted sums, with the
+// accumulator loads of four parts in flight.
+__global__ void __launch_bounds__(256) prefill_merge_kernel(const PrefillMergeRec *recs, const float *partials,
+                                                            float *out, const uint32_t *bad) {
+    if (bad != nullptr && uni(*reinterpret_cast<const volatile uint32_t *>(bad)) != 0)
+        return;
+    const PrefillMergeRec r = recs[blockIdx.x];
+    const uint32_t D = r.d, G = r.g & 0xffffu, GL = r.g >> 16, rpb = 16 / GL;
+    const uint32_t d4 = D / 4;
+    const float *base = partials + (uint64_t)r.part0 * kPrefillPartFloats;
+    for (uint32_t u = threadIdx.x; u < 16 * d4; u += 256) {
+        const uint32_t j = u / d4, e = (u % d4) * 4, col = blockIdx.y * 16 + j;
+        const uint32_t row = r.r0 + blockIdx.y * rpb + j / GL, head = j % GL;
+        if (row >= r.q_len || head >= G)
+            continue;
+        const float *ml = base + kPrefillCols * D + col * 2;
+        float M = kMinusBig;
+        for (uint32_t c = 0; c < r.n_parts; ++c)
+            M = fmaxf(M, ml[(uint64_t)c * kPrefillPartFloats]);
+        float L = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+        const float *acc = base + col * D + e;
+        for (uint32_t c0 = 0; c0 < r.n_parts; c0 += 4) {
+            uint4 x[4];
+            float w[4], lc[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t c = min(c0 + k, r.n_parts - 1);
+                x[k] = ld_g16(acc + (uint64_t)c * kPrefillPartFloats);
+                const float mc = ml[(uint64_t)c * kPrefillPartFloats];
+                lc[k] = ml[(uint64_t)c * kPrefillPartFloats + 1];
+                w[k] = c0 + k < r.n_parts ? fast_exp2(mc - M) : 0.f;
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                L = fmaf(lc[k], w[k], L);
+                o0 = fmaf(__uint_as_float(x[k].x), w[k], o0);
+                o1 = fmaf(__uint_as_float(x[k].y), w[k], o1);
+                o2 = fmaf(__uint_as_float(x[k].z), w[k], o2);
+                o3 = fmaf(__uint_as_float(x[k].w), w[k], o3);
+            }
+        }
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        st_g16(out + r.out_off + ((uint64_t)row * r.n_q + r.kvh * G + head) * D + e, o0 * inv, o1 * inv, o2 * inv, o3 * inv);
+    }
+}
+
+hipError_t launch_prefill_merge(const PrefillMergeRec *recs, uint32_t n_recs, const float *partials, float *out,
+                                const uint32_t *bad, hipStream_t s) {
+    if (n_recs == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(prefill_merge_kernel, dim3(n_recs, kPrefillCols / 16), dim3(256), 0, s, recs, partials, out, bad);
+    return hipGetLastError();
 }
 
 // The pool's V rows of one chunk of tokens (all kv heads of one request), as fp16, into the workspace: the

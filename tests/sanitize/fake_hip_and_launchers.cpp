@@ -230,6 +230,10 @@ hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_d
             continue; // filler
         if (r.q_len > r.ctx_len || r.r0 >= r.q_len)
             die("prefill record");
+        if (r.t0 >= r.t1 || r.t1 > r.ctx_len || (r.t0 % 32) != 0)
+            die("prefill record: stretch of tokens");
+        if (r.part != kPrefillDirect) // the partial this record leaves: written, so that the sanitizer sees its bounds
+            std::memset(a.partials + (uint64_t)r.part * kPrefillPartFloats, 0, kPrefillPartFloats * sizeof(float));
         if (parts == 1) { // the rows this record reads from the fp16 copy: first and last byte
             const volatile unsigned char *v = a.v16 + r.v16_off;
             (void)v[0];
@@ -239,6 +243,21 @@ hipError_t launch_prefill(const PrefillArgs &a, uint32_t n_recs, uint32_t head_d
         for (uint64_t e = 0; e <= last; ++e)
             if (a.page_table[r.table_off + e] < 0 || (uint64_t)a.page_table[r.table_off + e] >= g_fake.n_pages)
                 die("prefill through a page id out of range");
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_prefill_merge(const PrefillMergeRec *recs, uint32_t n_recs, const float *partials, float *,
+                                const uint32_t *bad, hipStream_t) {
+    if (bad && *bad)
+        return hipSuccess;
+    for (uint32_t i = 0; i < n_recs; ++i) {
+        const PrefillMergeRec &r = recs[i];
+        if (r.n_parts < 2 || r.r0 >= r.q_len || (r.d != 64 && r.d != 128))
+            die("prefill merge record");
+        const volatile float *v = partials + (uint64_t)r.part0 * kPrefillPartFloats;
+        (void)v[0];
+        (void)v[(uint64_t)r.n_parts * kPrefillPartFloats - 1];
     }
     return hipSuccess;
 }

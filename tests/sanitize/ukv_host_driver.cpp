@@ -321,6 +321,50 @@ static void bad_arguments() {
     std::free(base);
 }
 
+// Chunks of long prompts: few tiles of query rows, each with a long walk, which the call cuts into stretches with
+// partial results and a merge list (both forms of the weights, and a workspace without room for the partials).
+static void long_context_chunks() {
+    void *base = std::aligned_alloc(16384, 16384); // never dereferenced: the launchers are stand-ins
+    ukv_service_t sv[2] = {{8, 8, 64, 0.f}, {28, 4, 128, 0.f}};
+    const uint32_t n_pages = 4096;
+    ukv_pool_desc_t d{base, (uint64_t)n_pages * 16384, 16384, 2, sv};
+    ukv_pool_t *pool = nullptr;
+    EXPECT(ukv_pool_create(&d, &pool) == UKV_OK);
+    fake_device_set(n_pages, 14);
+    const uint32_t n = 3;
+    uint32_t sid[n] = {0, 1, 0}, ctx[n] = {6000, 9001, 70}, q_len[n] = {10, 300, 70};
+    std::vector<int32_t> table(n_pages);
+    for (uint32_t i = 0; i < n_pages; ++i)
+        table[i] = (int32_t)(n_pages - 1 - i);
+    uint64_t table_off[n] = {0, 1000, 3500}, q_off[n] = {0, 8192, 1 << 22}, out_off[n] = {0, 8192, 1 << 22};
+    ukv_batch_t b{};
+    b.n_requests = n;
+    b.service_id = sid;
+    b.ctx_len = ctx;
+    b.table_off = table_off;
+    b.page_table = table.data();
+    b.q = base;
+    b.q_off = q_off;
+    b.out = base;
+    b.out_off = out_off;
+    const uint64_t rows = 10 + 300 + 70, toks = 6000 + 9001 + 70;
+    const size_t small = ukv_prefill_workspace_bytes(pool, n, rows);
+    const size_t full = ukv_prefill_workspace_bytes_one_part(pool, n, rows, toks);
+    void *ws = std::aligned_alloc(256, (full + 255) / 256 * 256);
+    int64_t form = 0;
+    for (int64_t w = 0; w <= 2; ++w) {
+        EXPECT(ukv_set_param(pool, UKV_PARAM_PREFILL_WEIGHTS, w) == UKV_OK);
+        EXPECT(ukv_prefill_attention(pool, &b, q_len, ws, full, nullptr) == UKV_OK);
+        EXPECT(ukv_get_param(pool, UKV_PARAM_PREFILL_FORM_USED, &form) == UKV_OK && (w == 0 || form == w));
+        EXPECT(ukv_get_param(pool, UKV_PARAM_PREFILL_PARTIALS_USED, &form) == UKV_OK && form > 8);
+    }
+    EXPECT(ukv_prefill_attention(pool, &b, q_len, ws, small, nullptr) == UKV_OK); // no room: one workgroup per tile
+    EXPECT(ukv_get_param(pool, UKV_PARAM_PREFILL_PARTIALS_USED, &form) == UKV_OK && form == 0);
+    std::free(ws);
+    EXPECT(ukv_pool_destroy(pool) == UKV_OK);
+    std::free(base);
+}
+
 static void scheduler_trace(uint32_t round) {
     void *base = std::aligned_alloc(16384, 16384);
     ukv_service_t sv[3] = {{32, 32, 128, 0.f}, {40, 40, 128, 0.f}, {32, 8, 128, 0.f}};
@@ -374,6 +418,7 @@ static void scheduler_trace(uint32_t round) {
 int main(int argc, char **argv) {
     const int rounds = argc > 1 ? std::atoi(argv[1]) : 40;
     bad_arguments();
+    long_context_chunks();
     for (int r = 0; r < rounds; ++r)
         run_scenario((uint32_t)r);
     for (int r = 0; r < 6; ++r)

@@ -257,15 +257,13 @@ def test_prefill_errors():
             U.ukv_prefill_attention(db.pool, desc, q_len, db.pf_ws_t.data_ptr(), 256, db.stream())
         assert e.value.code == U.UKV_ENOSPC
         # a workspace sized for the two-part form: the default falls back to it, a forced one-part form says so
-        ws2 = U.ukv_prefill_workspace_bytes(db.pool, 2, 40)
-        rec_only = 32 * 64                                                    # what this batch's records take: 32 kv heads, one tile each
-        U.ukv_prefill_attention(db.pool, desc, q_len, db.pf_ws_t.data_ptr(), rec_only, db.stream())
+        ws2 = U.ukv_prefill_workspace_bytes(db.pool, 2, 40)                   # room for the work list, not for a copy of V
+        U.ukv_prefill_attention(db.pool, desc, q_len, db.pf_ws_t.data_ptr(), ws2, db.stream())
         assert _form_used(db) == 2
         U.ukv_set_param(db.pool, U.UKV_PARAM_PREFILL_WEIGHTS, 1)
         with pytest.raises(U.UkvError) as e:
-            U.ukv_prefill_attention(db.pool, desc, q_len, db.pf_ws_t.data_ptr(), rec_only, db.stream())
+            U.ukv_prefill_attention(db.pool, desc, q_len, db.pf_ws_t.data_ptr(), ws2, db.stream())
         assert e.value.code == U.UKV_ENOSPC
-        assert ws2 >= rec_only
         with pytest.raises(U.UkvError) as e:
             U.ukv_set_param(db.pool, U.UKV_PARAM_PREFILL_WEIGHTS, 3)
         assert e.value.code == U.UKV_EINVAL
@@ -364,5 +362,41 @@ def test_one_part_form_saturates_large_v_and_keeps_small_weights():
         say(f"  max relative err, all elements: {rel.max():.3e}; of the 2^-16 and 2^-19 weights: {rel[6:, :, 2:4].max():.3e}")
         assert ref[10, 0, 5] < 2.0 ** -15 and ref[10, 0, 6] < 2.0 ** -18 and ref[10, 0, 6] > 0
         assert rel.max() <= 1e-3
+    finally:
+        db.close()
+
+
+@pytest.mark.parametrize("page_bytes", [16384, 1024])
+def test_chunks_of_long_prompts_are_walked_in_stretches(weights, page_bytes):
+    """Few tiles of query rows with long walks: the call cuts the walks into stretches (partial results, merged by a
+    second launch).  Rows against the oracle; the same call with a workspace that has no room for partials (one
+    workgroup per tile) must agree to rounding."""
+    say(f"prefill: chunks of long prompts, weights in {weights} part(s), pages of {page_bytes}")
+    services = [SHAPES["7b"], SHAPES["70b"], SHAPES["h12"], Service(28, 4, 128)]
+    if page_bytes == 1024:
+        sid, ctx, q_len = np.array([1, 2]), np.array([5000, 3100]), np.array([40, 3])
+    else:
+        sid, ctx, q_len = np.array([0, 1, 2, 3, 1]), np.array([9000, 12001, 4097, 6000, 300]), np.array([130, 17, 1, 64, 300])
+    rng = np.random.default_rng(43)
+    need = sum(-(-int(c) * services[int(s)].token_bytes // page_bytes) for c, s in zip(ctx, sid))
+    b = make_batch(services, sid, ctx, need + 64, "permutation", rng, page_bytes=page_bytes, pool_seed=13)
+    db = _device_batch(b, weights)
+    try:
+        q_bits, q_off, out_off, n_el = draw_prefill_inputs(b, q_len, rng)
+        out_t, _ = db.prefill(q_len, q_bits, q_off, out_off, n_el)
+        n_partials = U.ukv_get_param(db.pool, U.UKV_PARAM_PREFILL_PARTIALS_USED)
+        say(f"  {n_partials} partial results")
+        assert n_partials > 8 and _form_used(db) == weights
+        out = out_t.cpu().numpy().copy()
+        pick = lambda m: np.unique(np.r_[0, 1, m // 2, m - 2, m - 1].clip(0, m - 1))
+        _check_rows(b, out, q_bits, q_len, q_off, out_off, rows_of=pick, tag="walked in stretches", weights=weights)
+        if weights == 2:                                     # the two-part form fits the small workspace: no stretches
+            _, _, desc = db._pf_keep
+            small = U.ukv_prefill_workspace_bytes(db.pool, b.n_requests, int(q_len.sum()))
+            out_t.fill_(float("nan"))
+            U.ukv_prefill_attention(db.pool, desc, np.ascontiguousarray(q_len, np.uint32), db.pf_ws_t.data_ptr(), small, db.stream())
+            assert U.ukv_get_param(db.pool, U.UKV_PARAM_PREFILL_PARTIALS_USED) == 0
+            whole = out_t.cpu().numpy()
+            assert np.max(np.abs(whole - out)) < 2e-5
     finally:
         db.close()
