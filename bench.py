@@ -264,6 +264,55 @@ def main_grid(args):
     print(json.dumps({"metric": "prefill attention on uniform batches of whole prompts: prefill kernel time, 1 GPU",
                       "unit": "us", "steps": max(5, args.steps), "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
 
+    # Chunks of long prompts: q_len rows of n requests against 16384 cached tokens (the chunk's own included), where
+    # few workgroups would each walk the whole context; with the room for partial results in the workspace
+    # ("stretches") and without it (one workgroup per tile of rows).
+    cells = []
+    ctx = 16384
+    for name in ("7b", "70b"):
+        sv = SHAPES[name]
+        row = sv.n_q_heads * sv.head_dim
+        for n, ql in ((1, 128), (1, 512), (1, 2048), (8, 512)):
+            n_pg = -(-ctx * sv.token_bytes // PAGE)
+            n_pages = n * n_pg + 64
+            raw = torch.empty(n_pages * PAGE // 2 + PAGE // 2, dtype=torch.int16, device=dev)
+            skip = (-raw.data_ptr() % PAGE) // 2
+            pool_t = raw[skip:skip + n_pages * PAGE // 2]
+            pool_t.copy_(noise.repeat(-(-pool_t.numel() // noise.numel()))[:pool_t.numel()])
+            table_t = torch.from_numpy(np.random.default_rng(2).permutation(n_pages)[:n * n_pg].astype(np.int32)).to(dev)
+            pool = U.ukv_pool_create(pool_t.data_ptr(), n_pages * PAGE, PAGE, [sv])
+            U.ukv_set_param(pool, U.UKV_PARAM_PROFILE, 1)
+            q_t = noise.repeat(-(-n * ql * row // noise.numel()))[:n * ql * row].contiguous()
+            out_t = torch.empty(n * ql * row, dtype=torch.float32, device=dev)
+            ws_small = U.ukv_prefill_workspace_bytes(pool, n, n * ql)
+            ws_full = U.ukv_prefill_workspace_bytes_one_part(pool, n, n * ql, n * ctx)
+            ws_t = torch.empty(ws_full, dtype=torch.uint8, device=dev)
+            off = (np.arange(n) * ql * row).astype(np.uint64)
+            desc = U.BatchDesc([0] * n, [ctx] * n, (np.arange(n) * n_pg).astype(np.uint64), table_t.data_ptr(),
+                               q_t.data_ptr(), off, out_t.data_ptr(), off)
+            q_len = np.full(n, ql, np.uint32)
+            cell = {"service": f"{sv.n_q_heads}/{sv.n_kv_heads} d={sv.head_dim}", "requests": n, "cached_tokens": ctx, "q_len": ql}
+            for label, ws in (("stretches", ws_full), ("one_workgroup_per_tile", ws_small)):
+                for _ in range(2):
+                    U.ukv_prefill_attention(pool, desc, q_len, ws_t.data_ptr(), ws, stream)
+                torch.cuda.synchronize()
+                U.ukv_profile_read(pool)
+                n_calls = max(30, args.steps)
+                t0 = time.perf_counter()
+                for _ in range(n_calls):
+                    U.ukv_prefill_attention(pool, desc, q_len, ws_t.data_ptr(), ws, stream)
+                torch.cuda.synchronize()
+                call_us = (time.perf_counter() - t0) / n_calls * 1e6
+                pr = U.ukv_profile_read(pool)
+                cell[label] = {"kernel_us": round(1e3 * pr.prefill_ms / pr.n_prefill, 1), "call_us": round(call_us, 1),
+                               "partials": U.ukv_get_param(pool, U.UKV_PARAM_PREFILL_PARTIALS_USED),
+                               "weights_parts": U.ukv_get_param(pool, U.UKV_PARAM_PREFILL_FORM_USED)}
+            cells.append(cell)
+            U.ukv_pool_destroy(pool)
+            del raw, pool_t, q_t, out_t, ws_t
+    print(json.dumps({"metric": "prefill attention on chunks of long prompts: prefill kernel and whole-call time, 1 GPU",
+                      "unit": "us", "steps": max(5, args.steps), "data": "synthetic", "page_bytes": PAGE, "cells": cells}))
+
 
 def main_serve(args):
     """Serving loop over the unified cache driven by the doubling-budget scheduler (section 4.2): requests of

@@ -250,8 +250,9 @@ int ukv_decode_attention_static(ukv_pool_t *pool, const ukv_device_batch_t *batc
  *   +-65504 saturate, elements below 2^-24 in magnitude become 0), which then has to hold
  *   ukv_prefill_workspace_bytes_one_part(pool, n_requests, sum of q_len, sum of ctx_len over the requests
  *   with q_len > 0) bytes.  By default the call takes the one-part form when the workspace is that large and the
- *   batch has at least 2000 flop of attention per byte of that copy (whole prompts of a few hundred tokens and more;
- *   below that the copy costs more than it saves), and the two-part form otherwise.
+ *   batch's attention (in flop) exceeds 35e9 plus 1500 per byte of that copy -- the cost of one more launch and of
+ *   moving the copy, against a quarter of the kernel's time: whole prompts of a thousand tokens and more qualify,
+ *   short chunks over long contexts do not -- and the two-part form otherwise.
  *
  * A workgroup takes 128 / G query rows of one (request, kv head) and walks the tokens they can see.  Where that gives few
  * workgroups with long walks (a chunk of a long prompt), the walks are cut into stretches of 1024 tokens or more, each a

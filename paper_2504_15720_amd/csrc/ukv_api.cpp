@@ -856,7 +856,9 @@ size_t ukv_prefill_workspace_bytes(const ukv_pool_t *p, uint32_t n_requests, uin
 
 // One-part weights: the copy pass takes a request's tokens in chunks of about kV16ChunkBytes of V (all kv heads).
 static constexpr uint64_t kV16ChunkBytes = 64 * 1024; // small enough that a few prompts already give every SIMD several waves
-static constexpr uint64_t kOnePartFlopPerByte = 2000; // below this the copy pass costs more than the products it saves
+// One-part weights pay where a quarter of the kernel's time (its gain) exceeds one more launch with its gap (about
+// 12 us) plus moving the fp16 copy (4 bytes per V element at about 4 TB/s): in flop of attention, at the kernel's rate,
+static constexpr uint64_t kOnePartFlopFixed = 35000000000ull, kOnePartFlopPerByte = 1500;
 static uint32_t v16_chunk_tokens(const ClassRec &c) {
     const uint64_t per_token = (uint64_t)c.n_kv * 2 * c.d;
     return (uint32_t)std::min<uint64_t>(4096, std::max<uint64_t>(8, kV16ChunkBytes / per_token));
@@ -975,7 +977,7 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
             longest_walk = std::max(longest_walk, walk);
         }
     }
-    const int cus = decode_resident_workgroups(256);
+    static const int cus = decode_resident_workgroups(256); // asked once: the query costs as much as a small launch
     const uint64_t places = 2ull * (cus > 0 ? (uint64_t)cus : 256); // two workgroups of this kernel per compute unit
     uint32_t stretch = 0; // 0: every tile is walked by one workgroup
     if (4 * longest_walk > 5 * (total_walk / places) && longest_walk >= 2 * kPrefillMinStretch)
@@ -1083,7 +1085,7 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
             return UKV_ENOSPC;
         }
         parts = 1;
-    } else if (p->tun.prefill_weights == 0 && one_part_total <= ws_bytes && flops >= kOnePartFlopPerByte * v16_bytes) {
+    } else if (p->tun.prefill_weights == 0 && one_part_total <= ws_bytes && flops >= kOnePartFlopFixed + kOnePartFlopPerByte * v16_bytes) {
         parts = 1;
     }
     p->tun.prefill_form_used = parts;
