@@ -62,7 +62,7 @@ extern "C" {
 typedef struct ukv_pool ukv_pool_t; /* opaque host object */
 
 /* One co-located service, reduced to the shape of one attention layer.
- * Supported: head_dim 128 with n_q_heads = G * n_kv_heads, any G from 1 to 16; head_dim 64 with G = 1, 2, 4 or 8
+ * Supported: head_dim 128 or 64 with n_q_heads = G * n_kv_heads, any G from 1 to 16
  * (the workloads' shapes -- G = 1, 4, 8 at head_dim 128, G = 1 at 64 -- are the ones the kernels are tuned for).
  * scale == 0 selects 1/sqrt(head_dim). */
 typedef struct {

@@ -163,8 +163,8 @@ __device__ __forceinline__ float2 ld_part2(const float *p) {
 // that every 64-bit store instruction of a wave covers contiguous memory (whole 128-byte lines):
 //   layout_g == 0 (ALU path): per query head D floats; lane lir of the row group holds columns
 //     8*lir + 2k + {0,1} and stores pair k at  hq*D + k*(D/4) + 2*lir.
-//   layout_g == G (matrix-core path): per kv head G*128 floats; lane (j, q) holds columns
-//     32q + 8r + 2pp + {0,1} of head j and stores pair (r, pp) at  hh*G*128 + ((4r+pp)*4G + q*G + j)*2.
+//   layout_g == G (matrix-core path): per kv head G*D floats; lane (j, q), q < D/32, holds columns
+//     32q + 8r + 2pp + {0,1} of head j and stores pair (r, pp) at  hh*G*D + ((4r+pp)*(D/32)*G + q*G + j)*2.
 // Returns the float offset of the pair holding columns 4*c4 + 2h, 4*c4 + 2h + 1 of query head hq.
 __device__ __forceinline__ uint32_t part_pair_off(uint32_t layout_g, uint32_t D, uint32_t hq, uint32_t c4,
                                                   uint32_t h) {
@@ -174,7 +174,7 @@ __device__ __forceinline__ uint32_t part_pair_off(uint32_t layout_g, uint32_t D,
     }
     const uint32_t G = layout_g, hh = hq / G, j = hq % G;
     const uint32_t q = c4 >> 3, r = (c4 & 7) >> 1, pp = ((c4 & 1) << 1) + h;
-    return hh * (G * 128) + (((r << 2) + pp) * (4 * G) + q * G + j) * 2;
+    return hh * (G * D) + (((r << 2) + pp) * ((D >> 5) * G) + q * G + j) * 2;
 }
 
 // The inverse: float e of a partial's accumulators, in memory order, is column `col` of query head `head` (of
@@ -187,8 +187,8 @@ __device__ __forceinline__ AccElem acc_elem(uint32_t layout_g, uint32_t D, uint3
         const uint32_t q4 = D >> 2, o = e % D, k = o / q4, rem = o % q4;
         return AccElem{e / D, 8 * (rem >> 1) + 2 * k + (rem & 1)};
     }
-    const uint32_t G = layout_g, hh = e / (G * 128), t = (e % (G * 128)) >> 1;
-    const uint32_t j = t % G, t2 = t / G, q = t2 & 3, t3 = t2 >> 2;
+    const uint32_t G = layout_g, hh = e / (G * D), t = (e % (G * D)) >> 1, nq = D >> 5;
+    const uint32_t j = t % G, t2 = t / G, q = t2 % nq, t3 = t2 / nq;
     return AccElem{hh * G + j, 32 * q + 8 * (t3 >> 2) + 2 * (t3 & 3) + (e & 1)};
 }
 
@@ -368,7 +368,7 @@ __device__ __forceinline__ void process_item(const StepPages &sp) {
     float *mbuf = s_mbuf;
     constexpr int LPR = D / 8;   // lanes per row
     constexpr int NG = NT / LPR; // row groups in the workgroup
-    constexpr int U = G >= 8 ? 1 : G >= 4 ? 2 : 4; // tokens per lane and round trip: what the registers hold next to G accumulator rows
+    constexpr int U = 4;
     const int tid = threadIdx.x;
     const int lir = tid % LPR, grp = tid / LPR;
     const uint32_t HS = c.hs, TI = c.ti;
@@ -553,8 +553,10 @@ __device__ __forceinline__ void process_item(const StepPages &sp) {
 
 
 // ---------------------------------------------------------------------------------------------
-// Grouped-query path (head_dim 128, G = 2 .. 16 query heads per kv head: whatever fits the 16 columns of a
-// product) on the matrix cores.
+// Grouped-query path (head_dim D = 128, or 64 for groups of three and more; G = 2 .. 16 query heads per kv head:
+// whatever fits the 16 columns of a product) on the matrix cores.  (The text below is written for D = 128; at D = 64 a
+// K row is two 64-byte steps instead of four, a V row 8 chunks instead of 16 -- lanes j >= 8 fetch chunk j - 8 again and
+// their output rows d = 8i + m >= 64, held by the lanes q >= 2, are never stored.)
 //
 // With G query heads sharing one kv head the path does G flop per KV byte and the plain-ALU
 // formulation above becomes ALU-bound.  Here one wave owns one kv head and walks the item's
@@ -569,7 +571,7 @@ __device__ __forceinline__ void process_item(const StepPages &sp) {
 // (MFMA m, lane i) is d = 8i + m.  P is split into bf16 high and low parts (two products), so the
 // weights keep 16 mantissa bits: a single bf16 P would cost up to ~1e-2 absolute error.
 
-template <int NT>
+template <int NT, int D>
 __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
     const DecodeArgs a = ctx_args();
     const SeqRec s = ctx_seq();
@@ -577,7 +579,8 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
     const Item it = ctx_item();
     int32_t *tab = s_tab;
     float *mbuf = s_mbuf;
-    constexpr int D = 128;
+    constexpr int KS = D / 32;  // products of 32 along head_dim for one score tile
+    constexpr int VCH = D / 8;  // 16-byte chunks of a V row
     const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t wave = uni((uint32_t)(tid >> 6));
     const uint32_t HS = c.hs, G = c.g;
@@ -587,12 +590,13 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
     const uint32_t lg = a.log2_page;
     const uint64_t page_mask = (1ull << lg) - 1;
 
-    bf16x8_t qB[4];
+    const uint32_t jv = j % VCH; // the V chunk this lane fetches
+    bf16x8_t qB[KS];
     {
         const uint4 *qp = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.q) + s.q_off +
                                                           (uint64_t)(kvh * G + (j < G ? j : 0)) * D) + q;
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
+        for (int st = 0; st < KS; ++st) {
             uint4 w = ld_g16(qp + st * 4);
             if (j >= G)
                 w = make_uint4(0, 0, 0, 0);
@@ -615,7 +619,7 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
     uint64_t new_lo;
     uint32_t new_n, new_first;
     step_entries(appends, sp, s, T, lg, new_lo, new_n, new_first);
-    u32x4 nK[4], nV; // the new token's K and V pieces of this lane (fused append)
+    u32x4 nK[KS], nV; // the new token's K and V pieces of this lane (fused append)
     unsigned char *new_dst = nullptr;
     uint32_t w0 = it.t0;
     while (w0 < it.t1) { // workgroup-uniform: one pass per page-table window
@@ -633,9 +637,9 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
             new_token_rows(kvh, D, nk16, nv16);
             const unsigned char *nk = reinterpret_cast<const unsigned char *>(nk16) + q * 16;
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
+            for (int st = 0; st < KS; ++st)
                 nK[st] = ld_g16v(nk + st * 64);
-            nV = ld_g16v(reinterpret_cast<const unsigned char *>(nv16) + j * 16);
+            nV = ld_g16v(reinterpret_cast<const unsigned char *>(nv16) + jv * 16);
         }
         if (w0 != it.t0)
             __syncthreads(); // later windows only: see process_item
@@ -656,28 +660,28 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
             // 8 tokens tau(q, e) -> vr[e].  Tokens past the range are clamped to its last token (and
             // masked in the scores of the range's last tile).
             auto tau = [&](uint32_t tb, int e) { return tb + (e < 4 ? 4 * q + e : 16 + 4 * q + (e - 4)); };
-            auto load_k = [&](uint32_t tb, u32x4 (&kA)[8]) {
+            auto load_k = [&](uint32_t tb, u32x4 (&kA)[2 * KS]) {
                 const unsigned char *p0 = row_ptr(min(tb + j, last)) + q * 16;
                 const unsigned char *p1 = row_ptr(min(tb + 16 + j, last)) + q * 16;
 #pragma unroll
-                for (int st = 0; st < 4; ++st) {
+                for (int st = 0; st < KS; ++st) {
                     kA[st] = ld_kv4(p0 + st * 64);
-                    kA[4 + st] = ld_kv4(p1 + st * 64);
+                    kA[KS + st] = ld_kv4(p1 + st * 64);
                 }
             };
             auto load_v = [&](uint32_t tb, u32x4 (&vr)[8]) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    vr[e] = ld_kv4(row_ptr(min(tau(tb, e), last)) + 2 * D + j * 16);
+                    vr[e] = ld_kv4(row_ptr(min(tau(tb, e), last)) + 2 * D + jv * 16);
             };
             // raw scores q . K of the tile: s0 = tokens tb + 4q + r, s1 = tokens tb + 16 + 4q + r
-            auto scores = [&](const u32x4 (&kA)[8], f32x4_t &s0, f32x4_t &s1) {
+            auto scores = [&](const u32x4 (&kA)[2 * KS], f32x4_t &s0, f32x4_t &s1) {
                 s0 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
                 s1 = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int st = 0; st < 4; ++st) {
+                for (int st = 0; st < KS; ++st) {
                     s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[st]), qB[st], s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[4 + st]), qB[st], s1, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[KS + st]), qB[st], s1, 0, 0, 0);
                 }
             };
             // Online softmax of the tile's scores and O^T += V^T P^T.  MASKED: only tokens below t_lim
@@ -744,11 +748,11 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
                 // The new token as a tile of its own: every row of the tile is that token (all but
                 // the first masked).  It goes into the pool once the item's loads are done.
                 new_dst = const_cast<unsigned char *>(row_ptr(it.t1 - 1));
-                u32x4 kA[8], vr[8];
+                u32x4 kA[2 * KS], vr[8];
 #pragma unroll
-                for (int st = 0; st < 4; ++st) {
+                for (int st = 0; st < KS; ++st) {
                     kA[st] = nK[st];
-                    kA[4 + st] = nK[st];
+                    kA[KS + st] = nK[st];
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -763,7 +767,7 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
                 // first, its V loads right after the second, so one of the two is always in flight
                 // behind the arithmetic without a second set of registers.  All tiles but the last are
                 // whole, so only the last one takes the masked path.
-                u32x4 kA[8], vr[8];
+                u32x4 kA[2 * KS], vr[8];
                 load_k(w0, kA);
                 load_v(w0, vr);
                 uint32_t tb = w0;
@@ -786,7 +790,7 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const bool direct = it.part == kDirect;
-    if (live && j < G) {
+    if (live && j < G && q < (uint32_t)KS) { // (at head_dim 64 the lanes q >= 2 hold rows past the head's end)
         if (direct) {
             const float inv = l > 0.f ? 1.f / l : 0.f;
             float *dst = a.out + s.out_off + (uint64_t)(kvh * G + j) * D + 32 * q;
@@ -803,18 +807,18 @@ __device__ __forceinline__ void process_item_gqa(const StepPages &sp) {
             for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int pp = 0; pp < 4; ++pp)
-                    st_part2(dst + (r * 4 + pp) * (8 * G), oacc[2 * pp][r], oacc[2 * pp + 1][r]);
+                    st_part2(dst + (r * 4 + pp) * (2 * KS * G), oacc[2 * pp][r], oacc[2 * pp + 1][r]);
             if (q == 0)
                 st_part2(pbase + (uint64_t)HS * G * D + hq * 2, m, l);
         }
     }
-    if (new_dst != nullptr) { // K: 16 pieces over lanes (j = 0, q) x 4; V: 16 pieces over lanes (j, q = 0)
+    if (new_dst != nullptr) { // K: D/8 pieces over lanes (j = 0, q) x D/32; V: D/8 pieces over lanes (j < D/8, q = 0)
         if (j == 0) {
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
+            for (int st = 0; st < KS; ++st)
                 st_g16v(new_dst + q * 16 + st * 64, nK[st]);
         }
-        if (q == 0)
+        if (q == 0 && j < (uint32_t)VCH)
             st_g16v(new_dst + 2 * D + j * 16, nV);
     }
     finish_item<NT>(a, s, it, HS * G, D, s.head0 * G, G, tab, mbuf);
@@ -887,11 +891,9 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const StepPages
             else if ((KINDS & (1u << kD128G1)) && kind == kD128G1)
                 process_item<128, 1, NT>(sp);
             else if ((KINDS & (1u << kD128GQA)) && kind == kD128GQA)
-                process_item_gqa<NT>(sp);
-            else if ((KINDS & (1u << kD64G4)) && kind == kD64G4)
-                process_item<64, 4, NT>(sp);
-            else if ((KINDS & (1u << kD64G8)) && kind == kD64G8)
-                process_item<64, 8, NT>(sp);
+                process_item_gqa<NT, 128>(sp);
+            else if ((KINDS & (1u << kD64GQA)) && kind == kD64GQA)
+                process_item_gqa<NT, 64>(sp);
             rec = rec_next;
         }
         __syncthreads(); // every wave has read the previous s_span
@@ -923,11 +925,11 @@ __global__ void __launch_bounds__(64) reduce_few_kernel(const ReduceRec *recs, c
         return;
     const ReduceRec r = recs[blockIdx.x];
     const uint32_t gx = r.layout_g ? r.layout_g : 1;             // query heads per unit
-    const uint32_t unit = blockIdx.y, unit_floats = gx * r.d;     // (the matrix-core path has d = 128)
+    const uint32_t unit = blockIdx.y, unit_floats = gx * r.d;
     if (unit >= r.n_heads / gx)
         return;
     const uint32_t lane = threadIdx.x;
-    const uint32_t ni = unit_floats / 64;                         // elements per lane: 1, 2 or 2G <= 16
+    const uint32_t ni = unit_floats / 64;                         // elements per lane: 1, 2 or G d / 64 <= 16 (reduce_few_takes)
     const uint32_t data_off = unit * unit_floats + lane;          // this lane's first float of every part
     const uint32_t head = acc_elem(r.layout_g, r.d, data_off).head; // its query head, the same for all its floats
     const float *base = partials + r.part_off;

@@ -48,9 +48,9 @@ __host__ __device__ inline bool merges_in_launch(uint32_t n_parts, uint32_t part
 // after part, and longer ones with four waves that share the parts.
 static constexpr uint32_t kReduceFewParts = 24;
 // reduce_few_kernel gives a lane 64-float strides of one partial and one query head's (m, l): in the matrix-core layout
-// that needs the group size to divide 32 and 2 G <= 16 elements per lane.  Other group sizes go to reduce_many_kernel.
-__host__ __device__ inline bool reduce_few_takes(uint32_t layout_g) {
-    return layout_g == 0 || layout_g == 2 || layout_g == 4 || layout_g == 8;
+// that needs the group size to divide 32 and G d / 64 <= 16 elements per lane.  Other shapes go to reduce_many_kernel.
+__host__ __device__ inline bool reduce_few_takes(uint32_t layout_g, uint32_t d) {
+    return layout_g == 0 || (32 % layout_g == 0 && layout_g * d <= 16 * 64);
 }
 
 // Per-service constants used by the kernels.
@@ -76,10 +76,11 @@ struct ItemRec {
 static_assert(sizeof(ItemRec) == 128 && offsetof(ItemRec, it.t1) == 8 && offsetof(ItemRec, s.ctx_len) == 56,
               "ItemRec layout (the kernel patches t1 and ctx_len by position)");
 
-// kD64G4 / kD64G8: grouped queries at head_dim 64 on the plain path (there is no matrix-core path at this head_dim);
-// arithmetic-bound, kept out of the kernels that the workloads' pools use (kWorkloadKinds).
-enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kD64G4, kD64G8, kNumKinds };
+// kD64GQA: groups of 3 to 16 query heads at head_dim 64, on the matrix-core path like kD128GQA; not a shape of the
+// workloads, and kept out of the kernels that their pools use (kWorkloadKinds).
+enum Kind : uint32_t { kD64G1, kD64G2, kD128G1, kD128GQA, kD64GQA, kNumKinds };
 static constexpr uint32_t kWorkloadKinds = (1u << kD64G1) | (1u << kD64G2) | (1u << kD128G1) | (1u << kD128GQA);
+__host__ __device__ inline bool kind_is_gqa(uint32_t kind) { return kind == kD128GQA || kind == kD64GQA; }
 static constexpr uint32_t kAllKinds = (1u << kNumKinds) - 1;
 
 // floats of one split partial of a (request, head-slice) sequence: accumulators and (m, l) pairs of its query heads,

@@ -45,7 +45,7 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
     // planner cost of one token of one head-slice: its KV bytes, weighted by the kernel kind
     auto token_cost = [&](const ClassRec &c) {
         const uint64_t bytes = (uint64_t)c.hs * c.row_bytes;
-        return c.kind == kD128GQA ? bytes * (uint64_t)p->tun.gqa_cost_pct / 100 : bytes;
+        return kind_is_gqa(c.kind) ? bytes * (uint64_t)p->tun.gqa_cost_pct / 100 : bytes;
     };
     uint64_t total_cost = 0;
     for (uint32_t i = 0; i < n; ++i) {
@@ -228,14 +228,14 @@ int build_plan(const ukv_pool *p, const ukv_batch_t *b, Plan &plan) {
         r.part_stride = s.part_stride;
         r.n_heads = c.hs * c.g;
         r.d = c.d;
-        r.layout_g = c.kind == kD128GQA ? c.g : 0;
+        r.layout_g = kind_is_gqa(c.kind) ? c.g : 0;
         plan.reduce.push_back(r);
         plan.max_reduce_heads = std::max(plan.max_reduce_heads, r.n_heads);
         plan.max_reduce_units = std::max(plan.max_reduce_units, r.layout_g ? r.n_heads / r.layout_g : r.n_heads);
     }
     const auto many = std::stable_partition(plan.reduce.begin(), plan.reduce.end(),
                                             [](const ReduceRec &r) {
-                                                return r.n_parts > kReduceFewParts || !reduce_few_takes(r.layout_g);
+                                                return r.n_parts > kReduceFewParts || !reduce_few_takes(r.layout_g, r.d);
                                             });
     plan.n_reduce_many = (uint32_t)(many - plan.reduce.begin());
     return UKV_OK;

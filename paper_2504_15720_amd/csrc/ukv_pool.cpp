@@ -68,12 +68,12 @@ int derive_classes(ukv_pool *p) {
         c.scale_log2e = (float)(scale * 1.4426950408889634);
         if (c.d == 128 && c.g >= 1 && c.g <= 16) // the matrix-core path pads a group to the 16 columns of a product
             c.kind = c.g == 1 ? kD128G1 : kD128GQA;
-        else if (c.d == 64 && (c.g == 1 || c.g == 2 || c.g == 4 || c.g == 8))
-            c.kind = c.g == 1 ? kD64G1 : c.g == 2 ? kD64G2 : c.g == 4 ? kD64G4 : kD64G8;
+        else if (c.d == 64 && c.g >= 1 && c.g <= 16)
+            c.kind = c.g == 1 ? kD64G1 : c.g == 2 ? kD64G2 : kD64GQA;
         else
-            return fail(UKV_EINVAL, "unsupported shape: head_dim 128 with group 1..16, or head_dim 64 with group 1/2/4/8");
+            return fail(UKV_EINVAL, "unsupported shape: head_dim 128 or 64 with groups of 1 to 16 query heads");
         p->kinds |= 1u << c.kind;
-        if (c.kind == kD128GQA) {
+        if (kind_is_gqa(c.kind)) {
             // matrix-core path: one wave per kv head of the slice, all waves on the same tokens
             const uint32_t waves = (uint32_t)p->tun.block_threads / 64;
             uint32_t hs = 1;
@@ -136,7 +136,7 @@ int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out) {
         // measured faster than inside the decode launch (2 % of the step on the GQA workload).
         bool all_gqa = true;
         for (uint32_t s = 0; s < p->n_services; ++s)
-            all_gqa = all_gqa && p->classes.c[s].kind == kD128GQA;
+            all_gqa = all_gqa && p->classes.c[s].kind == kD128GQA; // (the measured default: pools of the workloads' GQA shape)
         if (all_gqa) {
             p->tun.block_threads = 256;
             p->tun.fused_merge = 0;

@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
 
     auto token_cost = [&](const ClassRec &c) -> uint64_t {
         const uint64_t bytes = (uint64_t)c.hs * c.row_bytes;
-        return c.kind == kD128GQA ? bytes * a.gqa_cost_pct / 100 : bytes;
+        return kind_is_gqa(c.kind) ? bytes * a.gqa_cost_pct / 100 : bytes;
     };
 
     // sequences of request `tid`: one per head-slice; a request with a service id outside the pool has none
@@ -171,7 +171,7 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
         if (np > 1) {
             floats_mine += (uint64_t)np * seqs[k].part_stride;
             const ClassRec &c = a.classes.c[seqs[k].cls];
-            if (np > kReduceFewParts || !reduce_few_takes(c.kind == kD128GQA ? c.g : 0))
+            if (np > kReduceFewParts || !reduce_few_takes(kind_is_gqa(c.kind) ? c.g : 0, c.d))
                 ++many_mine;
             else
                 ++few_mine;
@@ -197,8 +197,8 @@ __global__ void __launch_bounds__(kPlanThreads) static_plan_kernel(StaticPlanArg
         r.part_stride = s.part_stride;
         r.n_heads = c.hs * c.g;
         r.d = c.d;
-        r.layout_g = c.kind == kD128GQA ? c.g : 0;
-        if (np > kReduceFewParts || !reduce_few_takes(r.layout_g))
+        r.layout_g = kind_is_gqa(c.kind) ? c.g : 0;
+        if (np > kReduceFewParts || !reduce_few_takes(r.layout_g, r.d))
             many[m_run++] = r;
         else
             few[w_run++] = r;
@@ -318,8 +318,8 @@ extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch
         max_sl = std::max(max_sl, c.n_kv / c.hs);
         max_stride = std::max(max_stride, part_stride_of(c));
         max_heads = std::max(max_heads, c.hs * c.g);
-        max_units = std::max(max_units, c.kind == kD128GQA ? c.hs : c.hs * c.g);
-        all_few = all_few && reduce_few_takes(c.kind == kD128GQA ? c.g : 0);
+        max_units = std::max(max_units, kind_is_gqa(c.kind) ? c.hs : c.hs * c.g);
+        all_few = all_few && reduce_few_takes(kind_is_gqa(c.kind) ? c.g : 0, c.d);
     }
     if (n > kStaticMaxRequests || (uint64_t)n * max_sl > kStaticMaxSeqs) {
         set_error("batch too large for the static scratch array: at most " + std::to_string(kStaticMaxRequests) +

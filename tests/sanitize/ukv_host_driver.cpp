@@ -258,8 +258,8 @@ static void bad_arguments() {
     ukv_service_t g17{68, 4, 128, 0.f}; // more query heads per kv head than a product has columns
     bad = d, bad.services = &g17;
     EXPECT(ukv_pool_create(&bad, &pool) == UKV_EINVAL);
-    ukv_service_t g3d64{24, 8, 64, 0.f}; // at head_dim 64 only groups of 1, 2, 4, 8
-    bad = d, bad.services = &g3d64;
+    ukv_service_t g17d64{34, 2, 64, 0.f}; // the same at head_dim 64
+    bad = d, bad.services = &g17d64;
     EXPECT(ukv_pool_create(&bad, &pool) == UKV_EINVAL);
     EXPECT(ukv_pool_create(&d, &pool) == UKV_OK);
     fake_device_set(64, 14);

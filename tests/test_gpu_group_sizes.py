@@ -1,6 +1,6 @@
 """Query groups that are not a power of two (and the largest one, 16) at head_dim 128 -- 24/8, 40/8, 12/2, 28/4, 48/4
-and 32/2 heads -- and groups of 4 and 8 at head_dim 64 (32/8 and 32/4 heads: the plain path, there is no matrix-core
-path at that head_dim) through every call that takes a service: decode attention whole and cut (merge inside the launch,
+and 32/2 heads -- and groups of 3 and more at head_dim 64 (24/8, 32/8, 14/2, 32/4 and 32/2 heads: the matrix-core path
+at half the row width) through every call that takes a service: decode attention whole and cut (merge inside the launch,
 as a second launch with the many-parts kernel these group sizes are sent to), decode steps, a kept plan, the entry
 point that allocates nothing, and prefill attention in both forms of the weights; all against the CPU oracle."""
 import numpy as np
@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 
 GROUPS = [Service(24, 8, 128), Service(40, 8, 128), Service(12, 2, 128), Service(28, 4, 128), Service(48, 4, 128),
           Service(32, 2, 128),                                        # G = 3, 5, 6, 7, 12, 16
-          Service(32, 8, 64), Service(32, 4, 64)]                     # G = 4, 8 at head_dim 64
+          Service(32, 8, 64), Service(32, 4, 64),                     # G = 4, 8 at head_dim 64
+          Service(24, 8, 64), Service(14, 2, 64), Service(32, 2, 64)]  # G = 3, 7, 16 at head_dim 64
 
 
 def _batch(rng, page_bytes=16384, with_others=True, reserve=12):
@@ -64,7 +65,7 @@ def test_small_pages_and_one_long_request_in_many_parts():
         _check_attention(db, b, "1 KiB pages, many cuts")
     finally:
         db.close()
-    for sv in (GROUPS[3], GROUPS[5], GROUPS[7]):                       # G = 7 and 16, and 8 at head_dim 64: one request alone on the device
+    for sv in (GROUPS[3], GROUPS[5], GROUPS[7], GROUPS[9]):            # G = 7 and 16, and 8 and 7 at head_dim 64: one request alone on the device
         b = make_batch([sv], np.array([0]), np.array([30000]), 30000 * sv.token_bytes // 16384 + 64, "permutation", rng,
                        pool_seed=22)
         db = DeviceBatch(b)
@@ -92,9 +93,9 @@ def test_entry_point_that_allocates_nothing():
 def test_prefill(weights):
     rng = np.random.default_rng(66)
     services = GROUPS + [SHAPES["8b"]]
-    sid = np.array([0, 1, 2, 3, 4, 5, 6, 3, 0, 7, 8, 6])
-    ctx = np.array([130, 257, 96, 700, 33, 300, 64, 1, 1500, 200, 64, 513])
-    q_len = np.array([130, 100, 96, 700, 33, 1, 64, 1, 300, 200, 17, 513])
+    sid = np.array([0, 1, 2, 3, 4, 5, 6, 3, 0, 7, 11, 6, 8, 9, 10])
+    ctx = np.array([130, 257, 96, 700, 33, 300, 64, 1, 1500, 200, 64, 513, 300, 129, 77])
+    q_len = np.array([130, 100, 96, 700, 33, 1, 64, 1, 300, 200, 17, 513, 300, 100, 77])
     b = make_batch(services, sid, ctx, 8192, "permutation", rng, pool_seed=23)
     db = DeviceBatch(b)
     try:

@@ -54,7 +54,7 @@ def test_pool_info_matches_the_paper_closed_form():
     (dict(), [Service(32, 32, 96)]),            # unsupported head_dim
     (dict(), [Service(30, 4, 128)]),            # q heads not a multiple of kv heads
     (dict(), [Service(34, 2, 128)]),            # group 17: more query heads than a product has columns
-    (dict(), [Service(24, 8, 64)]),             # group 3 at head_dim 64 (no matrix-core path there)
+    (dict(), [Service(34, 2, 64)]),             # the same at head_dim 64
     (dict(), []),
     (dict(n_pages=0), [SHAPES["7b"]]),
 ])
