@@ -398,7 +398,8 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
     a.queue_base = 0; // the upload has just zeroed the counter
     a.n_spans = n_spans;
     a.n_spans_dev = nullptr;
-    const uint32_t grid = decode_grid(n_spans, (uint32_t)p->tun.block_threads, p->kinds);
+    const uint32_t grid = decode_grid(n_spans, (uint32_t)p->tun.block_threads, p->kinds,
+                                      p->tun.grid_is_first_round ? (uint32_t)p->tun.slots : 0);
     if (keep) {
         keep->args = a;
         keep->grid = grid;

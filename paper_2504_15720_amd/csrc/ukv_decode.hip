@@ -1117,8 +1117,12 @@ static DecodeKernelFn decode_kernel_fn(int set, bool big) {
 }
 
 // Workgroups of a launch: as many as the device keeps resident of this instantiation (compute units x workgroups
-// per unit), so that none waits for a place; each takes spans from the queue until it is empty.
-uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds) {
+// per unit), so that none waits for a place; each takes spans from the queue until it is empty.  `first_round` (0 =
+// no such limit): a plan with more spans than places gets at most this many workgroups -- the spans of the planner's
+// first round.  Workgroups beyond those would start with the small spans of the later rounds and use them up in the
+// launch's first quarter, when nothing needs evening out; at the end, where the first round's spans finish 5-8 %
+// apart, the queue would be empty.
+uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds, uint32_t first_round) {
     static int places[2][kNumKindSets]; // per device kind this would differ; all devices of a process are alike
     const int set = kind_set_of(kinds);
     const bool big = block_threads == 512;
@@ -1135,7 +1139,9 @@ uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds) {
             cached = -1;
     }
     const uint32_t cap = cached > 0 ? (uint32_t)cached : 256u;
-    return n_spans < cap ? n_spans : cap;
+    if (n_spans <= cap)
+        return n_spans; // every span has a workgroup of its own from the start
+    return first_round != 0 && first_round < cap ? first_round : cap;
 }
 
 // grid: decode_grid() of the plan's spans.  sp: the step's new page ids for the kernel arguments, or null.

@@ -255,7 +255,7 @@ struct GatherRec { // tokens [t0, t1) of one request
 // ---- kernel launchers (ukv_decode.hip, ukv_prefill.hip, ukv_copy.hip) ----
 int decode_resident_workgroups(uint32_t block_threads); // spans of the planner's first round: one per compute unit; 0 on failure
 // workgroups to launch for n_spans spans: one per place the device offers the kernel instantiation, at most n_spans
-uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds);
+uint32_t decode_grid(uint32_t n_spans, uint32_t block_threads, uint32_t kinds, uint32_t first_round);
 hipError_t launch_stage_copy(void *dst, const void *src_mapped, size_t bytes, int32_t *page_table,
                              const uint64_t *patch_entry, const int32_t *patch_page, uint32_t n_patches,
                              hipStream_t s);
@@ -319,6 +319,7 @@ struct Tunables {
     int64_t prefill_partials_used = 0;
     int64_t replan_every = 64; // a kept plan is remade after its requests have grown by this many tokens
     bool slots_auto = true;
+    bool grid_is_first_round = false; // launches of more spans than the device holds get `slots` workgroups (decode_grid)
 };
 
 void set_error(const std::string &msg);

@@ -131,15 +131,20 @@ int ukv_pool_create(const ukv_pool_desc_t *desc, ukv_pool_t **out) {
     int rc = derive_classes(p);
     if (rc == UKV_OK) {
         // A pool whose services all run on the matrix-core path does better with four waves (four
-        // kv heads) per workgroup: smaller partials and twice the workgroups in flight.  Its partials
+        // kv heads) per workgroup: smaller partials.  Its partials
         // are G times larger than those of the other kinds, and merging them in a second launch was
-        // measured faster than inside the decode launch (2 % of the step on the GQA workload).
+        // measured faster than inside the decode launch (2 % of the step on the GQA workload).  Two such
+        // workgroups fit a compute unit, but one streams as fast as two, and a second one only uses up the later
+        // rounds' small spans at the start of the launch: one workgroup per first-round span, and a larger
+        // first round (94 % of the work: with single-kind batches the later rounds have less to even out).
         bool all_gqa = true;
         for (uint32_t s = 0; s < p->n_services; ++s)
             all_gqa = all_gqa && p->classes.c[s].kind == kD128GQA; // (the measured default: pools of the workloads' GQA shape)
         if (all_gqa) {
             p->tun.block_threads = 256;
             p->tun.fused_merge = 0;
+            p->tun.grid_is_first_round = true;
+            p->tun.taper = 94;
             rc = derive_classes(p);
         }
     }

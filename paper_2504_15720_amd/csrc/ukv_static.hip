@@ -382,7 +382,8 @@ extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch
     a.queue_base = 0;
     a.n_spans = kStaticMaxSpans;
     a.n_spans_dev = (const uint32_t *)(sp + kOffCounts) + 3; // what the plan kernel made of the batch
-    e = launch_decode(a, nullptr, decode_grid(kStaticMaxSpans, (uint32_t)p->tun.block_threads, p->kinds),
+    // (every place of the device: this plan's spans are all of one small size, there is no first round)
+    e = launch_decode(a, nullptr, decode_grid(kStaticMaxSpans, (uint32_t)p->tun.block_threads, p->kinds, 0),
                       (uint32_t)p->tun.block_threads, p->kinds, s, nullptr, nullptr);
     if (e != hipSuccess) {
         set_error(std::string("launch decode kernel: ") + hipGetErrorString(e));

@@ -70,7 +70,7 @@ static void die(const char *what) {
 namespace ukv {
 
 int decode_resident_workgroups(uint32_t) { return 256; }
-uint32_t decode_grid(uint32_t n_spans, uint32_t, uint32_t) { return n_spans < 256 ? n_spans : 256; }
+uint32_t decode_grid(uint32_t n_spans, uint32_t, uint32_t, uint32_t) { return n_spans < 256 ? n_spans : 256; }
 
 hipError_t launch_stage_copy(void *dst, const void *src, size_t bytes, int32_t *page_table, const uint64_t *pe,
                              const int32_t *pp, uint32_t n_patches, hipStream_t) {
