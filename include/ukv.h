@@ -342,7 +342,8 @@ int ukv_plan_decode(const ukv_pool_t *pool, const ukv_batch_t *batch, ukv_plan_i
 #define UKV_PARAM_PREFILL_PARTIALS_USED 16 /* read only: partial results the pool's last ukv_prefill_attention call made
                                         (0 = every tile of query rows was walked by one workgroup) */
 #define UKV_PARAM_TAPER 8            /* 0 = equal spans; else spans shrink batch by batch, each batch of resident
-                                        workgroups taking this percentage (5..95) of what is left; 1 = default (88) */
+                                        workgroups taking this percentage (5..95) of what is left; 1 = 88; default 1, and
+                                        94 for pools whose services all have d = 128 and g > 1 */
 int ukv_set_param(ukv_pool_t *pool, int key, int64_t value);
 int ukv_get_param(const ukv_pool_t *pool, int key, int64_t *value);
 

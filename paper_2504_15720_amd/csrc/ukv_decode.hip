@@ -1073,9 +1073,8 @@ __global__ void __launch_bounds__(64 * kReduceWaves) reduce_many_kernel(const Re
 
 // ------------------------------------------------------------------ launchers
 // How many spans the planner makes its first (largest) round of: one per compute unit.  Where two workgroups
-// fit a CU (the 256-lane kernel at 256 registers or fewer), a first round of two spans per CU was measured 2 %
-// slower on the grouped-query workload: twice the cuts, partials and merges; the second position of a CU then
-// picks up the later, smaller spans.
+// fit a CU (the 256-lane kernel at 256 registers or fewer), a first round of two spans per CU was measured 2-3 %
+// slower on the grouped-query workload: twice the cuts, partials and merges, and no higher a rate while they stream.
 int decode_resident_workgroups(uint32_t block_threads) {
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
