@@ -32,6 +32,10 @@
  *   - The library never allocates or frees the pool memory itself.  It owns its host
  *     object, the free list and pinned, device-mapped staging buffers (per-call records); with
  *     UKV_PARAM_VALIDATE also one 256-byte device allocation per pool.
+ *   - UKV_TRACE=1 in the environment: every compute call leaves one line on stderr when it returns,
+ *     "ukv_trace call=<entry point> t_us=<host time since the first traced call> host_us=<time in the call>
+ *     status=ok|error" followed by the call's work-list figures as key=value (requests, kv_bytes, sequences,
+ *     items, spans, workgroups, ...).  Host time only; UKV_PARAM_PROFILE times the kernels.
  *   - What lives in host memory is checked during the call (service ids, lengths against the
  *     pool size, page ids of patches, alignment of offsets).  What lives in device memory is
  *     not: every page id the kernels find in page_table for a request's ceil(n*T/page_bytes)

@@ -286,6 +286,7 @@ extern "C" {
 // launch parameters, for later launches of the same plan.
 static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, size_t ws_bytes, void *stream,
                        bool with_append, ukv_plan *keep = nullptr) {
+    Trace trace(keep ? "ukv_plan_step(replan)" : with_append ? "ukv_decode_step" : "ukv_decode_attention");
     if (!p || !b) {
         set_error("null pool or batch");
         return UKV_EINVAL;
@@ -400,6 +401,14 @@ static int decode_impl(ukv_pool_t *p, const ukv_batch_t *b, void *workspace, siz
     a.n_spans_dev = nullptr;
     const uint32_t grid = decode_grid(n_spans, (uint32_t)p->tun.block_threads, p->kinds,
                                       p->tun.grid_is_first_round ? (uint32_t)p->tun.slots : 0);
+    trace.add("requests", b->n_requests);
+    trace.add("kv_bytes", plan.kv_bytes);
+    trace.add("sequences", plan.seqs.size());
+    trace.add("items", plan.items.size());
+    trace.add("spans", n_spans);
+    trace.add("workgroups", grid);
+    trace.add("partial_floats", plan.partial_floats);
+    trace.add("merged_by_second_launch", plan.reduce.size());
     if (keep) {
         keep->args = a;
         keep->grid = grid;
@@ -593,6 +602,12 @@ int ukv_plan_step(ukv_plan_t *pl, const ukv_plan_io_t *io_in, int advance, const
         return UKV_OK;
     }
     // The resident plan serves: one launch, the new page ids in its arguments.
+    Trace trace("ukv_plan_step");
+    trace.add("requests", n);
+    trace.add("new_pages", n_new_pages);
+    trace.add("grown_since_plan", pl->delta + grow);
+    trace.add("spans", pl->n_spans);
+    trace.add("workgroups", pl->grid);
     int rc = report_bad_tables(p, s);
     if (rc != UKV_OK)
         return rc;
@@ -638,6 +653,11 @@ int ukv_plan_step(ukv_plan_t *pl, const ukv_plan_io_t *io_in, int advance, const
 }
 
 int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
+    Trace trace("ukv_append");
+    if (b) {
+        trace.add("requests", b->n_requests);
+        trace.add("patches", b->n_patches);
+    }
     if (!p || !b) {
         set_error("null pool or batch");
         return UKV_EINVAL;
@@ -754,6 +774,9 @@ int ukv_append(ukv_pool_t *p, const ukv_batch_t *b, void *stream) {
 // that the contiguous arrays hold.
 static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *n_last, void *k_io,
                        void *v_io, const uint64_t *kv_off, void *stream) {
+    Trace trace(!to_pool ? "ukv_gather" : n_last ? "ukv_scatter_tokens" : "ukv_scatter");
+    if (b)
+        trace.add("requests", b->n_requests);
     if (!p || !b || !k_io || !v_io || !kv_off || !b->page_table) {
         set_error("null argument");
         return UKV_EINVAL;
@@ -804,6 +827,7 @@ static int copy_tokens(bool to_pool, ukv_pool_t *p, const ukv_batch_t *b, const 
     ukv_pool::Stage *st = nullptr;
     if ((rc = stage_acquire(p, total, &st)) != UKV_OK)
         return rc;
+    trace.add("chunks", chunks.size());
     unsigned char *h = (unsigned char *)st->host;
     std::memcpy(h, &p->classes, sizeof(ClassTable));
     std::memcpy(h + off_recs, chunks.data(), chunks.size() * sizeof(GatherRec));
@@ -886,6 +910,9 @@ size_t ukv_prefill_workspace_bytes_one_part(const ukv_pool_t *p, uint32_t n_requ
 
 int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q_len, void *workspace,
                           size_t ws_bytes, void *stream) {
+    Trace trace("ukv_prefill_attention");
+    if (b)
+        trace.add("requests", b->n_requests);
     if (!p || !b) {
         set_error("null pool or batch");
         return UKV_EINVAL;
@@ -1091,6 +1118,11 @@ int ukv_prefill_attention(ukv_pool_t *p, const ukv_batch_t *b, const uint32_t *q
     }
     p->tun.prefill_form_used = parts;
     p->tun.prefill_partials_used = n_parts;
+    trace.add("query_rows", total_rows);
+    trace.add("workgroups", n_recs);
+    trace.add("weight_parts", parts);
+    trace.add("partial_results", n_parts);
+    trace.add("flops", flops);
     const size_t total = rec_bytes + merge_bytes + (parts == 1 ? chunk_bytes : 0); // what is uploaded
     const size_t v16_start = total;
     const size_t partial_start = v16_start + (parts == 1 ? (size_t)v16_bytes : 0);

@@ -324,6 +324,26 @@ struct Tunables {
 
 void set_error(const std::string &msg);
 
+// UKV_TRACE=1 in the environment: every compute call leaves one line on stderr when it returns --
+//   ukv_trace call=<entry point> t_us=<host time since the first traced call> host_us=<time spent in the call>
+//   status=ok|error key=value ...
+// with the call's work-list figures (requests, KV bytes, spans, items, workgroups, ...).  Host side only; nothing is
+// measured on the device (UKV_PARAM_PROFILE does that).  The line is built in a fixed buffer: tracing allocates nothing.
+struct Trace {
+    explicit Trace(const char *call);
+    ~Trace();
+    void add(const char *key, uint64_t value);
+    Trace(const Trace &) = delete;
+    Trace &operator=(const Trace &) = delete;
+
+  private:
+    const char *call_;
+    bool on_;
+    uint64_t t0_ns_, errors_at_start_;
+    char kv_[384];
+    size_t len_ = 0;
+};
+
 } // namespace ukv
 
 // ---- the opaque pool object ----

@@ -1,6 +1,10 @@
 // Unified block manager: pool validation, per-service derived constants, LIFO free list.
 // (Section 4.4 "Unified KV Cache" and the unified block manager of section 5.)  Host only.
+#include <algorithm>
+#include <chrono>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -10,7 +14,45 @@ namespace ukv {
 
 static thread_local std::string g_last_error;
 
-void set_error(const std::string &msg) { g_last_error = msg; }
+static thread_local uint64_t g_errors = 0; // set_error calls of this thread (a traced call compares before and after)
+
+void set_error(const std::string &msg) {
+    g_last_error = msg;
+    ++g_errors;
+}
+
+static uint64_t now_ns() {
+    return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+               std::chrono::steady_clock::now().time_since_epoch())
+        .count();
+}
+static bool trace_enabled() {
+    static const bool on = [] {
+        const char *e = std::getenv("UKV_TRACE");
+        return e != nullptr && e[0] != '\0' && e[0] != '0';
+    }();
+    return on;
+}
+Trace::Trace(const char *call) : call_(call), on_(trace_enabled()), t0_ns_(0), errors_at_start_(g_errors) {
+    kv_[0] = '\0';
+    if (on_)
+        t0_ns_ = now_ns();
+}
+void Trace::add(const char *key, uint64_t value) {
+    if (!on_ || len_ >= sizeof(kv_) - 1)
+        return;
+    const int w = std::snprintf(kv_ + len_, sizeof(kv_) - len_, " %s=%llu", key, (unsigned long long)value);
+    if (w > 0)
+        len_ = std::min(sizeof(kv_) - 1, len_ + (size_t)w);
+}
+Trace::~Trace() {
+    if (!on_)
+        return;
+    static const uint64_t first_ns = t0_ns_; // the first traced call of the process
+    const uint64_t t1 = now_ns();
+    std::fprintf(stderr, "ukv_trace call=%s t_us=%.1f host_us=%.1f status=%s%s\n", call_, (t0_ns_ - first_ns) * 1e-3,
+                 (t1 - t0_ns_) * 1e-3, g_errors == errors_at_start_ ? "ok" : "error", kv_);
+}
 
 static int fail(int code, const std::string &msg) {
     set_error(msg);

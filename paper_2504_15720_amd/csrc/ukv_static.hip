@@ -298,6 +298,9 @@ static int scratch_of_current_device(unsigned char **out, int *cus) {
 using namespace ukv;
 
 extern "C" int ukv_decode_attention_static(ukv_pool_t *p, const ukv_device_batch_t *b, void *stream) {
+    Trace trace("ukv_decode_attention_static"); // (a fixed buffer and stderr: nothing is allocated)
+    if (b)
+        trace.add("requests", b->n_requests);
     if (!p || !b) {
         set_error("null pool or batch");
         return UKV_EINVAL;

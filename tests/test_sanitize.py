@@ -35,6 +35,19 @@ def test_library_host_code_under_sanitizers(tmp_path):
           "-I" + CSRC, "-Wno-unused-result", "-Wno-unknown-attributes"] + FLAGS + srcs + ["-o", exe])
     out = _run([exe, "40"], env=ENV, timeout=300)
     assert "host driver ok" in out and "ERROR" not in out and "runtime error" not in out, out[-2000:]
+    assert "ukv_trace" not in out
+    # UKV_TRACE=1: one line per compute call, with the call's work-list figures; failed calls say so
+    out = _run([exe, "3"], env=dict(ENV, UKV_TRACE="1"), timeout=300)
+    assert "host driver ok" in out and "ERROR" not in out and "runtime error" not in out, out[-2000:]
+    lines = [l for l in out.splitlines() if l.startswith("ukv_trace ")]
+    calls = {l.split()[1] for l in lines}
+    for call in ("call=ukv_decode_attention", "call=ukv_decode_step", "call=ukv_plan_step", "call=ukv_append",
+                 "call=ukv_gather", "call=ukv_scatter", "call=ukv_prefill_attention"):
+        assert call in calls, (call, sorted(calls))
+    step = next(l for l in lines if "call=ukv_decode_step" in l and "status=ok" in l)
+    for key in ("t_us=", "host_us=", "requests=", "kv_bytes=", "spans=", "items=", "workgroups="):
+        assert key in step, step
+    assert any("status=error" in l for l in lines), "the driver's rejected calls should be traced as errors"
 
 
 def test_oracle_under_sanitizers(tmp_path):
